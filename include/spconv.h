@@ -1,0 +1,203 @@
+/*
+ * spconv.h - C ABI of the MI355X (gfx950) sparse 3-D convolution library.
+ *
+ * The library computes the sparse convolution of the paper's Equation 1
+ * (Section 2.1),
+ *
+ *     x_out[n] = sum over delta in Delta^3(K), sum over j of
+ *                1[p_j = s*q_n + delta] * (x_in[j] . W[delta]),
+ *
+ * in the implicit-GEMM dataflow (Sections 2.2.3, 3.1): an output-stationary
+ * kernel map M[n_out][K^3] is built first (M[n][k] = input row that is the
+ * k-th neighbour of output n, or -1), then the feature kernels gather input
+ * rows through M on their way into LDS and multiply them by the weight slice
+ * of the offset on the matrix cores, accumulating in fp32 registers.  Output
+ * rows can be visited in bitmask-sorted order and the loop over offsets can be
+ * cut into several separately sorted splits whose partial sums are added by a
+ * reduction kernel (Sections 2.2.3 and 4.1).
+ *
+ * Conventions (the paper gives only the set Delta^3(K); these are fixed here):
+ *   - a coordinate row is (b, x, y, z), int32; b is the batch index, never
+ *     offset or strided; x, y, z in [-32768, 32767], b in [0, 65534];
+ *   - offset index k = ((dx+r)*K + (dy+r))*K + (dz+r), r = (K-1)/2, i.e. x
+ *     slowest, z fastest; K is 1 or 3; bit k of a neighbour bitmask is 1u<<k;
+ *   - output q reads the input at s*q + delta with W[delta] (no kernel flip);
+ *   - stride 1: P_out = P_in in input order; stride s > 1: P_out = unique
+ *     floor(p / s), sorted ascending lexicographically in (b, x, y, z);
+ *   - transposed: the caller passes the FINE set (the outputs of the
+ *     transposed convolution); its inputs are the coarse set P_out(fine, s),
+ *     in that sorted order, and y[j] = sum over (i, delta) with
+ *     fine_j = s*coarse_i + delta of x[i] . W[delta].
+ *
+ * Memory: every pointer named "device" is a device pointer owned by the
+ * caller (the library never frees caller memory); tensors are row-major and
+ * contiguous, feature rows 16-byte aligned.  The opaque spconv_kmap owns all
+ * of its buffers (hash table, maps, masks, permutations, cached reordered
+ * maps, scratch) and releases them in spconv_kmap_destroy.  A kmap caches
+ * derived data on first use, so concurrent calls on ONE kmap from several
+ * host threads or several streams are not supported.
+ *
+ * Streams: `stream` is a hipStream_t passed as void* (NULL = the null
+ * stream).  Calls are asynchronous with respect to the host except where
+ * stated.  All work of one kmap must be issued on one stream (or the caller
+ * orders the streams).
+ *
+ * Errors: every function returns 0 on success or a negative spconv_status.
+ * Nothing is written to outputs on SPCONV_EINVAL / SPCONV_ESHAPE.
+ */
+#ifndef SPCONV_H
+#define SPCONV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SPCONV_API __attribute__((visibility("default")))
+
+typedef enum spconv_status {
+  SPCONV_OK = 0,
+  SPCONV_EINVAL = -1,  /* null pointer, negative size, unsupported K / stride / dtype / channels / config */
+  SPCONV_ERANGE = -2,  /* a coordinate lies outside the packable range */
+  SPCONV_EDUP = -3,    /* two input rows carry the same coordinate (Section 2 assumes Unique was applied) */
+  SPCONV_ENOMEM = -4,  /* device or host allocation failed */
+  SPCONV_ESHAPE = -5,  /* channel counts or row counts do not fit the kmap */
+  SPCONV_EHIP = -6     /* a HIP call failed; see spconv_last_hip_error() */
+} spconv_status;
+
+typedef enum spconv_dtype { SPCONV_F32 = 0, SPCONV_F16 = 1, SPCONV_BF16 = 2 } spconv_dtype;
+
+typedef enum spconv_op { SPCONV_OP_FWD = 0, SPCONV_OP_DGRAD = 1, SPCONV_OP_WGRAD = 2 } spconv_op;
+
+typedef struct spconv_kmap spconv_kmap; /* opaque */
+
+/* Dataflow parameters (the design space of Section 4.1).  Zero-initialise for
+ * the defaults.
+ *   n_split     0: unsorted implicit GEMM, rows in map order, one pass.
+ *               s >= 1 (at most 4): the K^3 offsets are cut into s contiguous
+ *               ranges [floor(i*V/s), floor((i+1)*V/s)); in each range the
+ *               rows are visited in ascending order of that range's bitmask
+ *               bits (stable), and for s > 1 the fp32 partial sums of the
+ *               ranges are added by a reduction kernel.
+ *   tile_m      output rows per workgroup: 64, 128 or 256 (0 = 128).
+ *   tile_n      output channels per workgroup: 32, 64 or 128 (0 = chosen from C_out).
+ *   wgrad_pairs target number of (output,input) pairs per wgrad workgroup
+ *               (0 = chosen from the pair count); ignored by fwd / dgrad.
+ */
+typedef struct spconv_config {
+  int32_t n_split;
+  int32_t tile_m;
+  int32_t tile_n;
+  int32_t wgrad_pairs;
+  int32_t reserved[4];
+} spconv_config;
+
+/* Kernel-map construction ("mapping operations", Sections 3.1, 4.2, 6.2).
+ *   coords      device, int32 [N][4] = (b, x, y, z), unique rows.
+ *   N           number of rows, >= 0 (N = 0 gives an empty kmap).
+ *   K           kernel size, 1 or 3.
+ *   stride      >= 1 (stride 1 with transposed = 0 is the submanifold case).
+ *   transposed  0: coords are P_in.  1: coords are the fine output set.
+ *   out         receives a new kmap; release with spconv_kmap_destroy.
+ * Synchronises `stream` once (to read the error flags and, for stride > 1,
+ * the number of coarse points).  Errors: EINVAL, ERANGE, EDUP, ENOMEM, EHIP;
+ * on error *out is NULL. */
+SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int stride, int transposed,
+                      void* stream, spconv_kmap** out);
+
+/* Row counts of the two sides of the map and the number of present pairs
+ * sum_k |M_k| (the "effective MACs" of Section 2.2.3 in units of
+ * C_in*C_out).  Any pointer may be NULL.  Asking for n_pairs the first time
+ * runs a small reduction on the kmap's build stream and synchronises it. */
+SPCONV_API int spconv_kmap_sizes(const spconv_kmap* km, int64_t* n_in, int64_t* n_out, int64_t* n_pairs);
+
+/* Copies P_out (int32 [n_out][4]) to dst (device). */
+SPCONV_API int spconv_kmap_out_coords(const spconv_kmap* km, int32_t* dst, void* stream);
+
+/* Copies P_in (int32 [n_in][4]) to dst (device): the caller's rows for
+ * transposed = 0, the sorted coarse set for transposed = 1. */
+SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* stream);
+
+/* Copies the canonical map M (int32 [n_out][K^3], -1 = absent) to dst (device). */
+SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* stream);
+
+/* Copies the neighbour bitmasks (uint32 [n_out], Section 2.2.3) to dst (device). */
+SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, void* stream);
+
+/* Builds (and caches in the kmap) everything op needs under cfg before the
+ * first compute call: the input-side map for dgrad of strided / transposed
+ * maps, per-split bitmask argsort, reordered and padded maps and per-tile
+ * masks (Sections 2.2.3, 3.2, 4.1), the offset-major map and work list of
+ * wgrad.  The compute calls do this themselves on first use; calling it
+ * explicitly lets the mapping cost be timed apart from the kernels
+ * (Section 6.1 separates them the same way).  May synchronise the stream. */
+SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_config* cfg_or_null, void* stream);
+
+/* Drops every cached plan (not the map itself), so that mapping can be timed again. */
+SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km);
+
+/* Permutation of split `split` of the cached plan of (op, cfg): int32
+ * [n_rows] with row r of the sorted order = original row perm[r] (identity
+ * for n_split = 0).  For tests of the sort invariants. */
+SPCONV_API int spconv_kmap_export_perm(spconv_kmap* km, spconv_op op, const spconv_config* cfg_or_null,
+                            int split, int32_t* dst, void* stream);
+
+/* Executed and effective MAC units (units of C_in*C_out MACs) of op under cfg
+ * in this library's lock-step model: a block of 16 consecutive rows of the
+ * visiting order (one MFMA block) pays for offset k whenever one of them has
+ * neighbour k (the quantity plotted in Section 4.1).  Synchronises the stream. */
+SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv_config* cfg_or_null,
+                          int64_t* executed, int64_t* effective, void* stream);
+
+SPCONV_API void spconv_kmap_destroy(spconv_kmap* km);
+
+/* Forward, Equation 1:  out[n] = sum_k feats[M[n][k]] . W[k].
+ *   feats   device [n_in][C_in]   weights device [K^3][C_in][C_out]
+ *   out     device [n_out][C_out], fully overwritten.
+ * dtype applies to feats, weights and out; accumulation is fp32 with one
+ * rounding (to nearest even) at the end.  C_in and C_out must be multiples
+ * of 8 (F16/BF16) or 4 (F32).  km is not const because plans are cached. */
+SPCONV_API int spconv_fwd(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out,
+               spconv_dtype dtype, const spconv_config* cfg_or_null, void* out, void* stream);
+
+/* Input gradient of Equation 1 (the dgrad kernel of Section 4.2):
+ *   din[j] = sum over (n, k) with M[n][k] = j of dout[n] . W[k]^T.
+ *   dout device [n_out][C_out]   weights as in spconv_fwd
+ *   din  device [n_in][C_in], fully overwritten. */
+SPCONV_API int spconv_dgrad(const void* dout, const void* weights, spconv_kmap* km, int C_in, int C_out,
+                 spconv_dtype dtype, const spconv_config* cfg_or_null, void* din, void* stream);
+
+/* Weight gradient of Equation 1 (the wgrad kernel of Sections 4.2, 6.2):
+ *   dweights[k] = sum over n with M[n][k] >= 0 of feats[M[n][k]]^T . dout[n].
+ *   dweights device fp32 [K^3][C_in][C_out] whatever dtype is, fully overwritten. */
+SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km, int C_in, int C_out,
+                 spconv_dtype dtype, const spconv_config* cfg_or_null, float* dweights, void* stream);
+
+/* Picks the configuration of the design space of Section 4.1 (number of
+ * splits, sorted or not, tile sizes) with the lowest measured time for op on
+ * this kmap and these channel counts, where time = kernel time + mapping time
+ * / layers_sharing_kmap (layers that use the same maps form a group and share
+ * the mapping cost, Section 4.2).  Blocking: allocates scratch tensors, runs
+ * and times every candidate on `stream`.  best receives the winner;
+ * best_us (may be NULL) its time in microseconds. */
+SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype, spconv_op op,
+                int layers_sharing_kmap, spconv_config* best, float* best_us, void* stream);
+
+/* Device allocations made by the library go through these callbacks when set
+ * (so that a framework's caching allocator can back them); NULL restores
+ * hipMalloc / hipFree. */
+SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* user), void (*free_)(void* ptr, void* user),
+                         void* user);
+
+SPCONV_API const char* spconv_strerror(int status);
+/* Text of the last failing HIP call on this host thread ("" if none). */
+SPCONV_API const char* spconv_last_hip_error(void);
+/* Library version as major*10000 + minor*100 + patch. */
+SPCONV_API int spconv_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SPCONV_H */

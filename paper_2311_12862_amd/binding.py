@@ -1,0 +1,249 @@
+"""ctypes binding of include/spconv.h: same names, argument marshalling only.
+
+torch is used for device memory and the current HIP stream; every step of the
+computation runs inside libspconv.so.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+
+import torch
+
+OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
+_DTYPES = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
+
+
+class SpconvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        lib = load_library()
+        msg = lib.spconv_strerror(status).decode()
+        hip = lib.spconv_last_hip_error().decode()
+        super().__init__(f"{where}: {msg} ({status})" + (f" [{hip}]" if status == -6 and hip else ""))
+        self.status = status
+
+
+class Config(C.Structure):
+    """Mirror of spconv_config (zero = library defaults)."""
+    _fields_ = [("n_split", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
+                ("wgrad_pairs", C.c_int32), ("reserved", C.c_int32 * 4)]
+
+    def __repr__(self):
+        return (f"Config(n_split={self.n_split}, tile_m={self.tile_m}, tile_n={self.tile_n}, "
+                f"wgrad_pairs={self.wgrad_pairs})")
+
+
+_LIB = None
+
+
+def lib_path() -> str:
+    return os.path.join(os.path.dirname(os.path.abspath(__file__)), "libspconv.so")
+
+
+def load_library():
+    """Loads libspconv.so and declares every prototype of include/spconv.h."""
+    global _LIB
+    if _LIB is not None:
+        return _LIB
+    path = lib_path()
+    if not os.path.exists(path):
+        raise ImportError(f"{path} is missing: build it with `python -m paper_2311_12862_amd.build` "
+                          "(there is no fallback implementation)")
+    lib = C.CDLL(path)
+    vp, i32, i64 = C.c_void_p, C.c_int, C.c_int64
+    cfgp = C.POINTER(Config)
+    protos = {
+        "spconv_build_kmap": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
+        "spconv_kmap_sizes": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]),
+        "spconv_kmap_out_coords": (i32, [vp, vp, vp]),
+        "spconv_kmap_in_coords": (i32, [vp, vp, vp]),
+        "spconv_kmap_export": (i32, [vp, vp, vp]),
+        "spconv_kmap_export_mask": (i32, [vp, vp, vp]),
+        "spconv_kmap_prepare": (i32, [vp, i32, cfgp, vp]),
+        "spconv_kmap_drop_plans": (i32, [vp]),
+        "spconv_kmap_export_perm": (i32, [vp, i32, cfgp, i32, vp, vp]),
+        "spconv_kmap_mac_units": (i32, [vp, i32, cfgp, C.POINTER(i64), C.POINTER(i64), vp]),
+        "spconv_kmap_destroy": (None, [vp]),
+        "spconv_fwd": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
+        "spconv_dgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
+        "spconv_wgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
+        "spconv_tune": (i32, [vp, i32, i32, i32, i32, i32, cfgp, C.POINTER(C.c_float), vp]),
+        "spconv_set_allocator": (i32, [vp, vp, vp]),
+        "spconv_strerror": (C.c_char_p, [i32]),
+        "spconv_last_hip_error": (C.c_char_p, []),
+        "spconv_version": (i32, []),
+    }
+    for name, (res, args) in protos.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _LIB = lib
+    return lib
+
+
+def _check(status: int, where: str):
+    if status != 0:
+        raise SpconvError(status, where)
+
+
+def _stream(stream):
+    if stream is None:
+        return torch.cuda.current_stream().cuda_stream
+    return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)
+
+
+def _cfg(cfg):
+    return None if cfg is None else C.byref(cfg)
+
+
+def _ptr(t):
+    return None if t is None or t.numel() == 0 else t.data_ptr()
+
+
+def _dev_tensor(t, dtype=None):
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("expected a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"expected dtype {dtype}, got {t.dtype}")
+    return t
+
+
+class KMap:
+    """Owner of an spconv_kmap handle."""
+
+    def __init__(self, handle, K):
+        self._h = handle
+        self.K = K
+        self.V = K ** 3
+        n_in, n_out = C.c_int64(), C.c_int64()
+        _check(load_library().spconv_kmap_sizes(self._h, C.byref(n_in), C.byref(n_out), None), "spconv_kmap_sizes")
+        self.n_in, self.n_out = n_in.value, n_out.value
+
+    @property
+    def handle(self):
+        if self._h is None:
+            raise ValueError("kmap was destroyed")
+        return self._h
+
+    def n_pairs(self) -> int:
+        v = C.c_int64()
+        _check(load_library().spconv_kmap_sizes(self.handle, None, None, C.byref(v)), "spconv_kmap_sizes")
+        return v.value
+
+    def out_coords(self, stream=None):
+        dst = torch.empty((self.n_out, 4), dtype=torch.int32, device="cuda")
+        _check(load_library().spconv_kmap_out_coords(self.handle, _ptr(dst), _stream(stream)), "spconv_kmap_out_coords")
+        return dst
+
+    def in_coords(self, stream=None):
+        dst = torch.empty((self.n_in, 4), dtype=torch.int32, device="cuda")
+        _check(load_library().spconv_kmap_in_coords(self.handle, _ptr(dst), _stream(stream)), "spconv_kmap_in_coords")
+        return dst
+
+    def export(self, stream=None):
+        dst = torch.empty((self.n_out, self.V), dtype=torch.int32, device="cuda")
+        _check(load_library().spconv_kmap_export(self.handle, _ptr(dst), _stream(stream)), "spconv_kmap_export")
+        return dst
+
+    def export_mask(self, stream=None):
+        dst = torch.empty((self.n_out,), dtype=torch.int32, device="cuda")  # bit patterns of uint32
+        _check(load_library().spconv_kmap_export_mask(self.handle, _ptr(dst), _stream(stream)), "spconv_kmap_export_mask")
+        return dst
+
+    def prepare(self, op, cfg=None, stream=None):
+        _check(load_library().spconv_kmap_prepare(self.handle, op, _cfg(cfg), _stream(stream)), "spconv_kmap_prepare")
+
+    def drop_plans(self):
+        _check(load_library().spconv_kmap_drop_plans(self.handle), "spconv_kmap_drop_plans")
+
+    def export_perm(self, op, cfg, split, stream=None):
+        rows = self.n_out if op == OP_FWD else self.n_in
+        dst = torch.empty((rows,), dtype=torch.int32, device="cuda")
+        _check(load_library().spconv_kmap_export_perm(self.handle, op, _cfg(cfg), split, _ptr(dst), _stream(stream)),
+               "spconv_kmap_export_perm")
+        return dst
+
+    def mac_units(self, op, cfg=None, stream=None):
+        ex, ef = C.c_int64(), C.c_int64()
+        _check(load_library().spconv_kmap_mac_units(self.handle, op, _cfg(cfg), C.byref(ex), C.byref(ef),
+                                                    _stream(stream)), "spconv_kmap_mac_units")
+        return ex.value, ef.value
+
+    def destroy(self):
+        if self._h is not None:
+            load_library().spconv_kmap_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def build_kmap(coords, K: int = 3, stride: int = 1, transposed: bool = False, stream=None) -> KMap:
+    """spconv_build_kmap: coords is an int32 device tensor [N, 4] = (b, x, y, z)."""
+    _dev_tensor(coords, torch.int32)
+    if coords.ndim != 2 or coords.shape[1] != 4:
+        raise ValueError("coords must be [N, 4]")
+    h = C.c_void_p()
+    _check(load_library().spconv_build_kmap(_ptr(coords), coords.shape[0], K, stride, int(transposed),
+                                            _stream(stream), C.byref(h)), "spconv_build_kmap")
+    return KMap(h, K)
+
+
+def _conv_args(a, w_or_b, kmap, rows_a):
+    _dev_tensor(a)
+    if a.dtype not in _DTYPES:
+        raise ValueError(f"unsupported dtype {a.dtype}")
+    if a.ndim != 2 or a.shape[0] != rows_a:
+        raise SpconvError(-5, f"feature rows {tuple(a.shape)} do not fit the kmap ({rows_a} rows)")
+    _dev_tensor(w_or_b, a.dtype)
+    return _DTYPES[a.dtype]
+
+
+def fwd(feats, weights, kmap: KMap, cfg: Config | None = None, out=None, stream=None):
+    """spconv_fwd: feats [n_in, C_in], weights [K^3, C_in, C_out] -> out [n_out, C_out]."""
+    dt = _conv_args(feats, weights, kmap, kmap.n_in)
+    V, c_in, c_out = weights.shape
+    if V != kmap.V or c_in != feats.shape[1]:
+        raise SpconvError(-5, "weights shape does not fit")
+    if out is None:
+        out = torch.empty((kmap.n_out, c_out), dtype=feats.dtype, device=feats.device)
+    _check(load_library().spconv_fwd(_ptr(feats), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
+                                     _ptr(out), _stream(stream)), "spconv_fwd")
+    return out
+
+
+def dgrad(dout, weights, kmap: KMap, cfg: Config | None = None, out=None, stream=None):
+    """spconv_dgrad: dout [n_out, C_out], weights [K^3, C_in, C_out] -> din [n_in, C_in]."""
+    dt = _conv_args(dout, weights, kmap, kmap.n_out)
+    V, c_in, c_out = weights.shape
+    if V != kmap.V or c_out != dout.shape[1]:
+        raise SpconvError(-5, "weights shape does not fit")
+    if out is None:
+        out = torch.empty((kmap.n_in, c_in), dtype=dout.dtype, device=dout.device)
+    _check(load_library().spconv_dgrad(_ptr(dout), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
+                                       _ptr(out), _stream(stream)), "spconv_dgrad")
+    return out
+
+
+def wgrad(feats, dout, kmap: KMap, cfg: Config | None = None, out=None, stream=None):
+    """spconv_wgrad: feats [n_in, C_in], dout [n_out, C_out] -> dweights fp32 [K^3, C_in, C_out]."""
+    dt = _conv_args(feats, dout, kmap, kmap.n_in)
+    if dout.ndim != 2 or dout.shape[0] != kmap.n_out:
+        raise SpconvError(-5, "dout rows do not fit the kmap")
+    c_in, c_out = feats.shape[1], dout.shape[1]
+    if out is None:
+        out = torch.empty((kmap.V, c_in, c_out), dtype=torch.float32, device=feats.device)
+    _check(load_library().spconv_wgrad(_ptr(feats), _ptr(dout), kmap.handle, c_in, c_out, dt, _cfg(cfg),
+                                       _ptr(out), _stream(stream)), "spconv_wgrad")
+    return out
+
+
+def tune(kmap: KMap, c_in: int, c_out: int, dtype, op: int, layers_sharing_kmap: int = 1, stream=None):
+    """spconv_tune: returns (Config, microseconds)."""
+    best, us = Config(), C.c_float()
+    _check(load_library().spconv_tune(kmap.handle, c_in, c_out, _DTYPES[dtype], op, layers_sharing_kmap,
+                                      C.byref(best), C.byref(us), _stream(stream)), "spconv_tune")
+    return best, us.value

@@ -1,0 +1,158 @@
+// Shared declarations of the library's translation units (host side).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include <stddef.h>
+#include <map>
+#include <memory>
+#include <vector>
+
+#include "spconv.h"
+
+namespace spc {
+
+constexpr int kMaxSplit = 4;
+constexpr int kRowPad = 256;  // map rows are padded to a multiple of the largest tile_m
+constexpr int kWave = 64;
+
+int hip_fail(hipError_t e, const char* what, const char* file, int line);
+#define SPC_HIP(expr)                                                        \
+  do {                                                                       \
+    hipError_t e__ = (expr);                                                 \
+    if (e__ != hipSuccess) return ::spc::hip_fail(e__, #expr, __FILE__, __LINE__); \
+  } while (0)
+#define SPC_TRY(expr)               \
+  do {                              \
+    int s__ = (expr);               \
+    if (s__ != SPCONV_OK) return s__; \
+  } while (0)
+#define SPC_LAUNCH_CHECK() SPC_HIP(hipGetLastError())
+
+void* dev_alloc(size_t bytes);
+void dev_free(void* p);
+
+// Owning device buffer (grow-only when used as scratch).
+struct DevBuf {
+  void* p = nullptr;
+  size_t bytes = 0;
+  DevBuf() = default;
+  DevBuf(const DevBuf&) = delete;
+  DevBuf& operator=(const DevBuf&) = delete;
+  ~DevBuf() { release(); }
+  void release() {
+    if (p) dev_free(p);
+    p = nullptr;
+    bytes = 0;
+  }
+  int alloc(size_t n) {  // exact size, contents undefined
+    release();
+    if (n == 0) n = 16;
+    p = dev_alloc(n);
+    if (!p) return SPCONV_ENOMEM;
+    bytes = n;
+    return SPCONV_OK;
+  }
+  int reserve(size_t n) { return (n <= bytes && p) ? SPCONV_OK : alloc(n); }
+  template <typename T> T* as() const { return reinterpret_cast<T*>(p); }
+};
+
+inline int64_t round_up(int64_t a, int64_t b) { return (a + b - 1) / b * b; }
+inline int64_t ceil_div(int64_t a, int64_t b) { return (a + b - 1) / b; }
+
+// Plan of the implicit-GEMM kernels for one side of the map (output rows for
+// fwd, input rows for dgrad), one split count and one tile height.
+struct IgemmPlan {
+  int n_split = 0;  // 0 = unsorted
+  int tile_m = 128;
+  int parts = 1;  // max(1, n_split)
+  int64_t rows = 0, rows_pad = 0, n_tiles = 0;
+  int lo[kMaxSplit] = {0}, width[kMaxSplit] = {0};
+  size_t map_off[kMaxSplit] = {0};  // element offsets into maps
+  DevBuf maps;      // reordered maps, part i: int32 [rows_pad][width[i]]  (unused when n_split == 0)
+  DevBuf perm;      // int32 [parts][rows_pad]                              (unused when n_split == 0)
+  DevBuf tilemask;  // uint32 [parts][n_tiles] bits relative to lo[i]
+};
+
+struct WgradItem {
+  int32_t k, row_begin, row_end, slot;  // slot: index of the partial tile this item writes
+};
+
+struct WgradPlan {
+  int64_t target_pairs = 0;
+  DevBuf map_k;   // int32 [V][rows_pad]  offset-major copy of M
+  DevBuf items;   // WgradItem [n_items]
+  DevBuf seg;     // int32 [V+1]: items of offset k are seg[k]..seg[k+1]
+  int n_items = 0;
+  int64_t counts[32] = {0};
+};
+
+struct SideMap {      // one output-stationary table: rows x V
+  int64_t rows = 0, rows_pad = 0;
+  DevBuf map;         // int32 [rows_pad][V]
+  DevBuf mask;        // uint32 [rows_pad]
+  bool ready = false;
+  std::map<std::pair<int, int>, std::unique_ptr<IgemmPlan>> plans;  // (n_split, tile_m)
+};
+
+}  // namespace spc
+
+struct spconv_kmap {
+  int K = 3, V = 27, stride = 1, transposed = 0;
+  int64_t n_in = 0, n_out = 0, n_pairs = -1;
+  hipStream_t build_stream = nullptr;
+  spc::DevBuf in_coords, out_coords;
+  spc::SideMap out_side;  // M: rows = n_out, entries index input rows
+  spc::SideMap in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)
+  std::map<int64_t, std::unique_ptr<spc::WgradPlan>> wplans;  // by target_pairs
+  spc::DevBuf scratch;    // split partial sums / wgrad partial tiles
+  bool submanifold() const { return stride == 1 && !transposed; }
+};
+
+namespace spc {
+
+// ---- kmap.hip
+int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, hipStream_t st,
+               spconv_kmap** out);
+int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
+int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);
+
+// ---- sort.hip
+// Stable LSD radix sort of n (key, value) pairs on key bits [0, key_bits).
+// keys/vals are ping-pong buffers of n elements each; *in_b tells where the
+// result ended up (0: buffer a, 1: buffer b).  hist must hold
+// sort_hist_elems(n) uint32.
+size_t sort_hist_elems(int64_t n);
+int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* val_b, int64_t n,
+                   int key_bits, uint32_t* hist, hipStream_t st, int* in_b);
+// Keys only, 64-bit, on the digit positions whose bits are set in `varying`.
+int radix_sort_u64(uint64_t* key_a, uint64_t* key_b, int64_t n, uint64_t varying, uint32_t* hist,
+                   hipStream_t st, int* in_b);
+
+// ---- plan.hip
+int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out);
+int plan_mac_units(spconv_kmap* km, SideMap& side, IgemmPlan* plan, int group_rows, hipStream_t st,
+                   int64_t* executed);
+int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan** out);
+
+// ---- igemm.hip
+struct IgemmArgs {
+  const void* feats;    // [rows_src][c_red]
+  const void* weights;  // [V][C_in][C_out] (always the forward layout)
+  void* out;            // [rows][c_out_eff] in dtype, or nullptr when partial sums are used
+  float* partial;       // [parts][rows][c_out_eff] fp32 when parts > 1
+  int C_in, C_out;      // of the layer (forward orientation)
+  int dgrad;            // 0: reduce over C_in, produce C_out.  1: reduce over C_out, produce C_in
+  int mirror;           // weight slice of map column k is V-1-k (dgrad on the submanifold map itself)
+  spconv_dtype dtype;
+  int tile_n;           // 0 = auto
+};
+int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
+              hipStream_t st);
+int split_reduce(const float* partial, int parts, int64_t rows, int c, spconv_dtype dtype, void* out,
+                 hipStream_t st);
+
+// ---- wgrad.hip
+int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const void* dout, int C_in,
+              int C_out, spconv_dtype dtype, float* dweights, hipStream_t st);
+
+}  // namespace spc

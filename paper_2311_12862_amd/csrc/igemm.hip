@@ -1,0 +1,488 @@
+// Implicit-GEMM sparse convolution kernels (Sections 2.2.3, 3.1, 3.2, 4.1):
+// forward and input-gradient.
+//
+// One workgroup owns BM consecutive rows of the (possibly bitmask-sorted)
+// output-stationary map and BN output channels.  The tile's map slab is copied
+// to LDS once (the addressing that Section 3.2 hoists out of the inner loop),
+// the loop over kernel offsets visits only offsets whose bit is set in the
+// tile's mask, and every 16-row MFMA block of a wave skips offsets none of its
+// rows has (the lock-step unit of Section 2.2.3 is a 16-row block here, not a
+// 32-thread warp).  Gathered feature rows and the weight slice are staged
+// through double-buffered LDS; global loads for step i+1 are in flight while
+// step i runs on the matrix cores.  Rows of absent neighbours are zero-filled
+// by predicated loads, and the map is padded to whole tiles so that no map
+// access needs a bounds check (the padding of Section 3.2).
+#include "common.h"
+
+namespace spc {
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+struct IgemmParams {
+  const void* feats;
+  const void* weights;
+  void* out;
+  float* partial;
+  const int* map[kMaxSplit];
+  const int* perm[kMaxSplit];
+  const unsigned* tilemask[kMaxSplit];
+  int lo[kMaxSplit], width[kMaxSplit];
+  long long rows;
+  int parts, V;
+  int c_red, c_out;  // reduced / produced channel counts
+  int C_in, C_out;   // of the layer
+  int dgrad, mirror;
+};
+
+template <typename T> struct Mfma;
+template <> struct Mfma<_Float16> {
+  typedef f16x8 vec;
+  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  }
+};
+template <> struct Mfma<__bf16> {
+  typedef bf16x8 vec;
+  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  }
+};
+
+template <int BM, int BN, int KC> struct IgemmSmem {
+  static constexpr int LDA = KC + 8;  // row pitch in 2-byte elements (+16 B against bank conflicts)
+  static constexpr size_t a_bytes = (size_t)2 * BM * LDA * 2;
+  static constexpr size_t b_bytes = (size_t)2 * BN * LDA * 2;
+  static constexpr size_t map_bytes = (size_t)BM * 27 * 4;
+  static constexpr size_t perm_bytes = (size_t)BM * 4;
+  static constexpr size_t total = a_bytes + b_bytes + map_bytes + perm_bytes;
+};
+
+template <typename T, int BM, int BN, int KC>
+__global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
+  typedef IgemmSmem<BM, BN, KC> S;
+  typedef typename Mfma<T>::vec vec8;
+  constexpr int LDA = S::LDA;
+  constexpr int WM = BM / 4;    // rows per wave
+  constexpr int MB = WM / 16;   // 16-row MFMA blocks per wave
+  constexpr int NB = BN / 16;   // 16-column MFMA blocks
+  constexpr int SEG = KC / 8;   // 16-byte segments per staged row
+  constexpr int A_RPP = 256 / SEG;
+  constexpr int A_PASSES = BM / A_RPP;
+  constexpr int B_PASSES = (KC * BN / 8 + 255) / 256;
+  constexpr int BF_RPP = 2048 / BN;  // forward: reduction rows covered per pass
+
+  extern __shared__ __align__(16) unsigned char smem[];
+  unsigned short* As = reinterpret_cast<unsigned short*>(smem);
+  unsigned short* Bs = reinterpret_cast<unsigned short*>(smem + S::a_bytes);
+  int* mapS = reinterpret_cast<int*>(smem + S::a_bytes + S::b_bytes);
+  int* permS = reinterpret_cast<int*>(smem + S::a_bytes + S::b_bytes + S::map_bytes);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int part = blockIdx.z;
+  const long long tile = blockIdx.x;
+  const int n0 = blockIdx.y * BN;
+  const int width = p.width[part], lo = p.lo[part];
+  const long long row0 = tile * BM;
+  const unsigned tmask = p.tilemask[part][tile];
+  const unsigned short* feats = reinterpret_cast<const unsigned short*>(p.feats);
+  const unsigned short* wts = reinterpret_cast<const unsigned short*>(p.weights);
+  const int c_red = p.c_red;
+
+  {  // map slab and output rows of this tile
+    const int* mp = p.map[part] + row0 * width;
+    for (int e = tid; e < BM * width; e += 256) mapS[e] = mp[e];
+    const int* pm = p.perm[part];
+    for (int r = tid; r < BM; r += 256) {
+      const long long g = row0 + r;
+      permS[r] = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+    }
+  }
+  __syncthreads();
+
+  // per-block offset masks: bit c set iff some row of the 16-row block has neighbour c
+  unsigned blk_mask[MB];
+  {
+    unsigned bits = 0;
+    if (lane < WM) {
+      const int* mr = mapS + (wave * WM + lane) * width;
+      for (int c = 0; c < width; ++c) bits |= (mr[c] >= 0 ? 1u : 0u) << c;
+    }
+    bits |= __shfl_xor(bits, 1);
+    bits |= __shfl_xor(bits, 2);
+    bits |= __shfl_xor(bits, 4);
+    bits |= __shfl_xor(bits, 8);
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb) blk_mask[mb] = __builtin_amdgcn_readlane(bits, mb * 16);
+  }
+
+  f32x4 acc[MB][NB];
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+  const int n_chunks = (c_red + KC - 1) / KC;
+  const int total = __popc(tmask) * n_chunks;
+
+  uint4 ra[A_PASSES], rb[B_PASSES];
+  const int a_seg = tid % SEG, a_row = tid / SEG;
+
+  auto load_regs = [&](int c, int chunk) {
+    const int col = chunk * KC + a_seg * 8;
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) {
+      const int idx = mapS[(a_row + ps * A_RPP) * width + c];
+      uint4 v = make_uint4(0, 0, 0, 0);
+      if (idx >= 0 && col < c_red) v = *reinterpret_cast<const uint4*>(feats + (long long)idx * c_red + col);
+      ra[ps] = v;
+    }
+    const int k = lo + c;
+    const long long wk = (long long)(p.mirror ? p.V - 1 - k : k) * p.C_in * p.C_out;
+    if (!p.dgrad) {
+      const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
+#pragma unroll
+      for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int kk = kk0 + ps * BF_RPP;
+        const int ci = chunk * KC + kk, co = n0 + nseg * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (kk < KC && ci < p.C_in && co < p.C_out)
+          v = *reinterpret_cast<const uint4*>(wts + wk + (long long)ci * p.C_out + co);
+        rb[ps] = v;
+      }
+    } else {
+#pragma unroll
+      for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int n = a_row + ps * A_RPP;
+        const int ci = n0 + n, co = chunk * KC + a_seg * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (n < BN && ci < p.C_in && co < p.C_out)
+          v = *reinterpret_cast<const uint4*>(wts + wk + (long long)ci * p.C_out + co);
+        rb[ps] = v;
+      }
+    }
+  };
+
+  auto store_lds = [&](int buf) {
+    unsigned short* a = As + buf * BM * LDA;
+    unsigned short* b = Bs + buf * BN * LDA;
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps)
+      *reinterpret_cast<uint4*>(a + (a_row + ps * A_RPP) * LDA + a_seg * 8) = ra[ps];
+    if (!p.dgrad) {  // forward: the weight slice arrives [ci][co]; the MFMA wants [co][ci]
+      const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
+#pragma unroll
+      for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int kk = kk0 + ps * BF_RPP;
+        if (kk < KC) {
+          const unsigned w[4] = {rb[ps].x, rb[ps].y, rb[ps].z, rb[ps].w};
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            b[(nseg * 8 + 2 * i) * LDA + kk] = (unsigned short)(w[i] & 0xFFFFu);
+            b[(nseg * 8 + 2 * i + 1) * LDA + kk] = (unsigned short)(w[i] >> 16);
+          }
+        }
+      }
+    } else {
+#pragma unroll
+      for (int ps = 0; ps < B_PASSES; ++ps) {
+        const int n = a_row + ps * A_RPP;
+        if (n < BN) *reinterpret_cast<uint4*>(b + n * LDA + a_seg * 8) = rb[ps];
+      }
+    }
+  };
+
+  unsigned m_rem = tmask;
+  int cur_c = 0, cur_chunk = 0;
+  if (total > 0) {
+    cur_c = __ffs((int)m_rem) - 1;
+    m_rem &= m_rem - 1;
+    load_regs(cur_c, 0);
+    store_lds(0);
+  }
+  __syncthreads();
+
+  for (int it = 0; it < total; ++it) {
+    int nxt_c = cur_c, nxt_chunk = cur_chunk + 1;
+    if (nxt_chunk == n_chunks) {
+      nxt_chunk = 0;
+      nxt_c = __ffs((int)m_rem) - 1;
+      m_rem &= m_rem - 1;
+    }
+    const bool more = (it + 1 < total);
+    if (more) load_regs(nxt_c, nxt_chunk);
+
+    const unsigned short* a = As + (it & 1) * BM * LDA + (wave * WM + (lane & 15)) * LDA + (lane >> 4) * 8;
+    const unsigned short* b = Bs + (it & 1) * BN * LDA + (lane & 15) * LDA + (lane >> 4) * 8;
+#pragma unroll
+    for (int ks = 0; ks < KC / 32; ++ks) {
+      vec8 bf[NB];
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDA + ks * 32);
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) {
+        if ((blk_mask[mb] >> cur_c) & 1u) {
+          const vec8 af = *reinterpret_cast<const vec8*>(a + mb * 16 * LDA + ks * 32);
+#pragma unroll
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = Mfma<T>::run(af, bf[nb], acc[mb][nb]);
+        }
+      }
+    }
+    if (more) store_lds((it + 1) & 1);
+    __syncthreads();
+    cur_c = nxt_c;
+    cur_chunk = nxt_chunk;
+  }
+
+  // D layout of the 16x16 MFMA: lane holds rows 4*(lane/16)+r, column lane%16
+  const int c_out = p.c_out;
+#pragma unroll
+  for (int mb = 0; mb < MB; ++mb) {
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int orow = permS[wave * WM + mb * 16 + (lane >> 4) * 4 + r];
+      if (orow < 0) continue;
+#pragma unroll
+      for (int nb = 0; nb < NB; ++nb) {
+        const int col = n0 + nb * 16 + (lane & 15);
+        if (col >= c_out) continue;
+        const float v = acc[mb][nb][r];
+        if (p.parts > 1)
+          p.partial[((long long)part * p.rows + orow) * c_out + col] = v;
+        else
+          reinterpret_cast<T*>(p.out)[(long long)orow * c_out + col] = (T)v;
+      }
+    }
+  }
+}
+
+// fp32 path: plain FMA arithmetic, 64 x 64 tile, 4 x 4 outputs per thread.
+constexpr int F32_BM = 64, F32_BN = 64, F32_KC = 16;
+
+__global__ void __launch_bounds__(256) k_igemm_f32(const IgemmParams p) {
+  __shared__ float As[F32_BM][F32_KC + 1];
+  __shared__ float Bs[F32_KC][F32_BN + 4];
+  __shared__ int mapS[F32_BM * 27];
+  __shared__ int permS[F32_BM];
+  const int tid = threadIdx.x;
+  const int part = blockIdx.z;
+  const long long tile = blockIdx.x;
+  const int n0 = blockIdx.y * F32_BN;
+  const int width = p.width[part], lo = p.lo[part];
+  const long long row0 = tile * F32_BM;
+  const unsigned tmask = p.tilemask[part][tile];
+  const float* feats = reinterpret_cast<const float*>(p.feats);
+  const float* wts = reinterpret_cast<const float*>(p.weights);
+  const int c_red = p.c_red;
+  {
+    const int* mp = p.map[part] + row0 * width;
+    for (int e = tid; e < F32_BM * width; e += 256) mapS[e] = mp[e];
+    const int* pm = p.perm[part];
+    if (tid < F32_BM) {
+      const long long g = row0 + tid;
+      permS[tid] = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+    }
+  }
+  __syncthreads();
+  const int ty = tid / 16, tx = tid % 16;
+  float acc[4][4] = {};
+  const int n_chunks = (c_red + F32_KC - 1) / F32_KC;
+  unsigned m_rem = tmask;
+  while (m_rem) {
+    const int c = __ffs((int)m_rem) - 1;
+    m_rem &= m_rem - 1;
+    const int k = lo + c;
+    const long long wk = (long long)(p.mirror ? p.V - 1 - k : k) * p.C_in * p.C_out;
+    for (int chunk = 0; chunk < n_chunks; ++chunk) {
+      {  // A: 64 rows x 16 floats, one float4 per thread
+        const int r = tid / 4, seg = tid % 4;
+        const int idx = mapS[r * width + c];
+        const int col = chunk * F32_KC + seg * 4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (idx >= 0 && col < c_red) v = *reinterpret_cast<const float4*>(feats + (long long)idx * c_red + col);
+        As[r][seg * 4 + 0] = v.x;
+        As[r][seg * 4 + 1] = v.y;
+        As[r][seg * 4 + 2] = v.z;
+        As[r][seg * 4 + 3] = v.w;
+      }
+      if (!p.dgrad) {  // B[kk][n] = W[k][ci = chunk*KC + kk][co = n0 + n]
+        const int kk = tid / 16, n4 = (tid % 16) * 4;
+        const int ci = chunk * F32_KC + kk, co = n0 + n4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ci < p.C_in && co < p.C_out) v = *reinterpret_cast<const float4*>(wts + wk + (long long)ci * p.C_out + co);
+        Bs[kk][n4 + 0] = v.x;
+        Bs[kk][n4 + 1] = v.y;
+        Bs[kk][n4 + 2] = v.z;
+        Bs[kk][n4 + 3] = v.w;
+      } else {  // B[kk][n] = W[k][ci = n0 + n][co = chunk*KC + kk]
+        const int n = tid / 4, kk4 = (tid % 4) * 4;
+        const int ci = n0 + n, co = chunk * F32_KC + kk4;
+        float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+        if (ci < p.C_in && co < p.C_out) v = *reinterpret_cast<const float4*>(wts + wk + (long long)ci * p.C_out + co);
+        Bs[kk4 + 0][n] = v.x;
+        Bs[kk4 + 1][n] = v.y;
+        Bs[kk4 + 2][n] = v.z;
+        Bs[kk4 + 3][n] = v.w;
+      }
+      __syncthreads();
+#pragma unroll
+      for (int kk = 0; kk < F32_KC; ++kk) {
+        float a[4], b[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) a[i] = As[ty * 4 + i][kk];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+      }
+      __syncthreads();
+    }
+  }
+  const int c_out = p.c_out;
+  for (int i = 0; i < 4; ++i) {
+    const int orow = permS[ty * 4 + i];
+    if (orow < 0) continue;
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx * 4 + j;
+      if (col >= c_out) continue;
+      if (p.parts > 1)
+        p.partial[((long long)part * p.rows + orow) * c_out + col] = acc[i][j];
+      else
+        reinterpret_cast<float*>(p.out)[(long long)orow * c_out + col] = acc[i][j];
+    }
+  }
+}
+
+// out[e] = sum over parts of partial[part][e], rounded once to the output type (Section 4.1)
+template <typename T>
+__global__ void __launch_bounds__(256) k_split_reduce(const float* __restrict__ partial, int parts, long long elems,
+                                                      T* __restrict__ out) {
+  const long long e4 = ((long long)blockIdx.x * blockDim.x + threadIdx.x) * 4;
+  if (e4 >= elems) return;
+  float4 s = *reinterpret_cast<const float4*>(partial + e4);
+  for (int q = 1; q < parts; ++q) {
+    const float4 v = *reinterpret_cast<const float4*>(partial + (long long)q * elems + e4);
+    s.x += v.x;
+    s.y += v.y;
+    s.z += v.z;
+    s.w += v.w;
+  }
+  out[e4 + 0] = (T)s.x;
+  out[e4 + 1] = (T)s.y;
+  out[e4 + 2] = (T)s.z;
+  out[e4 + 3] = (T)s.w;
+}
+
+template <typename T, int BM, int BN, int KC>
+int launch_igemm(const IgemmParams& p, dim3 grid, hipStream_t st) {
+  typedef IgemmSmem<BM, BN, KC> S;
+  static bool attr_set = false;
+  auto fn = k_igemm<T, BM, BN, KC>;
+  if (!attr_set) {
+    SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)S::total));
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(fn, grid, dim3(256), S::total, st, p);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+template <typename T, int BM, int BN>
+int launch_kc(const IgemmParams& p, int kc, dim3 grid, hipStream_t st) {
+  return kc == 64 ? launch_igemm<T, BM, BN, 64>(p, grid, st) : launch_igemm<T, BM, BN, 32>(p, grid, st);
+}
+
+template <typename T, int BM>
+int launch_bn(const IgemmParams& p, int bn, int kc, dim3 grid, hipStream_t st) {
+  switch (bn) {
+    case 32: return launch_kc<T, BM, 32>(p, kc, grid, st);
+    case 64: return launch_kc<T, BM, 64>(p, kc, grid, st);
+    case 128: return launch_kc<T, BM, 128>(p, kc, grid, st);
+  }
+  return SPCONV_EINVAL;
+}
+
+template <typename T>
+int launch_bm(const IgemmParams& p, int bm, int bn, int kc, dim3 grid, hipStream_t st) {
+  switch (bm) {
+    case 64: return launch_bn<T, 64>(p, bn, kc, grid, st);
+    case 128: return launch_bn<T, 128>(p, bn, kc, grid, st);
+    case 256: return launch_bn<T, 256>(p, bn, kc, grid, st);
+  }
+  return SPCONV_EINVAL;
+}
+
+}  // namespace
+
+int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
+              hipStream_t st) {
+  if (plan.rows == 0) return SPCONV_OK;
+  IgemmParams p{};
+  p.feats = a.feats;
+  p.weights = a.weights;
+  p.out = a.out;
+  p.partial = a.partial;
+  p.rows = plan.rows;
+  p.parts = plan.parts;
+  p.V = km->V;
+  p.C_in = a.C_in;
+  p.C_out = a.C_out;
+  p.dgrad = a.dgrad;
+  p.mirror = a.mirror;
+  p.c_red = a.dgrad ? a.C_out : a.C_in;
+  p.c_out = a.dgrad ? a.C_in : a.C_out;
+  const int64_t tiles_alloc = plan.n_tiles > 0 ? plan.n_tiles : 1;
+  for (int i = 0; i < plan.parts; ++i) {
+    p.lo[i] = plan.lo[i];
+    p.width[i] = plan.width[i];
+    p.tilemask[i] = plan.tilemask.as<unsigned>() + (size_t)i * tiles_alloc;
+    if (plan.n_split == 0) {
+      p.map[i] = side.map.as<int>();
+      p.perm[i] = nullptr;
+    } else {
+      p.map[i] = plan.maps.as<int>() + plan.map_off[i];
+      p.perm[i] = plan.perm.as<int>() + (size_t)i * plan.rows_pad;
+    }
+  }
+  if (a.dtype == SPCONV_F32) {
+    dim3 grid((unsigned)plan.n_tiles, (unsigned)ceil_div(p.c_out, F32_BN), (unsigned)plan.parts);
+    hipLaunchKernelGGL(k_igemm_f32, grid, dim3(256), 0, st, p);
+    SPC_LAUNCH_CHECK();
+    return SPCONV_OK;
+  }
+  int bn = a.tile_n;
+  if (bn == 0) bn = p.c_out <= 32 ? 32 : (p.c_out <= 64 ? 64 : 128);
+  const int kc = (p.c_red % 64 == 0) ? 64 : 32;
+  dim3 grid((unsigned)plan.n_tiles, (unsigned)ceil_div(p.c_out, bn), (unsigned)plan.parts);
+  if (a.dtype == SPCONV_F16) return launch_bm<_Float16>(p, plan.tile_m, bn, kc, grid, st);
+  return launch_bm<__bf16>(p, plan.tile_m, bn, kc, grid, st);
+}
+
+int split_reduce(const float* partial, int parts, int64_t rows, int c, spconv_dtype dtype, void* out,
+                 hipStream_t st) {
+  const long long elems = (long long)rows * c;
+  if (elems == 0) return SPCONV_OK;
+  const unsigned blocks = (unsigned)ceil_div(elems / 4, 256);
+  switch (dtype) {
+    case SPCONV_F32:
+      hipLaunchKernelGGL((k_split_reduce<float>), dim3(blocks), dim3(256), 0, st, partial, parts, elems, (float*)out);
+      break;
+    case SPCONV_F16:
+      hipLaunchKernelGGL((k_split_reduce<_Float16>), dim3(blocks), dim3(256), 0, st, partial, parts, elems,
+                         (_Float16*)out);
+      break;
+    case SPCONV_BF16:
+      hipLaunchKernelGGL((k_split_reduce<__bf16>), dim3(blocks), dim3(256), 0, st, partial, parts, elems,
+                         (__bf16*)out);
+      break;
+  }
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+}  // namespace spc

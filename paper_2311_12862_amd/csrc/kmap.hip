@@ -1,0 +1,487 @@
+// Kernel-map construction: coordinate hash table, output-coordinate
+// generation for strided maps, neighbour probe, neighbour bitmask, and the
+// input-side (transposed) table that dgrad of strided maps walks.
+//
+// The paper treats these "mapping operations" as a cost centre (Sections 4.2,
+// 6.1, 6.3) but gives no algorithm for them; the design below is this
+// library's own: one 16-byte slot per key (64-bit packed coordinate + row
+// index) in an open-addressing table at load factor <= 0.5, one probe lane per
+// (output row, offset) so that map writes are contiguous per wave, and the
+// bitmask assembled from a wave ballot.
+#include "common.h"
+
+#include <algorithm>
+#include <new>
+
+namespace spc {
+namespace {
+
+constexpr unsigned long long kEmpty = ~0ull;
+
+enum : unsigned long long { FLAG_RANGE = 1, FLAG_DUP = 2, FLAG_FULL = 4 };
+
+// ctl block layout (8 x u64): [0] flags, [1] unique counter, [2] OR of keys, [3] AND of keys
+struct Ctl {
+  unsigned long long flags, count, key_or, key_and, pad[4];
+};
+
+__device__ __forceinline__ bool coord_ok(int b, int x, int y, int z) {
+  return (unsigned)b <= 65534u && (unsigned)(x + 32768) <= 65535u && (unsigned)(y + 32768) <= 65535u &&
+         (unsigned)(z + 32768) <= 65535u;
+}
+
+// (b, x, y, z) -> 64-bit key whose unsigned order is the lexicographic order of (b, x, y, z).
+__device__ __forceinline__ unsigned long long pack_key(int b, int x, int y, int z) {
+  return ((unsigned long long)(unsigned)b << 48) | ((unsigned long long)(unsigned)(x + 32768) << 32) |
+         ((unsigned long long)(unsigned)(y + 32768) << 16) | (unsigned long long)(unsigned)(z + 32768);
+}
+
+__device__ __forceinline__ unsigned hash_slot(unsigned long long key, int log_cap) {
+  return (unsigned)((key * 0x9E3779B97F4A7C15ull) >> (64 - log_cap));
+}
+
+// 0: inserted, 1: key already there, 2: table full (cannot happen at load <= 0.5)
+__device__ __forceinline__ int table_insert(unsigned long long* tab, int log_cap, unsigned long long key,
+                                            int val, unsigned* slot_out) {
+  const unsigned cap_mask = (1u << log_cap) - 1u;
+  unsigned s = hash_slot(key, log_cap);
+  for (unsigned it = 0; it <= cap_mask; ++it) {
+    unsigned long long old = atomicCAS(&tab[2 * (size_t)s], kEmpty, key);
+    if (old == kEmpty) {
+      tab[2 * (size_t)s + 1] = (unsigned long long)(unsigned)val;
+      if (slot_out) *slot_out = s;
+      return 0;
+    }
+    if (old == key) {
+      if (slot_out) *slot_out = s;
+      return 1;
+    }
+    s = (s + 1) & cap_mask;
+  }
+  return 2;
+}
+
+__device__ __forceinline__ int table_find(const unsigned long long* tab, int log_cap, unsigned long long key,
+                                          unsigned* slot_out) {
+  const unsigned cap_mask = (1u << log_cap) - 1u;
+  unsigned s = hash_slot(key, log_cap);
+  for (unsigned it = 0; it <= cap_mask; ++it) {
+    const ulonglong2 e = *reinterpret_cast<const ulonglong2*>(&tab[2 * (size_t)s]);
+    if (e.x == key) {
+      if (slot_out) *slot_out = s;
+      return (int)(unsigned)e.y;
+    }
+    if (e.x == kEmpty) return -1;
+    s = (s + 1) & cap_mask;
+  }
+  return -1;
+}
+
+__device__ __forceinline__ int floor_div(int a, int s) {
+  int q = a / s;
+  return (a % s != 0 && a < 0) ? q - 1 : q;
+}
+
+__global__ void k_ctl_init(Ctl* ctl) {
+  if (threadIdx.x == 0) {
+    ctl->flags = 0;
+    ctl->count = 0;
+    ctl->key_or = 0;
+    ctl->key_and = ~0ull;
+  }
+}
+
+// Insert key(p_j) -> j for every input row; flags range and duplicate errors.
+__global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ coords, int n,
+                                                     unsigned long long* tab, int log_cap, Ctl* ctl) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int4 c = coords[j];
+  if (!coord_ok(c.x, c.y, c.z, c.w)) {
+    atomicOr(&ctl->flags, FLAG_RANGE);
+    return;
+  }
+  const int r = table_insert(tab, log_cap, pack_key(c.x, c.y, c.z, c.w), j, nullptr);
+  if (r == 1) atomicOr(&ctl->flags, FLAG_DUP);
+  if (r == 2) atomicOr(&ctl->flags, FLAG_FULL);
+}
+
+// Coarse coordinates floor(p / s): de-duplicate through a second table, append each
+// new key to ukeys (order arbitrary; sorted afterwards), and reduce OR / AND of the
+// keys so that the host knows which key bytes vary.
+__global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ coords, int n, int stride,
+                                                       unsigned long long* tab, int log_cap,
+                                                       unsigned long long* __restrict__ ukeys, Ctl* ctl) {
+  __shared__ unsigned long long s_or[4], s_and[4];
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bool fresh = false;
+  unsigned long long key = 0, k_or = 0, k_and = ~0ull;
+  if (j < n) {
+    const int4 c = coords[j];
+    if (coord_ok(c.x, c.y, c.z, c.w)) {
+      key = pack_key(c.x, floor_div(c.y, stride), floor_div(c.z, stride), floor_div(c.w, stride));
+      const int r = table_insert(tab, log_cap, key, 0, nullptr);
+      fresh = (r == 0);
+      if (r == 2) atomicOr(&ctl->flags, FLAG_FULL);
+      k_or = key;
+      k_and = key;
+    }
+  }
+  // wave-aggregated append
+  const unsigned long long bal = __ballot(fresh);
+  unsigned long long base = 0;
+  if (bal != 0) {
+    const int leader = __ffsll((long long)bal) - 1;
+    if (lane == leader) base = atomicAdd(&ctl->count, (unsigned long long)__popcll(bal));
+    base = __shfl(base, leader);
+    if (fresh) ukeys[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
+  }
+  for (int o = 32; o > 0; o >>= 1) {
+    k_or |= __shfl_xor(k_or, o);
+    k_and &= __shfl_xor(k_and, o);
+  }
+  if (lane == 0) {
+    s_or[wave] = k_or;
+    s_and[wave] = k_and;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    atomicOr(&ctl->key_or, s_or[0] | s_or[1] | s_or[2] | s_or[3]);
+    atomicAnd(&ctl->key_and, s_and[0] & s_and[1] & s_and[2] & s_and[3]);
+  }
+}
+
+__global__ void __launch_bounds__(256) k_decode_keys(const unsigned long long* __restrict__ keys, int n,
+                                                     int4* __restrict__ coords) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const unsigned long long k = keys[i];
+  int4 c;
+  c.x = (int)(k >> 48);
+  c.y = (int)((k >> 32) & 0xFFFF) - 32768;
+  c.z = (int)((k >> 16) & 0xFFFF) - 32768;
+  c.w = (int)(k & 0xFFFF) - 32768;
+  coords[i] = c;
+}
+
+// After sorting the unique coarse keys: store each key's rank as its table value.
+__global__ void __launch_bounds__(256) k_assign_rank(const unsigned long long* __restrict__ keys, int n,
+                                                     unsigned long long* tab, int log_cap) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  unsigned slot = 0;
+  if (table_find(tab, log_cap, keys[i], &slot) >= 0) tab[2 * (size_t)slot + 1] = (unsigned long long)(unsigned)i;
+}
+
+// One lane per (row, offset).  A wave covers 64 / V rows, so that its V-lane
+// groups write contiguous map entries and a single ballot yields the bitmasks.
+//   TRANSPOSED = false: row coords are output points q; look up s*q + delta.
+//   TRANSPOSED = true : row coords are fine points f; look up (f - delta) / s if divisible.
+template <int K, bool TRANSPOSED>
+__global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, int n_rows, int stride,
+                                               const unsigned long long* __restrict__ tab, int log_cap,
+                                               int* __restrict__ map, unsigned* __restrict__ mask) {
+  constexpr int V = K * K * K;
+  constexpr int RPW = 64 / V;
+  constexpr int R = (K - 1) / 2;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int sub = lane / V, k = lane - sub * V;
+  const long long row = wave * RPW + sub;
+  const bool active = (sub < RPW) && (row < n_rows);
+  int found = -1;
+  if (active) {
+    const int4 c = rows[row];
+    const int dx = k / (K * K) - R, dy = (k / K) % K - R, dz = k % K - R;
+    int tx, ty, tz;
+    bool ok = true;
+    if (!TRANSPOSED) {
+      tx = stride * c.y + dx;
+      ty = stride * c.z + dy;
+      tz = stride * c.w + dz;
+    } else {
+      const int fx = c.y - dx, fy = c.z - dy, fz = c.w - dz;
+      tx = floor_div(fx, stride);
+      ty = floor_div(fy, stride);
+      tz = floor_div(fz, stride);
+      ok = (tx * stride == fx) && (ty * stride == fy) && (tz * stride == fz);
+    }
+    if (ok && coord_ok(c.x, tx, ty, tz)) found = table_find(tab, log_cap, pack_key(c.x, tx, ty, tz), nullptr);
+    map[row * V + k] = found;
+  }
+  const unsigned long long bal = __ballot(found >= 0);
+  if (active && k == 0) mask[row] = (unsigned)((bal >> (sub * V)) & ((1ull << V) - 1ull));
+}
+
+// T[j][k] = n for every present pair M[n][k] = j.
+__global__ void __launch_bounds__(256) k_scatter_in_side(const int* __restrict__ map, long long n_entries, int V,
+                                                         int* __restrict__ tmap) {
+  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= n_entries) return;
+  const int j = map[e];
+  if (j >= 0) {
+    const long long n = e / V;
+    const int k = (int)(e - n * V);
+    tmap[(long long)j * V + k] = (int)n;
+  }
+}
+
+template <int V>
+__global__ void __launch_bounds__(256) k_mask_from_map(const int* __restrict__ map, int n_rows,
+                                                       unsigned* __restrict__ mask) {
+  constexpr int RPW = 64 / V;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int sub = lane / V, k = lane - sub * V;
+  const long long row = wave * RPW + sub;
+  const bool active = (sub < RPW) && (row < n_rows);
+  const bool hit = active && map[row * V + k] >= 0;
+  const unsigned long long bal = __ballot(hit);
+  if (active && k == 0) mask[row] = (unsigned)((bal >> (sub * V)) & ((1ull << V) - 1ull));
+}
+
+// Per-offset pair counts from the bitmasks.
+__global__ void __launch_bounds__(256) k_count_pairs(const unsigned* __restrict__ mask, int n_rows,
+                                                     unsigned long long* __restrict__ counts) {
+  __shared__ unsigned cnt[32];
+  if (threadIdx.x < 32) cnt[threadIdx.x] = 0;
+  __syncthreads();
+  for (long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x; r < n_rows;
+       r += (long long)gridDim.x * blockDim.x) {
+    unsigned m = mask[r];
+    while (m) {
+      const int k = __ffs((int)m) - 1;
+      m &= m - 1;
+      atomicAdd(&cnt[k], 1u);
+    }
+  }
+  __syncthreads();
+  if (threadIdx.x < 32 && cnt[threadIdx.x]) atomicAdd(&counts[threadIdx.x], (unsigned long long)cnt[threadIdx.x]);
+}
+
+int log2_capacity(int64_t n) {
+  int lc = 10;
+  while ((1ll << lc) < 2 * n) ++lc;
+  return lc;
+}
+
+inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)ceil_div(n > 0 ? n : 1, per_block); }
+
+template <int K>
+int launch_probe(bool transposed, const int4* rows, int64_t n_rows, int stride, const unsigned long long* tab,
+                 int log_cap, int* map, unsigned* mask, hipStream_t st) {
+  constexpr int V = K * K * K;
+  constexpr int RPW = 64 / V;
+  const int64_t waves = ceil_div(n_rows, RPW);
+  const unsigned blocks = blocks_for(waves, 4);
+  if (transposed)
+    hipLaunchKernelGGL((k_probe<K, true>), dim3(blocks), dim3(256), 0, st, rows, (int)n_rows, stride, tab, log_cap,
+                       map, mask);
+  else
+    hipLaunchKernelGGL((k_probe<K, false>), dim3(blocks), dim3(256), 0, st, rows, (int)n_rows, stride, tab,
+                       log_cap, map, mask);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st) {
+  side.rows = rows;
+  side.rows_pad = round_up(rows > 0 ? rows : 1, kRowPad);
+  SPC_TRY(side.map.alloc((size_t)side.rows_pad * V * sizeof(int)));
+  SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
+  // padding rows: no neighbours
+  const size_t pad_rows = (size_t)(side.rows_pad - rows);
+  SPC_HIP(hipMemsetAsync(side.map.as<int>() + (size_t)rows * V, 0xFF, pad_rows * V * sizeof(int), st));
+  SPC_HIP(hipMemsetAsync(side.mask.as<unsigned>() + rows, 0, pad_rows * sizeof(unsigned), st));
+  return SPCONV_OK;
+}
+
+}  // namespace
+
+int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, hipStream_t st,
+               spconv_kmap** out) {
+  std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
+  if (!km) return SPCONV_ENOMEM;
+  km->K = K;
+  km->V = K * K * K;
+  km->stride = stride;
+  km->transposed = transposed;
+  km->build_stream = st;
+  const int V = km->V;
+  const bool needs_coarse = stride > 1;
+
+  if (N == 0) {
+    km->n_in = km->n_out = 0;
+    km->n_pairs = 0;
+    SPC_TRY(km->in_coords.alloc(16));
+    SPC_TRY(km->out_coords.alloc(16));
+    SPC_TRY(alloc_side(km->out_side, 0, V, st));
+    km->out_side.ready = true;
+    *out = km.release();
+    return SPCONV_OK;
+  }
+
+  const int4* rows = reinterpret_cast<const int4*>(coords);
+  DevBuf ctl_buf, tab_fine, tab_coarse, ukeys_a, ukeys_b, hist;
+  SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
+  Ctl* ctl = ctl_buf.as<Ctl>();
+  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(64), 0, st, ctl);
+  SPC_LAUNCH_CHECK();
+
+  // fine table: key(p_j) -> j.  Also the duplicate / range check of the caller's rows.
+  const int lc_fine = log2_capacity(N);
+  SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
+  SPC_HIP(hipMemsetAsync(tab_fine.p, 0xFF, (size_t)16 << lc_fine, st));
+  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
+                     tab_fine.as<unsigned long long>(), lc_fine, ctl);
+  SPC_LAUNCH_CHECK();
+
+  // the caller's rows are kept: they are P_in (and P_out for stride 1), or the fine output set
+  DevBuf own_rows;
+  SPC_TRY(own_rows.alloc((size_t)N * 16));
+  SPC_HIP(hipMemcpyAsync(own_rows.p, coords, (size_t)N * 16, hipMemcpyDeviceToDevice, st));
+
+  Ctl h{};
+  int64_t U = 0;
+  DevBuf coarse_rows;
+  if (needs_coarse) {
+    SPC_TRY(tab_coarse.alloc((size_t)16 << lc_fine));
+    SPC_HIP(hipMemsetAsync(tab_coarse.p, 0xFF, (size_t)16 << lc_fine, st));
+    SPC_TRY(ukeys_a.alloc((size_t)N * 8));
+    SPC_TRY(ukeys_b.alloc((size_t)N * 8));
+    hipLaunchKernelGGL(k_coarse_unique, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N, stride,
+                       tab_coarse.as<unsigned long long>(), lc_fine, ukeys_a.as<unsigned long long>(), ctl);
+    SPC_LAUNCH_CHECK();
+  }
+  if (needs_coarse) {
+    // the one synchronisation of a strided build: error flags, U, varying key bits
+    SPC_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+    SPC_HIP(hipStreamSynchronize(st));
+    if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
+    if (h.flags & FLAG_DUP) return SPCONV_EDUP;
+    if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+    U = (int64_t)h.count;
+    SPC_TRY(hist.alloc(sort_hist_elems(U) * sizeof(uint32_t)));
+    int in_b = 0;
+    SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, h.key_or ^ h.key_and,
+                           hist.as<uint32_t>(), st, &in_b));
+    const unsigned long long* sorted = in_b ? ukeys_b.as<unsigned long long>() : ukeys_a.as<unsigned long long>();
+    SPC_TRY(coarse_rows.alloc((size_t)U * 16));
+    hipLaunchKernelGGL(k_decode_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
+                       coarse_rows.as<int4>());
+    SPC_LAUNCH_CHECK();
+    if (transposed) {
+      hipLaunchKernelGGL(k_assign_rank, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
+                         tab_coarse.as<unsigned long long>(), lc_fine);
+      SPC_LAUNCH_CHECK();
+    }
+  }
+
+  int status = SPCONV_OK;
+  if (!transposed) {
+    km->n_in = N;
+    km->n_out = needs_coarse ? U : N;
+    const int4* qrows = needs_coarse ? coarse_rows.as<int4>() : rows;
+    SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
+    status = (K == 3) ? launch_probe<3>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
+                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), st)
+                      : launch_probe<1>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
+                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), st);
+    SPC_TRY(status);
+  } else {
+    km->n_in = needs_coarse ? U : N;
+    km->n_out = N;
+    const unsigned long long* tab = needs_coarse ? tab_coarse.as<unsigned long long>()
+                                                 : tab_fine.as<unsigned long long>();
+    SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
+    status = (K == 3) ? launch_probe<3>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
+                                        km->out_side.mask.as<unsigned>(), st)
+                      : launch_probe<1>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
+                                        km->out_side.mask.as<unsigned>(), st);
+    SPC_TRY(status);
+  }
+  km->out_side.ready = true;
+
+  if (!needs_coarse) {
+    SPC_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+    SPC_HIP(hipStreamSynchronize(st));
+    if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
+    if (h.flags & FLAG_DUP) return SPCONV_EDUP;
+    if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+  }
+
+  // coordinate sets kept for the export calls and for the next layer of a network
+  if (!transposed) {
+    if (needs_coarse) {
+      std::swap(km->in_coords.p, own_rows.p);
+      std::swap(km->in_coords.bytes, own_rows.bytes);
+      std::swap(km->out_coords.p, coarse_rows.p);
+      std::swap(km->out_coords.bytes, coarse_rows.bytes);
+    } else {
+      std::swap(km->in_coords.p, own_rows.p);
+      std::swap(km->in_coords.bytes, own_rows.bytes);  // P_out == P_in: out_coords stays empty
+    }
+  } else {
+    std::swap(km->out_coords.p, own_rows.p);
+    std::swap(km->out_coords.bytes, own_rows.bytes);
+    if (needs_coarse) {
+      std::swap(km->in_coords.p, coarse_rows.p);
+      std::swap(km->in_coords.bytes, coarse_rows.bytes);
+    }  // stride 1: P_in == the caller's rows: in_coords stays empty
+  }
+  // temporaries (tables, key lists) go back to the pool here; the stream has either been
+  // synchronised (stride 1) or later work on it is ordered after the kernels that read them
+  *out = km.release();
+  return SPCONV_OK;
+}
+
+int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
+  if (km->in_side.ready) return SPCONV_OK;
+  const int V = km->V;
+  SPC_TRY(alloc_side(km->in_side, km->n_in, V, st));
+  if (km->n_in > 0) {
+    SPC_HIP(hipMemsetAsync(km->in_side.map.p, 0xFF, (size_t)km->in_side.rows_pad * V * sizeof(int), st));
+    const long long entries = (long long)km->n_out * V;
+    if (entries > 0) {
+      hipLaunchKernelGGL(k_scatter_in_side, dim3(blocks_for(entries, 256)), dim3(256), 0, st,
+                         km->out_side.map.as<int>(), entries, V, km->in_side.map.as<int>());
+      SPC_LAUNCH_CHECK();
+    }
+    const int64_t rpw = 64 / V;
+    const unsigned blocks = blocks_for(ceil_div(km->n_in, rpw), 4);
+    if (V == 27)
+      hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
+                         (int)km->n_in, km->in_side.mask.as<unsigned>());
+    else
+      hipLaunchKernelGGL((k_mask_from_map<1>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
+                         (int)km->n_in, km->in_side.mask.as<unsigned>());
+    SPC_LAUNCH_CHECK();
+  }
+  km->in_side.ready = true;
+  return SPCONV_OK;
+}
+
+int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
+  unsigned long long h[32] = {0};
+  if (km->n_out > 0) {
+    DevBuf counts;
+    SPC_TRY(counts.alloc(32 * sizeof(unsigned long long)));
+    SPC_HIP(hipMemsetAsync(counts.p, 0, 32 * sizeof(unsigned long long), st));
+    const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(km->n_out, 256), 1024);
+    hipLaunchKernelGGL(k_count_pairs, dim3(blocks), dim3(256), 0, st, km->out_side.mask.as<unsigned>(),
+                       (int)km->n_out, counts.as<unsigned long long>());
+    SPC_LAUNCH_CHECK();
+    SPC_HIP(hipMemcpyAsync(h, counts.p, sizeof(h), hipMemcpyDeviceToHost, st));
+    SPC_HIP(hipStreamSynchronize(st));
+  }
+  int64_t total = 0;
+  for (int k = 0; k < km->V; ++k) {
+    total += (int64_t)h[k];
+    if (per_k) per_k[k] = (int64_t)h[k];
+  }
+  km->n_pairs = total;
+  return SPCONV_OK;
+}
+
+}  // namespace spc

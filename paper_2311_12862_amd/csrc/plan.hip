@@ -1,0 +1,235 @@
+// Mapping work that depends on the dataflow parameters (Sections 2.2.3, 3.2,
+// 4.1): per-split bitmask argsort, offline map reordering and padding,
+// per-tile mask reduction, the offset-major map and work list of wgrad, and
+// the executed-MAC count of a configuration.
+#include "common.h"
+
+#include <algorithm>
+#include <new>
+
+namespace spc {
+namespace {
+
+inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)ceil_div(n > 0 ? n : 1, per_block); }
+
+// key[r] = bits [lo, lo+width) of mask[r]; val[r] = r
+__global__ void __launch_bounds__(256) k_split_keys(const unsigned* __restrict__ mask, int rows, int lo, int width,
+                                                    unsigned* __restrict__ key, int* __restrict__ val) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  key[r] = (mask[r] >> lo) & ((1u << width) - 1u);
+  val[r] = r;
+}
+
+// perm_out[r] = sorted row index (or -1 in the padding); reordered[r][c] = map[perm[r]][lo + c]
+__global__ void __launch_bounds__(256)
+    k_reorder(const int* __restrict__ map, int V, const int* __restrict__ sorted_rows, int rows, long long rows_pad,
+              int lo, int width, int* __restrict__ reordered, int* __restrict__ perm_out) {
+  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= rows_pad * width) return;
+  const long long r = e / width;
+  const int c = (int)(e - r * width);
+  const int src = (r < rows) ? sorted_rows[r] : -1;
+  reordered[e] = (src >= 0) ? map[(long long)src * V + lo + c] : -1;
+  if (c == 0) perm_out[r] = src;
+}
+
+// tilemask[t] = OR over the tile's rows of their split keys.  One wave per tile.
+// perm == nullptr: rows in map order.
+__global__ void __launch_bounds__(256)
+    k_tile_mask(const unsigned* __restrict__ mask, const int* __restrict__ perm, long long rows, int tile_m, int lo,
+                int width, long long n_tiles, unsigned* __restrict__ tilemask) {
+  const int lane = threadIdx.x & 63;
+  const long long t = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (t >= n_tiles) return;
+  unsigned m = 0;
+  for (int i = lane; i < tile_m; i += 64) {
+    const long long r = t * tile_m + i;
+    if (r < rows) {
+      const int src = perm ? perm[r] : (int)r;
+      if (src >= 0) m |= mask[src];
+    }
+  }
+  for (int o = 32; o > 0; o >>= 1) m |= __shfl_xor(m, o);
+  if (lane == 0) tilemask[t] = (m >> lo) & (width >= 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));
+}
+
+// executed MAC units: for every group of `group` consecutive (sorted) rows,
+// popcount(OR of keys) * real rows in the group
+__global__ void __launch_bounds__(256)
+    k_mac_units(const unsigned* __restrict__ mask, const int* __restrict__ perm, long long rows, int group, int lo,
+                int width, unsigned long long* __restrict__ executed) {
+  const long long g = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long r0 = g * group;
+  unsigned long long mine = 0;
+  if (r0 < rows) {
+    unsigned m = 0;
+    int real = 0;
+    for (int i = 0; i < group; ++i) {
+      const long long r = r0 + i;
+      if (r < rows) {
+        const int src = perm ? perm[r] : (int)r;
+        if (src >= 0) {
+          m |= mask[src];
+          ++real;
+        }
+      }
+    }
+    m = (m >> lo) & (width >= 32 ? 0xFFFFFFFFu : ((1u << width) - 1u));
+    mine = (unsigned long long)__popc(m) * (unsigned long long)real;
+  }
+  for (int o = 32; o > 0; o >>= 1) mine += __shfl_xor(mine, o);
+  if ((threadIdx.x & 63) == 0 && mine) atomicAdd(executed, mine);
+}
+
+// map_k[k][n] = map[n][k]
+__global__ void __launch_bounds__(256)
+    k_offset_major(const int* __restrict__ map, int V, long long rows_pad, int* __restrict__ map_k) {
+  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (e >= rows_pad * V) return;
+  const long long k = e / rows_pad, n = e - k * rows_pad;
+  map_k[e] = map[n * V + k];
+}
+
+}  // namespace
+
+int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out) {
+  auto key = std::make_pair(n_split, tile_m);
+  auto it = side.plans.find(key);
+  if (it != side.plans.end()) {
+    *out = it->second.get();
+    return SPCONV_OK;
+  }
+  std::unique_ptr<IgemmPlan> p(new (std::nothrow) IgemmPlan);
+  if (!p) return SPCONV_ENOMEM;
+  const int V = km->V;
+  p->n_split = n_split;
+  p->tile_m = tile_m;
+  p->parts = std::max(1, n_split);
+  p->rows = side.rows;
+  p->rows_pad = side.rows_pad;
+  p->n_tiles = ceil_div(side.rows, tile_m);
+  size_t off = 0;
+  for (int i = 0; i < p->parts; ++i) {
+    p->lo[i] = (int)(((int64_t)i * V) / p->parts);
+    p->width[i] = (int)(((int64_t)(i + 1) * V) / p->parts) - p->lo[i];
+    p->map_off[i] = off;
+    off += (size_t)p->rows_pad * p->width[i];
+  }
+  const int64_t tiles_alloc = std::max<int64_t>(1, p->n_tiles);
+  SPC_TRY(p->tilemask.alloc((size_t)p->parts * tiles_alloc * sizeof(unsigned)));
+  const unsigned tile_blocks = blocks_for(tiles_alloc, 4);
+  if (n_split == 0) {
+    if (p->n_tiles > 0) {
+      hipLaunchKernelGGL(k_tile_mask, dim3(tile_blocks), dim3(256), 0, st, side.mask.as<unsigned>(),
+                         (const int*)nullptr, (long long)p->rows, tile_m, 0, V, (long long)p->n_tiles,
+                         p->tilemask.as<unsigned>());
+      SPC_LAUNCH_CHECK();
+    }
+  } else {
+    SPC_TRY(p->maps.alloc(off * sizeof(int)));
+    SPC_TRY(p->perm.alloc((size_t)p->parts * p->rows_pad * sizeof(int)));
+    if (p->rows > 0) {
+      DevBuf key_a, key_b, val_a, val_b, hist;
+      const size_t n = (size_t)p->rows;
+      SPC_TRY(key_a.alloc(n * 4));
+      SPC_TRY(key_b.alloc(n * 4));
+      SPC_TRY(val_a.alloc(n * 4));
+      SPC_TRY(val_b.alloc(n * 4));
+      SPC_TRY(hist.alloc(sort_hist_elems(p->rows) * sizeof(uint32_t)));
+      for (int i = 0; i < p->parts; ++i) {
+        hipLaunchKernelGGL(k_split_keys, dim3(blocks_for(p->rows, 256)), dim3(256), 0, st,
+                           side.mask.as<unsigned>(), (int)p->rows, p->lo[i], p->width[i], key_a.as<unsigned>(),
+                           val_a.as<int>());
+        SPC_LAUNCH_CHECK();
+        int in_b = 0;
+        SPC_TRY(radix_sort_u32(key_a.as<uint32_t>(), key_b.as<uint32_t>(), val_a.as<int32_t>(), val_b.as<int32_t>(),
+                               p->rows, p->width[i], hist.as<uint32_t>(), st, &in_b));
+        const int* sorted_rows = in_b ? val_b.as<int>() : val_a.as<int>();
+        int* perm_i = p->perm.as<int>() + (size_t)i * p->rows_pad;
+        hipLaunchKernelGGL(k_reorder, dim3(blocks_for(p->rows_pad * p->width[i], 256)), dim3(256), 0, st,
+                           side.map.as<int>(), V, sorted_rows, (int)p->rows, (long long)p->rows_pad, p->lo[i],
+                           p->width[i], p->maps.as<int>() + p->map_off[i], perm_i);
+        SPC_LAUNCH_CHECK();
+        hipLaunchKernelGGL(k_tile_mask, dim3(tile_blocks), dim3(256), 0, st, side.mask.as<unsigned>(),
+                           (const int*)perm_i, (long long)p->rows, tile_m, p->lo[i], p->width[i],
+                           (long long)p->n_tiles, p->tilemask.as<unsigned>() + (size_t)i * tiles_alloc);
+        SPC_LAUNCH_CHECK();
+      }
+      // the sort temporaries return to the pool while the stream may still use them;
+      // later users are ordered behind on the same stream
+    }
+  }
+  *out = p.get();
+  side.plans[key] = std::move(p);
+  return SPCONV_OK;
+}
+
+int plan_mac_units(spconv_kmap* km, SideMap& side, IgemmPlan* plan, int group_rows, hipStream_t st,
+                   int64_t* executed) {
+  (void)km;
+  *executed = 0;
+  if (plan->rows == 0) return SPCONV_OK;
+  DevBuf acc;
+  SPC_TRY(acc.alloc(8));
+  SPC_HIP(hipMemsetAsync(acc.p, 0, 8, st));
+  const int64_t groups = ceil_div(plan->rows, group_rows);
+  for (int i = 0; i < plan->parts; ++i) {
+    const int* perm = plan->n_split ? plan->perm.as<int>() + (size_t)i * plan->rows_pad : nullptr;
+    hipLaunchKernelGGL(k_mac_units, dim3(blocks_for(groups, 256)), dim3(256), 0, st, side.mask.as<unsigned>(),
+                       perm, (long long)plan->rows, group_rows, plan->lo[i], plan->width[i],
+                       acc.as<unsigned long long>());
+    SPC_LAUNCH_CHECK();
+  }
+  unsigned long long h = 0;
+  SPC_HIP(hipMemcpyAsync(&h, acc.p, 8, hipMemcpyDeviceToHost, st));
+  SPC_HIP(hipStreamSynchronize(st));
+  *executed = (int64_t)h;
+  return SPCONV_OK;
+}
+
+int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan** out) {
+  auto it = km->wplans.find(target_pairs);
+  if (it != km->wplans.end()) {
+    *out = it->second.get();
+    return SPCONV_OK;
+  }
+  std::unique_ptr<WgradPlan> p(new (std::nothrow) WgradPlan);
+  if (!p) return SPCONV_ENOMEM;
+  const int V = km->V;
+  const SideMap& side = km->out_side;
+  p->target_pairs = target_pairs;
+  SPC_TRY(p->map_k.alloc((size_t)side.rows_pad * V * sizeof(int)));
+  hipLaunchKernelGGL(k_offset_major, dim3(blocks_for(side.rows_pad * V, 256)), dim3(256), 0, st, side.map.as<int>(),
+                     V, (long long)side.rows_pad, p->map_k.as<int>());
+  SPC_LAUNCH_CHECK();
+  SPC_TRY(kmap_count_pairs(km, st, p->counts));  // synchronises
+  std::vector<WgradItem> items;
+  std::vector<int32_t> seg(V + 1, 0);
+  for (int k = 0; k < V; ++k) {
+    seg[k] = (int32_t)items.size();
+    if (p->counts[k] == 0) continue;
+    const int64_t pieces = std::max<int64_t>(1, ceil_div(p->counts[k], target_pairs));
+    for (int64_t q = 0; q < pieces; ++q) {
+      WgradItem w;
+      w.k = k;
+      w.row_begin = (int32_t)((km->n_out * q) / pieces);
+      w.row_end = (int32_t)((km->n_out * (q + 1)) / pieces);
+      w.slot = (int32_t)items.size();
+      if (w.row_end > w.row_begin) items.push_back(w);
+    }
+  }
+  seg[V] = (int32_t)items.size();
+  p->n_items = (int)items.size();
+  SPC_TRY(p->items.alloc(std::max<size_t>(1, items.size()) * sizeof(WgradItem)));
+  SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int32_t)));
+  if (!items.empty())
+    SPC_HIP(hipMemcpyAsync(p->items.p, items.data(), items.size() * sizeof(WgradItem), hipMemcpyHostToDevice, st));
+  SPC_HIP(hipMemcpyAsync(p->seg.p, seg.data(), seg.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
+  SPC_HIP(hipStreamSynchronize(st));  // the host vectors go out of scope
+  *out = p.get();
+  km->wplans[target_pairs] = std::move(p);
+  return SPCONV_OK;
+}
+
+}  // namespace spc

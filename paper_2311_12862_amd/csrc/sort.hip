@@ -1,0 +1,172 @@
+// Stable least-significant-digit radix sort built from wavefront primitives.
+//
+// Each wave owns a contiguous run of kItemsPerWave items.  A pass is three
+// launches: per-wave digit histograms (LDS atomics, wave-private counters),
+// one exclusive scan over the [digit][wave] matrix, and a scatter in which a
+// wave ranks its 64 items per step with ballots (lanes with equal digits find
+// each other from one ballot per digit bit; the rank is the number of peers in
+// lower lanes) against wave-private running offsets held in LDS.  Used for the
+// bitmask argsort of Sections 2.2.3 / 4.1 and for putting the output
+// coordinates of strided maps into their canonical order.
+#include "common.h"
+
+namespace spc {
+namespace {
+
+constexpr int kItemsPerWave = 512;
+constexpr int kMaxBits = 9;
+constexpr int kMaxBins = 1 << kMaxBits;
+
+template <typename KeyT>
+__global__ void __launch_bounds__(256) k_radix_hist(const KeyT* __restrict__ keys, long long n, int shift, int bits,
+                                                    unsigned* __restrict__ hist, int n_waves) {
+  __shared__ unsigned cnt[4][kMaxBins];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long long w = (long long)blockIdx.x * 4 + wib;
+  const int bins = 1 << bits;
+  for (int d = lane; d < bins; d += 64) cnt[wib][d] = 0;
+  __syncthreads();
+  if (w < n_waves) {
+    const long long begin = w * kItemsPerWave;
+    const long long end = begin + kItemsPerWave < n ? begin + kItemsPerWave : n;
+    for (long long i = begin + lane; i < end; i += 64)
+      atomicAdd(&cnt[wib][(unsigned)(keys[i] >> shift) & (unsigned)(bins - 1)], 1u);
+  }
+  __syncthreads();
+  if (w < n_waves)
+    for (int d = lane; d < bins; d += 64) hist[(long long)d * n_waves + w] = cnt[wib][d];
+}
+
+// Exclusive scan of `elems` counters in place, one workgroup of 1024 threads.
+__global__ void __launch_bounds__(1024) k_radix_scan(unsigned* __restrict__ hist, long long elems) {
+  __shared__ unsigned part[1024];
+  const int t = threadIdx.x;
+  const long long per = (elems + 1023) / 1024;
+  const long long begin = t * per;
+  const long long end = begin + per < elems ? begin + per : elems;
+  unsigned sum = 0;
+  for (long long i = begin; i < end; ++i) sum += hist[i];
+  part[t] = sum;
+  __syncthreads();
+  for (int off = 1; off < 1024; off <<= 1) {
+    const unsigned v = (t >= off) ? part[t - off] : 0u;
+    __syncthreads();
+    part[t] += v;
+    __syncthreads();
+  }
+  unsigned run = part[t] - sum;
+  for (long long i = begin; i < end; ++i) {
+    const unsigned v = hist[i];
+    hist[i] = run;
+    run += v;
+  }
+}
+
+template <typename KeyT, bool HAS_VAL>
+__global__ void __launch_bounds__(256)
+    k_radix_scatter(const KeyT* __restrict__ kin, KeyT* __restrict__ kout, const int* __restrict__ vin,
+                    int* __restrict__ vout, long long n, int shift, int bits, const unsigned* __restrict__ hist,
+                    int n_waves) {
+  __shared__ unsigned off[4][kMaxBins];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const long long w = (long long)blockIdx.x * 4 + wib;
+  const int bins = 1 << bits;
+  if (w < n_waves)
+    for (int d = lane; d < bins; d += 64) off[wib][d] = hist[(long long)d * n_waves + w];
+  __syncthreads();
+  if (w >= n_waves) return;
+  const long long begin = w * kItemsPerWave;
+  const long long end = begin + kItemsPerWave < n ? begin + kItemsPerWave : n;
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (long long base = begin; base < end; base += 64) {
+    const long long i = base + lane;
+    const bool valid = i < end;
+    const KeyT key = valid ? kin[i] : (KeyT)0;
+    const unsigned d = (unsigned)(key >> shift) & (unsigned)(bins - 1);
+    unsigned long long peers = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+      const bool bit = (d >> b) & 1u;
+      const unsigned long long bal = __ballot(bit);
+      peers &= bit ? bal : ~bal;
+    }
+    const unsigned rank = (unsigned)__popcll(peers & lt);
+    unsigned pos = 0;
+    if (valid) pos = off[wib][d];
+    __builtin_amdgcn_wave_barrier();  // every lane has read its offset before a leader advances it
+    if (valid && rank == 0) off[wib][d] = pos + (unsigned)__popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+    if (valid) {
+      kout[pos + rank] = key;
+      if (HAS_VAL) vout[pos + rank] = vin[i];
+    }
+  }
+}
+
+template <typename KeyT, bool HAS_VAL>
+int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n, int shift, int bits,
+               uint32_t* hist, hipStream_t st) {
+  const int n_waves = (int)ceil_div(n, kItemsPerWave);
+  const unsigned blocks = (unsigned)ceil_div(n_waves, 4);
+  hipLaunchKernelGGL((k_radix_hist<KeyT>), dim3(blocks), dim3(256), 0, st, kin, (long long)n, shift, bits, hist,
+                     n_waves);
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_radix_scan, dim3(1), dim3(1024), 0, st, hist, ((long long)n_waves) << bits);
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL((k_radix_scatter<KeyT, HAS_VAL>), dim3(blocks), dim3(256), 0, st, kin, kout, vin, vout,
+                     (long long)n, shift, bits, hist, n_waves);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+}  // namespace
+
+size_t sort_hist_elems(int64_t n) { return (size_t)ceil_div(n > 0 ? n : 1, kItemsPerWave) * kMaxBins; }
+
+int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* val_b, int64_t n, int key_bits,
+                   uint32_t* hist, hipStream_t st, int* in_b) {
+  *in_b = 0;
+  if (n <= 1 || key_bits <= 0) return SPCONV_OK;
+  const int passes = (key_bits + kMaxBits - 1) / kMaxBits;
+  const int bits = (key_bits + passes - 1) / passes;  // even digit widths, each <= kMaxBits
+  int shift = 0;
+  for (int p = 0; p < passes; ++p) {
+    const int b = (shift + bits <= key_bits) ? bits : key_bits - shift;
+    if (*in_b == 0)
+      SPC_TRY((radix_pass<uint32_t, true>(key_a, key_b, val_a, val_b, n, shift, b, hist, st)));
+    else
+      SPC_TRY((radix_pass<uint32_t, true>(key_b, key_a, val_b, val_a, n, shift, b, hist, st)));
+    *in_b ^= 1;
+    shift += b;
+  }
+  return SPCONV_OK;
+}
+
+int radix_sort_u64(uint64_t* key_a, uint64_t* key_b, int64_t n, uint64_t varying, uint32_t* hist, hipStream_t st,
+                   int* in_b) {
+  *in_b = 0;
+  if (n <= 1) return SPCONV_OK;
+  // Digits are taken over maximal runs of bit positions that contain a varying bit,
+  // cut into pieces of at most kMaxBits; constant bits in between cost nothing.
+  int pos = 0;
+  while (pos < 64) {
+    if (!((varying >> pos) & 1ull)) {
+      ++pos;
+      continue;
+    }
+    int top = pos;
+    for (int b = pos; b < 64 && b < pos + kMaxBits; ++b)
+      if ((varying >> b) & 1ull) top = b;
+    const int bits = top - pos + 1;
+    if (*in_b == 0)
+      SPC_TRY((radix_pass<unsigned long long, false>((unsigned long long*)key_a, (unsigned long long*)key_b,
+                                                     nullptr, nullptr, n, pos, bits, hist, st)));
+    else
+      SPC_TRY((radix_pass<unsigned long long, false>((unsigned long long*)key_b, (unsigned long long*)key_a,
+                                                     nullptr, nullptr, n, pos, bits, hist, st)));
+    *in_b ^= 1;
+    pos += bits;
+  }
+  return SPCONV_OK;
+}
+
+}  // namespace spc

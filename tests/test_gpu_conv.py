@@ -1,0 +1,205 @@
+"""Feature kernels (fwd, dgrad, wgrad) of the HIP library against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sparse_conv as oc
+from workloads import generators as gen
+from _util import TOL, coords_dev, make_layer, norm_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import paper_2311_12862_amd as sp
+    return sp
+
+
+@pytest.fixture(scope="module")
+def cloud():
+    """A cloud that spans several 256-row tiles with a ragged tail and mixed neighbour counts."""
+    c = gen.lidar_scene(77, target_n=2900)
+    return c, oc.build_kmap(c, 3, 1)
+
+
+def _cfg(sp, n_split=0, tile_m=0, tile_n=0, wgrad_pairs=0):
+    c = sp.Config()
+    c.n_split, c.tile_m, c.tile_n, c.wgrad_pairs = n_split, tile_m, tile_n, wgrad_pairs
+    return c
+
+
+def test_config1_tiny_fp32_forward(sp):
+    """2,000 voxels in 64^3, fp32, 16 -> 16, forward only."""
+    c = gen.uniform_cloud(2000, 64, seed=1000)
+    ref = oc.build_kmap(c, 3, 1)
+    (x32, x), (w32, w), _ = make_layer(2000, 2000, 16, 16, 27, "f32", 1001)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    want = oc.forward(x32, w32, ref.M)
+    for n_split in range(5):
+        got = sp.fwd(x, w, km, _cfg(sp, n_split))
+        assert norm_err(got, want) <= TOL["f32"], n_split
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("c_in,c_out", [(64, 64), (32, 96), (96, 32), (8, 16), (128, 256), (256, 128)])
+def test_forward_channels(sp, cloud, dtype, c_in, c_out):
+    c, ref = cloud
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 5)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    want = oc.forward(x32, w32, ref.M)
+    got = sp.fwd(x, w, km)
+    assert norm_err(got, want) <= TOL[dtype]
+
+
+@pytest.mark.parametrize("n_split", [0, 1, 2, 3, 4])
+@pytest.mark.parametrize("tile_m", [64, 128, 256])
+def test_forward_design_space(sp, cloud, n_split, tile_m):
+    """Sorting and splitting change the work, never the result (Sections 2.2.3, 4.1)."""
+    c, ref = cloud
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 6)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    want = oc.forward(x32, w32, ref.M)
+    got = sp.fwd(x, w, km, _cfg(sp, n_split, tile_m))
+    assert norm_err(got, want) <= TOL["f16"]
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+
+
+@pytest.mark.parametrize("tile_n", [32, 64, 128])
+def test_forward_tile_n(sp, cloud, tile_n):
+    c, ref = cloud
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 96, 27, "bf16", 7)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    got = sp.fwd(x, w, km, _cfg(sp, 1, 128, tile_n))
+    assert norm_err(got, oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("stride,transposed", [(1, False), (2, False), (2, True), (1, True)])
+def test_fwd_dgrad_wgrad_all_map_kinds(sp, dtype, stride, transposed):
+    c = gen.lidar_scene(78, target_n=2500)
+    ref = oc.build_kmap(c, 3, stride, transposed)
+    c_in, c_out = (16, 24) if dtype == "f32" else (32, 64)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 11)
+    km = sp.build_kmap(coords_dev(c), 3, stride, transposed)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    for n_split in (0, 1, 3):
+        cfg = _cfg(sp, n_split)
+        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL[dtype]
+        assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL[dtype]
+    dw = sp.wgrad(x, g, km)
+    assert dw.dtype == torch.float32
+    # dW is produced in fp32 from exactly representable inputs: only the summation order differs
+    assert norm_err(dw, oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    dw2 = sp.wgrad(x, g, km, _cfg(sp, wgrad_pairs=1500))
+    assert norm_err(dw2, oc.wgrad(x32, g32, ref.M)) <= 1e-4
+
+
+def test_k1_is_linear_layer(sp):
+    c = gen.uniform_cloud(1500, 16, seed=3)
+    (x32, x), (w32, w), (g32, g) = make_layer(1500, 1500, 64, 32, 1, "f16", 21)
+    km = sp.build_kmap(coords_dev(c), 1, 1)
+    assert norm_err(sp.fwd(x, w, km), x32.astype(np.float64) @ w32[0].astype(np.float64)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km), g32.astype(np.float64) @ w32[0].astype(np.float64).T) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, km), (x32.astype(np.float64).T @ g32.astype(np.float64))[None]) <= 1e-4
+
+
+def test_isolated_points_and_dense_cube(sp):
+    # every point isolated: only the centre offset is present
+    iso = gen.uniform_cloud(300, 10, seed=2) * np.array([1, 3, 3, 3], dtype=np.int32)
+    ref = oc.build_kmap(iso, 3, 1)
+    assert (ref.M >= 0).sum() == 300
+    (x32, x), (w32, w), (g32, g) = make_layer(300, 300, 32, 32, 27, "f16", 31)
+    km = sp.build_kmap(coords_dev(iso), 3, 1)
+    assert norm_err(sp.fwd(x, w, km), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    # fully occupied cube: all 27 offsets present in the interior
+    cube = gen.full_grid(9, 2, seed=4)
+    ref = oc.build_kmap(cube, 3, 1)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 32, 27, "f16", 32)
+    km = sp.build_kmap(coords_dev(cube), 3, 1)
+    for n_split in (0, 2):
+        assert norm_err(sp.fwd(x, w, km, _cfg(sp, n_split)), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+        assert norm_err(sp.dgrad(g, w, km, _cfg(sp, n_split)), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+
+
+def test_single_point_and_empty(sp):
+    one = np.array([[0, 1, 2, 3]], dtype=np.int32)
+    (x32, x), (w32, w), (g32, g) = make_layer(1, 1, 16, 16, 27, "f16", 41)
+    km = sp.build_kmap(coords_dev(one), 3, 1)
+    assert norm_err(sp.fwd(x, w, km), x32.astype(np.float64) @ w32[13].astype(np.float64)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km), g32.astype(np.float64) @ w32[13].astype(np.float64).T) <= TOL["f16"]
+    dw = sp.wgrad(x, g, km).cpu().numpy()
+    assert np.abs(dw[np.arange(27) != 13]).max() == 0
+    empty = sp.build_kmap(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
+    e = torch.empty((0, 16), dtype=torch.float16, device="cuda")
+    assert sp.fwd(e, w, empty).shape == (0, 16)
+    assert sp.wgrad(e, e, empty).abs().max().item() == 0
+
+
+def test_shape_and_config_errors(sp, cloud):
+    c, ref = cloud
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 51)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    with pytest.raises(sp.SpconvError) as e:
+        sp.fwd(x[:-1].contiguous(), w, km)
+    assert e.value.status == -5
+    with pytest.raises(sp.SpconvError) as e:
+        sp.fwd(x, w, km, _cfg(sp, 9))
+    assert e.value.status == -1
+    with pytest.raises(sp.SpconvError) as e:
+        sp.fwd(x, w, km, _cfg(sp, 1, 100))
+    assert e.value.status == -1
+    x12 = torch.zeros((ref.n_in, 12), dtype=torch.float16, device="cuda")
+    w12 = torch.zeros((27, 12, 64), dtype=torch.float16, device="cuda")
+    with pytest.raises(sp.SpconvError) as e:
+        sp.fwd(x12, w12, km)
+    assert e.value.status == -5
+
+
+@pytest.mark.parametrize("n_split", [1, 2, 4])
+def test_sort_invariants(sp, cloud, n_split):
+    """Any order of equal keys is valid; what is unique is checked: each perm is a
+    bijection, its keys ascend, and (this library sorts stably) ties keep row order."""
+    c, ref = cloud
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    mask = oc.bitmask(ref.M).astype(np.uint64)
+    cfg = _cfg(sp, n_split)
+    for i, (lo, hi) in enumerate(oc.split_ranges(27, n_split)):
+        perm = km.export_perm(sp.OP_FWD, cfg, i).cpu().numpy()
+        assert sorted(perm.tolist()) == list(range(ref.n_out))
+        key = (mask[perm] >> np.uint64(lo)) & np.uint64((1 << (hi - lo)) - 1)
+        assert (np.diff(key.astype(np.int64)) >= 0).all()
+        same = np.diff(key.astype(np.int64)) == 0
+        assert (np.diff(perm)[same] > 0).all()
+
+
+@pytest.mark.parametrize("n_split", [0, 1, 2, 3])
+def test_mac_units_match_oracle_model(sp, cloud, n_split):
+    c, ref = cloud
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    ex, eff = km.mac_units(sp.OP_FWD, _cfg(sp, n_split))
+    assert (ex, eff) == oc.redundancy(ref.M, 16, n_split)
+
+
+def test_results_are_reproducible(sp, cloud):
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 61)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    for cfg in (_cfg(sp, 0), _cfg(sp, 2)):
+        assert torch.equal(sp.fwd(x, w, km, cfg), sp.fwd(x, w, km, cfg))
+    assert torch.equal(sp.wgrad(x, g, km), sp.wgrad(x, g, km))
+
+
+def test_tune_returns_a_valid_config(sp, cloud):
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 71)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    for op in (sp.OP_FWD, sp.OP_DGRAD, sp.OP_WGRAD):
+        best, us = sp.tune(km, 64, 64, torch.float16, op, 4)
+        assert us > 0
+        assert 0 <= best.n_split <= 4
+    best, _ = sp.tune(km, 64, 64, torch.float16, sp.OP_FWD, 1)
+    assert norm_err(sp.fwd(x, w, km, best), oc.forward(x32, w32, ref.M)) <= TOL["f16"]

@@ -1,0 +1,110 @@
+"""Kernel maps built by the HIP library against the oracle: bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sparse_conv as oc
+from workloads import generators as gen
+from _util import coords_dev
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import paper_2311_12862_amd as sp
+    return sp
+
+
+def _check_kmap(sp, c, K, stride, transposed):
+    ref = oc.build_kmap(c, K, stride, transposed)
+    km = sp.build_kmap(coords_dev(c), K, stride, transposed)
+    assert (km.n_in, km.n_out) == (ref.n_in, ref.n_out)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    np.testing.assert_array_equal(km.out_coords().cpu().numpy(), ref.out_coords)
+    np.testing.assert_array_equal(km.in_coords().cpu().numpy(), ref.in_coords)
+    mask = km.export_mask().cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(mask, oc.bitmask(ref.M))
+    assert km.n_pairs() == int((ref.M >= 0).sum())
+    km.destroy()
+    return ref
+
+
+@pytest.mark.parametrize("n,grid,lo", [(2000, 64, 0), (3000, 16, -8), (777, 9, 100)])
+def test_submanifold(sp, n, grid, lo):
+    c = gen.uniform_cloud(n, grid, seed=n, lo=lo)
+    c[: n // 3, 0] = 2
+    _check_kmap(sp, c, 3, 1, False)
+
+
+@pytest.mark.parametrize("stride", [2, 3])
+@pytest.mark.parametrize("lo", [0, -7])
+def test_strided(sp, stride, lo):
+    c = gen.uniform_cloud(4000, 20, seed=17 + stride, lo=lo)
+    c[:1500, 0] = 1
+    ref = _check_kmap(sp, c, 3, stride, False)
+    assert ref.n_out < 4000
+
+
+@pytest.mark.parametrize("stride", [1, 2])
+def test_transposed(sp, stride):
+    c = gen.uniform_cloud(3500, 18, seed=23, lo=-5)
+    c[:1000, 0] = 3
+    _check_kmap(sp, c, 3, stride, True)
+
+
+def test_k1(sp):
+    c = gen.uniform_cloud(1000, 12, seed=5)
+    _check_kmap(sp, c, 1, 1, False)
+    _check_kmap(sp, c, 1, 2, False)
+
+
+def test_lidar_scene_small(sp):
+    c = gen.lidar_scene(2000, target_n=20_000)
+    _check_kmap(sp, c, 3, 1, False)
+    _check_kmap(sp, c, 3, 2, False)
+
+
+def test_empty_single_and_limits(sp):
+    km = sp.build_kmap(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
+    assert (km.n_in, km.n_out, km.n_pairs()) == (0, 0, 0)
+    assert km.export().shape == (0, 27)
+    km.destroy()
+    _check_kmap(sp, np.array([[0, 5, -3, 7]], dtype=np.int32), 3, 1, False)
+    _check_kmap(sp, np.array([[0, 5, -3, 7]], dtype=np.int32), 3, 2, False)
+    lim = np.array([[65534, 32767, 32767, 32767], [65534, 32766, 32767, 32766], [0, -32768, -32768, -32768],
+                    [0, -32767, -32768, -32768], [0, -32768, 32767, 0]], dtype=np.int32)
+    _check_kmap(sp, lim, 3, 1, False)
+    _check_kmap(sp, lim, 3, 2, False)
+    _check_kmap(sp, lim, 3, 2, True)
+
+
+def test_errors(sp):
+    c = gen.uniform_cloud(500, 10, seed=1)
+    dup = c.copy()
+    dup[100] = dup[400]
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(dup), 3, 1)
+    assert e.value.status == -3
+    with pytest.raises(ValueError):
+        oc.build_kmap(dup, 3, 1)
+    for bad in ([0, 32768, 0, 0], [0, 0, -32769, 0], [65535, 0, 0, 0], [-1, 0, 0, 0]):
+        r = c.copy()
+        r[7] = bad
+        with pytest.raises(sp.SpconvError) as e:
+            sp.build_kmap(coords_dev(r), 3, 1)
+        assert e.value.status == -2
+    for K, stride in ((2, 1), (5, 1), (3, 0), (3, 65)):
+        with pytest.raises(sp.SpconvError) as e:
+            sp.build_kmap(coords_dev(c), K, stride)
+        assert e.value.status == -1
+    # the library still works after the error paths
+    _check_kmap(sp, c, 3, 1, False)
+
+
+def test_build_is_deterministic(sp):
+    c = gen.uniform_cloud(5000, 24, seed=9)
+    a = sp.build_kmap(coords_dev(c), 3, 2)
+    b = sp.build_kmap(coords_dev(c), 3, 2)
+    assert torch.equal(a.export(), b.export())
+    assert torch.equal(a.out_coords(), b.out_coords())

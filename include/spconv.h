@@ -81,8 +81,16 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *               rows are visited in ascending order of that range's bitmask
  *               bits (stable), and for s > 1 the fp32 partial sums of the
  *               ranges are added by a reduction kernel.
- *   tile_m      output rows per workgroup: 64, 128 or 256 (0 = 128).
- *   tile_n      output channels per workgroup: 32, 64 or 128 (0 = chosen from C_out).
+ *   kernel      which fwd / dgrad kernel runs (F16 / BF16 only):
+ *               1: weights of a split resident in LDS, one wave per 16-row
+ *                  block (needs reduced channels <= 128 and the split's
+ *                  weight slices for tile_n channels to fit in LDS, else
+ *                  SPCONV_EINVAL); tile_m is ignored;
+ *               2: workgroup tiles of tile_m rows, weights streamed per offset;
+ *               0: 1 if it fits, else 2.
+ *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 128).
+ *   tile_n      output channels per workgroup: 16, 32, 64 (kernel 1) or 32, 64,
+ *               128 (kernel 2); 0 = chosen from the channel counts.
  *   wgrad_pairs target number of (output,input) pairs per wgrad workgroup
  *               (0 = chosen from the pair count); ignored by fwd / dgrad.
  */
@@ -91,7 +99,8 @@ typedef struct spconv_config {
   int32_t tile_m;
   int32_t tile_n;
   int32_t wgrad_pairs;
-  int32_t reserved[4];
+  int32_t kernel;
+  int32_t reserved[3];
 } spconv_config;
 
 /* Kernel-map construction ("mapping operations", Sections 3.1, 4.2, 6.2).

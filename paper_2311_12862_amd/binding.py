@@ -26,11 +26,11 @@ class SpconvError(RuntimeError):
 class Config(C.Structure):
     """Mirror of spconv_config (zero = library defaults)."""
     _fields_ = [("n_split", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
-                ("wgrad_pairs", C.c_int32), ("reserved", C.c_int32 * 4)]
+                ("wgrad_pairs", C.c_int32), ("kernel", C.c_int32), ("reserved", C.c_int32 * 3)]
 
     def __repr__(self):
         return (f"Config(n_split={self.n_split}, tile_m={self.tile_m}, tile_n={self.tile_n}, "
-                f"wgrad_pairs={self.wgrad_pairs})")
+                f"wgrad_pairs={self.wgrad_pairs}, kernel={self.kernel})")
 
 
 _LIB = None

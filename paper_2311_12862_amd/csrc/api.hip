@@ -109,9 +109,12 @@ int resolve_config(const spconv_config* cfg, spconv_dtype dtype, spconv_config* 
   if (c.n_split < 0 || c.n_split > kMaxSplit) return SPCONV_EINVAL;
   if (c.tile_m == 0) c.tile_m = 128;
   if (c.tile_m != 64 && c.tile_m != 128 && c.tile_m != 256) return SPCONV_EINVAL;
-  if (c.tile_n != 0 && c.tile_n != 32 && c.tile_n != 64 && c.tile_n != 128) return SPCONV_EINVAL;
-  if (c.wgrad_pairs < 0) return SPCONV_EINVAL;
-  if (dtype == SPCONV_F32) c.tile_m = 64;  // the fp32 kernel has one tile shape
+  if (c.tile_n != 0 && c.tile_n != 16 && c.tile_n != 32 && c.tile_n != 64 && c.tile_n != 128) return SPCONV_EINVAL;
+  if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 2) return SPCONV_EINVAL;
+  if (dtype == SPCONV_F32) {  // the fp32 kernel has one tile shape
+    c.tile_m = 64;
+    c.kernel = 2;
+  }
   *out = c;
   return SPCONV_OK;
 }
@@ -154,8 +157,15 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   SPC_TRY(resolve_config(cfg, dtype, &c));
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
+  const int c_red = os.dgrad ? C_out : C_in;
+  bool wave = false;
+  if (c.kernel != 2) {
+    wave = igemm_wave_pick_bn(km->V, c.n_split, c_red, os.dgrad ? C_in : C_out, c.tile_n, nullptr) > 0;
+    if (!wave && c.kernel == 1) return SPCONV_EINVAL;
+  }
+  if (!wave && c.tile_n == 16) return SPCONV_EINVAL;
   IgemmPlan* plan = nullptr;
-  SPC_TRY(plan_get(km, *os.side, c.n_split, c.tile_m, st, &plan));
+  SPC_TRY(plan_get(km, *os.side, c.n_split, wave ? 16 : c.tile_m, st, &plan));
   IgemmArgs a{};
   a.feats = src;
   a.weights = weights;
@@ -170,11 +180,11 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
     SPC_TRY(km->scratch.reserve((size_t)plan->parts * plan->rows * c_dst * sizeof(float)));
     a.partial = km->scratch.as<float>();
     a.out = nullptr;
-    SPC_TRY(igemm_run(km, *os.side, *plan, a, st));
+    SPC_TRY(wave ? igemm_wave_run(km, *os.side, *plan, a, st) : igemm_run(km, *os.side, *plan, a, st));
     return split_reduce(a.partial, plan->parts, plan->rows, c_dst, dtype, dst, st);
   }
   a.out = dst;
-  return igemm_run(km, *os.side, *plan, a, st);
+  return wave ? igemm_wave_run(km, *os.side, *plan, a, st) : igemm_run(km, *os.side, *plan, a, st);
 }
 
 }  // namespace
@@ -251,7 +261,7 @@ SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_c
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
-  return plan_get(km, *os.side, c.n_split, c.tile_m, st, &plan);
+  return plan_get(km, *os.side, c.n_split, c.kernel == 1 ? 16 : c.tile_m, st, &plan);
 }
 
 SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
@@ -357,13 +367,26 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
     }
   } else {
     const int tiles[3] = {64, 128, 256};
-    for (int s = 0; s <= kMaxSplit; ++s)
+    const int c_red = op == SPCONV_OP_DGRAD ? C_out : C_in, c_dst = op == SPCONV_OP_DGRAD ? C_in : C_out;
+    for (int s = 0; s <= kMaxSplit; ++s) {
       for (int t = 0; t < (dtype == SPCONV_F32 ? 1 : 3); ++t) {
         spconv_config c{};
         c.n_split = s;
         c.tile_m = tiles[t];
+        c.kernel = 2;
         cands.push_back(c);
       }
+      if (dtype == SPCONV_F32) continue;
+      for (int tn : {64, 32, 16}) {
+        if (tn >= 2 * c_dst && tn > 16) continue;
+        if (igemm_wave_pick_bn(km->V, s, c_red, c_dst, tn, nullptr) == 0) continue;
+        spconv_config c{};
+        c.n_split = s;
+        c.kernel = 1;
+        c.tile_n = tn;
+        cands.push_back(c);
+      }
+    }
   }
   int status = SPCONV_OK;
   float best_t = 1e30f;

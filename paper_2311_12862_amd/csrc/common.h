@@ -148,6 +148,10 @@ struct IgemmArgs {
 };
 int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
               hipStream_t st);
+// ---- igemm_wave.hip (weights resident in LDS; plan tile_m must be 16)
+int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int* waves_out);
+int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
+                   hipStream_t st);
 int split_reduce(const float* partial, int parts, int64_t rows, int c, spconv_dtype dtype, void* out,
                  hipStream_t st);
 

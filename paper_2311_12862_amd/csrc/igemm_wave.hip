@@ -1,0 +1,365 @@
+// Implicit-GEMM forward / input-gradient for small channel counts: weights
+// resident in LDS, one wave per 16-row block, no workgroup barriers in the loop.
+//
+// At 64 channels the layer is bound by memory latency, not by the matrix
+// cores, so this kernel is organised around keeping loads in flight rather
+// than around large MFMA tiles:
+//   * the weight slices of all offsets of this part (Section 4.1's split) for
+//     BN output channels stay in the CU's 160 KB LDS for the life of the
+//     workgroup (stored reduction-index-contiguous, 16-byte chunks XOR-swizzled
+//     so that fragment reads do not collide on banks);
+//   * each wave owns whole 16-row blocks of the (possibly bitmask-sorted) map;
+//     a lane fetches its MFMA A-fragment (8 consecutive channels of one
+//     gathered row) straight from global memory into registers, predicated on
+//     the neighbour being present, several offsets ahead of the MFMAs that
+//     consume it;
+//   * offsets whose bit is clear in the block's mask are skipped: the lock-step
+//     unit of Section 2.2.3 is the 16-row block;
+//   * the block's map rows are staged in a per-wave LDS slab (the hoisted
+//     addressing of Section 3.2), and output rows leave through the same slab
+//     as whole 16-byte segments.
+#include "common.h"
+
+#include <algorithm>
+
+namespace spc {
+namespace {
+
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+template <typename T> struct MfmaW;
+template <> struct MfmaW<_Float16> {
+  static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                  0);
+  }
+};
+template <> struct MfmaW<__bf16> {
+  static __device__ __forceinline__ f32x4 run(uint4 a, uint4 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
+  }
+};
+
+struct WaveParams {
+  const void* feats;
+  const void* weights;
+  void* out;
+  float* partial;
+  const int* map[kMaxSplit];
+  const int* perm[kMaxSplit];
+  const unsigned* blkmask[kMaxSplit];
+  int lo[kMaxSplit], width[kMaxSplit];
+  long long rows, n_blocks;
+  int parts, V;
+  int c_red, c_out;
+  int C_in, C_out;
+  int dgrad, mirror;
+  int slab_bytes;  // per-wave LDS slab (map rows, then output staging)
+};
+
+// physical 16-byte chunk of logical chunk q in weight row n (row pitch = 4*KS chunks)
+template <int KS> __device__ __forceinline__ int swz(int q, int n) {
+  if ((4 * KS) % 8 == 0) return (q & ~7) | ((q ^ n) & 7);
+  return (q & ~3) | ((q ^ (n >> 1)) & 3);
+}
+
+constexpr int kDepth = 4;  // offsets whose A-fragments are in flight per wave
+
+template <typename T, int KS, int NB>
+__global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
+  constexpr int BN = NB * 16;
+  constexpr int ROW_CHUNKS = 4 * KS;        // 16-byte chunks per weight row
+  constexpr int ROW_HALFS = 32 * KS;
+  extern __shared__ __align__(16) unsigned char smem[];
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int n_waves = blockDim.x >> 6;
+  const int part = blockIdx.z;
+  const int n0 = blockIdx.y * BN;
+  const int width = p.width[part], lo = p.lo[part];
+  const int c_red = p.c_red, c_out = p.c_out;
+  const unsigned short* feats = reinterpret_cast<const unsigned short*>(p.feats);
+  const unsigned short* wts = reinterpret_cast<const unsigned short*>(p.weights);
+
+  unsigned short* Ws = reinterpret_cast<unsigned short*>(smem);  // [width][BN][ROW_HALFS] swizzled
+  unsigned char* slab = smem + (size_t)width * BN * ROW_HALFS * 2 + (size_t)wave * p.slab_bytes;
+  int* mapW = reinterpret_cast<int*>(slab);
+
+  // ---- weights of this part -> LDS (once per workgroup)
+  {
+    const long long slice = (long long)p.C_in * p.C_out;
+    if (p.dgrad) {
+      // B[kk = co][n = ci] = W[k][ci][co]: rows of W are already reduction-contiguous
+      const int chunks = width * BN * ROW_CHUNKS;
+      for (int e = tid; e < chunks; e += blockDim.x) {
+        const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
+        const int k = lo + c;
+        const int ci = n0 + n, co = q * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ci < p.C_in && co < p.C_out)
+          v = *reinterpret_cast<const uint4*>(wts + (long long)(p.mirror ? p.V - 1 - k : k) * slice +
+                                              (long long)ci * p.C_out + co);
+        *reinterpret_cast<uint4*>(Ws + ((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(q, n)) * 8) = v;
+      }
+    } else {
+      // B[kk = ci][n = co] = W[k][ci][co]: read 8 output channels of one ci, scatter transposed
+      const int vecs = width * ROW_HALFS * (BN / 8);
+      for (int e = tid; e < vecs; e += blockDim.x) {
+        const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
+        const int k = lo + c;
+        const int ci = kk, co = n0 + ng * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (ci < p.C_in && co < p.C_out)
+          v = *reinterpret_cast<const uint4*>(wts + (long long)(p.mirror ? p.V - 1 - k : k) * slice +
+                                              (long long)ci * p.C_out + co);
+        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int n = ng * 8 + i;
+          const unsigned short h = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu));
+          Ws[((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(kk >> 3, n)) * 8 + (kk & 7)] = h;
+        }
+      }
+    }
+  }
+  __syncthreads();
+
+  const int arow = lane & 15, aq = lane >> 4;  // fragment row and 8-channel group within a k-step
+  const long long wave_global = (long long)blockIdx.x * n_waves + wave;
+  const long long wave_stride = (long long)gridDim.x * n_waves;
+  const int map_vecs = (16 * width + 63) / 64;
+
+  for (long long b = wave_global; b < p.n_blocks; b += wave_stride) {
+    const long long row0 = b * 16;
+    const unsigned bm = __builtin_amdgcn_readfirstlane(p.blkmask[part][b]);
+    {  // the block's map rows: contiguous 16*width ints
+      const int* mp = p.map[part] + row0 * width;
+      for (int i = 0; i < map_vecs; ++i) {
+        const int e = lane + 64 * i;
+        if (e < 16 * width) mapW[e] = mp[e];
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
+
+    f32x4 acc[NB];
+#pragma unroll
+    for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    uint4 fr[kDepth][KS];
+    int cc[kDepth];
+    unsigned m = bm;
+
+    auto issue = [&](int s) {
+      if (m) {
+        const int c = __ffs((int)m) - 1;
+        m &= m - 1;
+        cc[s] = c;
+        const int idx = mapW[arow * width + c];
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+          const int col = (ks * 4 + aq) * 8;
+          uint4 v = make_uint4(0, 0, 0, 0);
+          if (idx >= 0 && col < c_red) v = *reinterpret_cast<const uint4*>(feats + (long long)idx * c_red + col);
+          fr[s][ks] = v;
+        }
+      } else {
+        cc[s] = -1;
+      }
+    };
+    auto consume = [&](int s) {
+      const unsigned short* wrow = Ws + (size_t)(cc[s] * BN + arow) * ROW_HALFS;
+#pragma unroll
+      for (int ks = 0; ks < KS; ++ks) {
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int n = nb * 16 + arow;
+          const uint4 bf = *reinterpret_cast<const uint4*>(wrow + (size_t)nb * 16 * ROW_HALFS +
+                                                           swz<KS>(ks * 4 + aq, n) * 8);
+          acc[nb] = MfmaW<T>::run(fr[s][ks], bf, acc[nb]);
+        }
+      }
+    };
+
+#pragma unroll
+    for (int s = 0; s < kDepth; ++s) issue(s);
+    bool live = true;
+    while (live) {
+#pragma unroll
+      for (int s = 0; s < kDepth; ++s) {
+        if (cc[s] < 0) {
+          live = false;
+          break;
+        }
+        consume(s);
+        issue(s);
+      }
+    }
+
+    // ---- output rows
+    int orow = -1;
+    if (lane < 16) {
+      const long long g = row0 + lane;
+      const int* pm = p.perm[part];
+      orow = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+    }
+    if (p.parts > 1) {
+      // fp32 partial sums: lane holds rows 4*(lane/16)+r, column lane%16 of each 16-column block
+      int o4[4];
+#pragma unroll
+      for (int r = 0; r < 4; ++r) o4[r] = __shfl(orow, aq * 4 + r);
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        if (o4[r] < 0) continue;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const int col = n0 + nb * 16 + arow;
+          if (col < c_out) p.partial[((long long)part * p.rows + o4[r]) * c_out + col] = acc[nb][r];
+        }
+      }
+    } else {
+      // stage the 16 x BN tile in the slab (the map rows are no longer needed), then
+      // write whole 16-byte segments of each output row
+      __builtin_amdgcn_wave_barrier();
+      T* stage = reinterpret_cast<T*>(slab);
+#pragma unroll
+      for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) stage[(aq * 4 + r) * BN + nb * 16 + arow] = (T)acc[nb][r];
+      __builtin_amdgcn_wave_barrier();
+      constexpr int SEGS = BN / 8;  // 16-byte segments per staged row
+#pragma unroll
+      for (int i = 0; i < (16 * SEGS + 63) / 64; ++i) {
+        const int e = lane + 64 * i;
+        const int r = e / SEGS, sg = e % SEGS;
+        const int o = __shfl(orow, r & 15);
+        if (e < 16 * SEGS && o >= 0 && n0 + sg * 8 < c_out)
+          *reinterpret_cast<uint4*>(reinterpret_cast<T*>(p.out) + (long long)o * c_out + n0 + sg * 8) =
+              *reinterpret_cast<const uint4*>(stage + r * BN + sg * 8);
+      }
+      __builtin_amdgcn_wave_barrier();
+    }
+  }
+}
+
+template <typename T, int KS, int NB>
+int launch_wave(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+  static size_t attr_bytes = 0;
+  auto fn = k_igemm_wave<T, KS, NB>;
+  if (smem > attr_bytes) {
+    SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)smem));
+    attr_bytes = smem;
+  }
+  hipLaunchKernelGGL(fn, grid, dim3(threads), smem, st, p);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+template <typename T, int KS>
+int launch_wave_nb(int nb, const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+  switch (nb) {
+    case 1: return launch_wave<T, KS, 1>(p, grid, threads, smem, st);
+    case 2: return launch_wave<T, KS, 2>(p, grid, threads, smem, st);
+    case 4: return launch_wave<T, KS, 4>(p, grid, threads, smem, st);
+  }
+  return SPCONV_EINVAL;
+}
+
+template <typename T>
+int launch_wave_ks(int ks, int nb, const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+  switch (ks) {
+    case 1: return launch_wave_nb<T, 1>(nb, p, grid, threads, smem, st);
+    case 2: return launch_wave_nb<T, 2>(nb, p, grid, threads, smem, st);
+    case 3: return launch_wave_nb<T, 3>(nb, p, grid, threads, smem, st);
+    case 4: return launch_wave_nb<T, 4>(nb, p, grid, threads, smem, st);
+  }
+  return SPCONV_EINVAL;
+}
+
+constexpr size_t kLdsBudget = 160 * 1024;
+
+size_t slab_bytes_for(int max_width, int bn, int parts) {
+  size_t s = (size_t)16 * max_width * 4;
+  if (parts == 1) s = std::max(s, (size_t)16 * bn * 2);
+  return (size_t)round_up((int64_t)s, 16);
+}
+
+}  // namespace
+
+// Largest BN in {64, 32, 16} (or exactly tile_n) for which the weights of the widest part plus
+// the per-wave slabs of at least 8 waves fit in LDS; 0 if none does.
+int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int* waves_out) {
+  if (c_red > 128) return 0;
+  const int ks = (c_red + 31) / 32;
+  const int parts = std::max(1, n_split);
+  int max_width = 0;
+  for (int i = 0; i < parts; ++i) max_width = std::max(max_width, (i + 1) * V / parts - i * V / parts);
+  const int cands[3] = {64, 32, 16};
+  for (int bn : cands) {
+    if (tile_n != 0 && bn != tile_n) continue;
+    if (tile_n == 0 && bn > 16 && bn >= 2 * c_out) continue;  // no point in a tile twice as wide as the layer
+    const size_t w = (size_t)max_width * bn * ks * 64;
+    const size_t slab = slab_bytes_for(max_width, bn, parts);
+    for (int waves : {16, 8}) {
+      if (w + (size_t)waves * slab <= kLdsBudget) {
+        if (waves_out) *waves_out = waves;
+        return bn;
+      }
+    }
+  }
+  return 0;
+}
+
+int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
+                   hipStream_t st) {
+  if (plan.rows == 0) return SPCONV_OK;
+  if (plan.tile_m != 16 || a.dtype == SPCONV_F32) return SPCONV_EINVAL;
+  WaveParams p{};
+  p.feats = a.feats;
+  p.weights = a.weights;
+  p.out = a.out;
+  p.partial = a.partial;
+  p.rows = plan.rows;
+  p.n_blocks = plan.n_tiles;
+  p.parts = plan.parts;
+  p.V = km->V;
+  p.C_in = a.C_in;
+  p.C_out = a.C_out;
+  p.dgrad = a.dgrad;
+  p.mirror = a.mirror;
+  p.c_red = a.dgrad ? a.C_out : a.C_in;
+  p.c_out = a.dgrad ? a.C_in : a.C_out;
+  int waves = 8;
+  const int bn = igemm_wave_pick_bn(km->V, plan.n_split, p.c_red, p.c_out, a.tile_n, &waves);
+  if (bn == 0) return SPCONV_EINVAL;
+  const int ks = (p.c_red + 31) / 32;
+  int max_width = 0;
+  const int64_t tiles_alloc = plan.n_tiles > 0 ? plan.n_tiles : 1;
+  for (int i = 0; i < plan.parts; ++i) {
+    p.lo[i] = plan.lo[i];
+    p.width[i] = plan.width[i];
+    max_width = std::max(max_width, plan.width[i]);
+    p.blkmask[i] = plan.tilemask.as<unsigned>() + (size_t)i * tiles_alloc;
+    if (plan.n_split == 0) {
+      p.map[i] = side.map.as<int>();
+      p.perm[i] = nullptr;
+    } else {
+      p.map[i] = plan.maps.as<int>() + plan.map_off[i];
+      p.perm[i] = plan.perm.as<int>() + (size_t)i * plan.rows_pad;
+    }
+  }
+  p.slab_bytes = (int)slab_bytes_for(max_width, bn, plan.parts);
+  const size_t smem = (size_t)max_width * bn * ks * 64 + (size_t)waves * p.slab_bytes;
+  const int n_tiles_n = (int)ceil_div(p.c_out, bn);
+  // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block
+  int64_t per_slice = std::max<int64_t>(1, 256 / ((int64_t)n_tiles_n * plan.parts));
+  per_slice = std::min<int64_t>(per_slice, ceil_div(plan.n_tiles, waves));
+  dim3 grid((unsigned)per_slice, (unsigned)n_tiles_n, (unsigned)plan.parts);
+  if (a.dtype == SPCONV_F16) return launch_wave_ks<_Float16>(ks, bn / 16, p, grid, waves * 64, smem, st);
+  return launch_wave_ks<__bf16>(ks, bn / 16, p, grid, waves * 64, smem, st);
+}
+
+}  // namespace spc

@@ -23,9 +23,9 @@ def cloud():
     return c, oc.build_kmap(c, 3, 1)
 
 
-def _cfg(sp, n_split=0, tile_m=0, tile_n=0, wgrad_pairs=0):
+def _cfg(sp, n_split=0, tile_m=0, tile_n=0, wgrad_pairs=0, kernel=0):
     c = sp.Config()
-    c.n_split, c.tile_m, c.tile_n, c.wgrad_pairs = n_split, tile_m, tile_n, wgrad_pairs
+    c.n_split, c.tile_m, c.tile_n, c.wgrad_pairs, c.kernel = n_split, tile_m, tile_n, wgrad_pairs, kernel
     return c
 
 
@@ -43,25 +43,43 @@ def test_config1_tiny_fp32_forward(sp):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("c_in,c_out", [(64, 64), (32, 96), (96, 32), (8, 16), (128, 256), (256, 128)])
-def test_forward_channels(sp, cloud, dtype, c_in, c_out):
+@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("c_in,c_out", [(64, 64), (32, 96), (96, 32), (8, 16), (128, 256), (256, 128), (24, 40)])
+def test_forward_and_dgrad_channels(sp, cloud, dtype, kernel, c_in, c_out):
     c, ref = cloud
-    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 5)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 5)
     km = sp.build_kmap(coords_dev(c), 3, 1)
-    want = oc.forward(x32, w32, ref.M)
-    got = sp.fwd(x, w, km)
-    assert norm_err(got, want) <= TOL[dtype]
+    for n_split in (0, 3):
+        cfg = _cfg(sp, n_split, kernel=kernel)
+        if kernel == 1 and c_in > 128:     # the LDS-resident kernel reduces over at most 128 channels
+            with pytest.raises(sp.SpconvError) as e:
+                sp.fwd(x, w, km, cfg)
+            assert e.value.status == -1
+        else:
+            assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL[dtype]
+        if kernel == 1 and c_out > 128:
+            with pytest.raises(sp.SpconvError):
+                sp.dgrad(g, w, km, cfg)
+        else:
+            assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL[dtype]
 
 
 @pytest.mark.parametrize("n_split", [0, 1, 2, 3, 4])
-@pytest.mark.parametrize("tile_m", [64, 128, 256])
-def test_forward_design_space(sp, cloud, n_split, tile_m):
+@pytest.mark.parametrize("kernel,tile_m,tile_n", [(2, 64, 0), (2, 128, 0), (2, 256, 0), (1, 0, 16), (1, 0, 32), (1, 0, 64)])
+def test_forward_design_space(sp, cloud, n_split, kernel, tile_m, tile_n):
     """Sorting and splitting change the work, never the result (Sections 2.2.3, 4.1)."""
     c, ref = cloud
     (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 6)
     km = sp.build_kmap(coords_dev(c), 3, 1)
     want = oc.forward(x32, w32, ref.M)
-    got = sp.fwd(x, w, km, _cfg(sp, n_split, tile_m))
+    cfg = _cfg(sp, n_split, tile_m, tile_n, kernel=kernel)
+    if kernel == 1 and tile_n == 64 and n_split < 2:
+        # 27 offsets x 64 x 64 fp16 weights do not fit in LDS: the call must refuse, not fall back
+        with pytest.raises(sp.SpconvError) as e:
+            sp.fwd(x, w, km, cfg)
+        assert e.value.status == -1
+        return
+    got = sp.fwd(x, w, km, cfg)
     assert norm_err(got, want) <= TOL["f16"]
     np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
 
@@ -71,7 +89,7 @@ def test_forward_tile_n(sp, cloud, tile_n):
     c, ref = cloud
     (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 96, 27, "bf16", 7)
     km = sp.build_kmap(coords_dev(c), 3, 1)
-    got = sp.fwd(x, w, km, _cfg(sp, 1, 128, tile_n))
+    got = sp.fwd(x, w, km, _cfg(sp, 1, 128, tile_n, kernel=2))
     assert norm_err(got, oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
 
 
@@ -85,9 +103,10 @@ def test_fwd_dgrad_wgrad_all_map_kinds(sp, dtype, stride, transposed):
     km = sp.build_kmap(coords_dev(c), 3, stride, transposed)
     np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
     for n_split in (0, 1, 3):
-        cfg = _cfg(sp, n_split)
-        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL[dtype]
-        assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL[dtype]
+        for kernel in ((2,) if dtype == "f32" else (1, 2)):
+            cfg = _cfg(sp, n_split, kernel=kernel)
+            assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL[dtype]
+            assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL[dtype]
     dw = sp.wgrad(x, g, km)
     assert dw.dtype == torch.float32
     # dW is produced in fp32 from exactly representable inputs: only the summation order differs

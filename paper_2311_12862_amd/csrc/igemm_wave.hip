@@ -21,6 +21,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <cstdlib>
 
 namespace spc {
 namespace {
@@ -57,7 +58,9 @@ struct WaveParams {
   int c_red, c_out;
   int C_in, C_out;
   int dgrad, mirror;
-  int slab_bytes;  // per-wave LDS slab (map rows, then output staging)
+  int slab_bytes;  // per-wave LDS slab: map rows, then the output staging tile
+  int map_bytes;   // size of the map part of the slab
+  unsigned feats_bytes;  // size of the gathered tensor, < 2^32 - 16 KiB
 };
 
 // physical 16-byte chunk of logical chunk q in weight row n (row pitch = 4*KS chunks)
@@ -66,10 +69,26 @@ template <int KS> __device__ __forceinline__ int swz(int q, int n) {
   return (q & ~3) | ((q ^ (n >> 1)) & 3);
 }
 
-constexpr int kDepth = 4;  // offsets whose A-fragments are in flight per wave
 
-template <typename T, int KS, int NB>
-__global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer descriptor over [base, base + bytes): loads beyond the end return zeros and touch
+// no memory, which turns "neighbour absent" (index -1) into an out-of-range offset instead of a
+// branch, so that every load is issued unconditionally and the wait counters stay countable.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+constexpr int kMapVecs = 7;  // ceil(16 rows * 27 offsets / 64 lanes)
+
+// DEPTH = offsets whose A-fragments are in flight per wave.  DEPTH 8 needs more than the 128
+// registers a 16-wave workgroup leaves per lane, so it runs with 8 waves.
+template <typename T, int KS, int NB, int DEPTH>
+__global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const WaveParams p) {
   constexpr int BN = NB * 16;
   constexpr int ROW_CHUNKS = 4 * KS;        // 16-byte chunks per weight row
   constexpr int ROW_HALFS = 32 * KS;
@@ -77,98 +96,146 @@ __global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n_waves = blockDim.x >> 6;
+  const int arow = lane & 15, aq = lane >> 4;  // fragment row and 8-channel group within a k-step
   const int part = blockIdx.z;
   const int n0 = blockIdx.y * BN;
   const int width = p.width[part], lo = p.lo[part];
   const int c_red = p.c_red, c_out = p.c_out;
-  const unsigned short* feats = reinterpret_cast<const unsigned short*>(p.feats);
-  const unsigned short* wts = reinterpret_cast<const unsigned short*>(p.weights);
 
   unsigned short* Ws = reinterpret_cast<unsigned short*>(smem);  // [width][BN][ROW_HALFS] swizzled
   unsigned char* slab = smem + (size_t)width * BN * ROW_HALFS * 2 + (size_t)wave * p.slab_bytes;
   int* mapW = reinterpret_cast<int*>(slab);
 
-  // ---- weights of this part -> LDS (once per workgroup)
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 2));
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
+
+  const long long wave_global = (long long)blockIdx.x * n_waves + wave;
+  const long long wave_stride = (long long)gridDim.x * n_waves;
+  const bool has_work = wave_global < p.n_blocks;
+  const unsigned row_bytes = (unsigned)c_red * 2u;
+  const int map_len = 16 * width;
+  const int* map_part = p.map[part];
+  const int* pm = p.perm[part];
+  const unsigned* bmask = p.blkmask[part];
+  T* stage = reinterpret_cast<T*>(slab + p.map_bytes);
+
+  // registers holding the next block's map rows, mask and output rows
+  int mreg[kMapVecs];
+  unsigned bm_next = 0;
+  int orow_next = -1;
+  auto prefetch_block = [&](long long b) {
+    const int* mp = map_part + b * map_len;
+#pragma unroll
+    for (int i = 0; i < kMapVecs; ++i) {
+      const int e = lane + 64 * i;
+      mreg[i] = mp[e < map_len ? e : map_len - 1];
+    }
+    bm_next = bmask[b];
+    const long long g = b * 16 + arow;
+    orow_next = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+  };
+
+  uint4 fr[DEPTH][KS];
+  int cc[DEPTH];
+  unsigned m = 0;
+  // Always issues KS loads: with no offset left they are out-of-range loads (zeros, no traffic).
+  auto issue = [&](int s) {
+    const int c = m ? __ffs((int)m) - 1 : -1;
+    m &= m - 1;  // 0 stays 0
+    cc[s] = c;
+    const int idx = mapW[arow * width + (c < 0 ? 0 : c)];
+    const unsigned base = (unsigned)idx * row_bytes;  // idx = -1 wraps to just below 2^32: out of range
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+      const unsigned col = (unsigned)(ks * 4 + aq) * 8u;
+      const bool ok = c >= 0 && col < (unsigned)c_red;
+      fr[s][ks] = buf_load16(x_rsrc, ok ? base + col * 2u : 0xFFFFFFFFu);
+    }
+  };
+  // Publishes the prefetched block in the wave's slab and puts its first DEPTH offsets in flight.
+  auto start_block = [&](long long b_next_next) {
+#pragma unroll
+    for (int i = 0; i < kMapVecs; ++i) {
+      const int e = lane + 64 * i;
+      if (e < map_len) mapW[e] = mreg[i];
+    }
+    m = __builtin_amdgcn_readfirstlane(bm_next);
+    prefetch_block(b_next_next < p.n_blocks ? b_next_next : p.n_blocks - 1);
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int s = 0; s < DEPTH; ++s) issue(s);
+  };
+
+  // the first block's map rows travel while the weights are being staged
+  if (has_work) prefetch_block(wave_global);
+
+  // ---- weights of this part -> LDS (once per workgroup), four loads in flight per thread
   {
-    const long long slice = (long long)p.C_in * p.C_out;
+    const unsigned slice = (unsigned)(p.C_in * p.C_out * 2);
     if (p.dgrad) {
       // B[kk = co][n = ci] = W[k][ci][co]: rows of W are already reduction-contiguous
       const int chunks = width * BN * ROW_CHUNKS;
-      for (int e = tid; e < chunks; e += blockDim.x) {
-        const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
-        const int k = lo + c;
-        const int ci = n0 + n, co = q * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (ci < p.C_in && co < p.C_out)
-          v = *reinterpret_cast<const uint4*>(wts + (long long)(p.mirror ? p.V - 1 - k : k) * slice +
-                                              (long long)ci * p.C_out + co);
-        *reinterpret_cast<uint4*>(Ws + ((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(q, n)) * 8) = v;
+      for (int e0 = tid; e0 < chunks; e0 += 4 * blockDim.x) {
+        uint4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * blockDim.x;
+          const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
+          const int k = lo + c;
+          const int ci = n0 + n, co = q * 8;
+          const bool ok = e < chunks && ci < p.C_in && co < p.C_out;
+          const unsigned off = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice + (unsigned)(ci * p.C_out + co) * 2u;
+          v[u] = buf_load16(w_rsrc, ok ? off : 0xFFFFFFFFu);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * blockDim.x;
+          const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
+          if (e < chunks)
+            *reinterpret_cast<uint4*>(Ws + ((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(q, n)) * 8) = v[u];
+        }
       }
     } else {
       // B[kk = ci][n = co] = W[k][ci][co]: read 8 output channels of one ci, scatter transposed
       const int vecs = width * ROW_HALFS * (BN / 8);
-      for (int e = tid; e < vecs; e += blockDim.x) {
-        const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
-        const int k = lo + c;
-        const int ci = kk, co = n0 + ng * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (ci < p.C_in && co < p.C_out)
-          v = *reinterpret_cast<const uint4*>(wts + (long long)(p.mirror ? p.V - 1 - k : k) * slice +
-                                              (long long)ci * p.C_out + co);
-        const unsigned w[4] = {v.x, v.y, v.z, v.w};
+      for (int e0 = tid; e0 < vecs; e0 += 4 * blockDim.x) {
+        uint4 v[4];
 #pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          const int n = ng * 8 + i;
-          const unsigned short h = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu));
-          Ws[((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(kk >> 3, n)) * 8 + (kk & 7)] = h;
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * blockDim.x;
+          const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
+          const int k = lo + c;
+          const int ci = kk, co = n0 + ng * 8;
+          const bool ok = e < vecs && ci < p.C_in && co < p.C_out;
+          const unsigned off = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice + (unsigned)(ci * p.C_out + co) * 2u;
+          v[u] = buf_load16(w_rsrc, ok ? off : 0xFFFFFFFFu);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+          const int e = e0 + u * blockDim.x;
+          if (e >= vecs) continue;
+          const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
+          const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+          for (int i = 0; i < 8; ++i) {
+            const int n = ng * 8 + i;
+            const unsigned short h = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu));
+            Ws[((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(kk >> 3, n)) * 8 + (kk & 7)] = h;
+          }
         }
       }
     }
   }
-  __syncthreads();
-
-  const int arow = lane & 15, aq = lane >> 4;  // fragment row and 8-channel group within a k-step
-  const long long wave_global = (long long)blockIdx.x * n_waves + wave;
-  const long long wave_stride = (long long)gridDim.x * n_waves;
-  const int map_vecs = (16 * width + 63) / 64;
+  __syncthreads();  // weights visible
+  if (!has_work) return;
 
   for (long long b = wave_global; b < p.n_blocks; b += wave_stride) {
-    const long long row0 = b * 16;
-    const unsigned bm = __builtin_amdgcn_readfirstlane(p.blkmask[part][b]);
-    {  // the block's map rows: contiguous 16*width ints
-      const int* mp = p.map[part] + row0 * width;
-      for (int i = 0; i < map_vecs; ++i) {
-        const int e = lane + 64 * i;
-        if (e < 16 * width) mapW[e] = mp[e];
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-
+    const int orow_cur = orow_next;
+    start_block(b + wave_stride);
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    uint4 fr[kDepth][KS];
-    int cc[kDepth];
-    unsigned m = bm;
-
-    auto issue = [&](int s) {
-      if (m) {
-        const int c = __ffs((int)m) - 1;
-        m &= m - 1;
-        cc[s] = c;
-        const int idx = mapW[arow * width + c];
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          const int col = (ks * 4 + aq) * 8;
-          uint4 v = make_uint4(0, 0, 0, 0);
-          if (idx >= 0 && col < c_red) v = *reinterpret_cast<const uint4*>(feats + (long long)idx * c_red + col);
-          fr[s][ks] = v;
-        }
-      } else {
-        cc[s] = -1;
-      }
-    };
     auto consume = [&](int s) {
       const unsigned short* wrow = Ws + (size_t)(cc[s] * BN + arow) * ROW_HALFS;
 #pragma unroll
@@ -183,33 +250,24 @@ __global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
       }
     };
 
+    // The exits leave the loop directly (not through its latch), so that the wait-count
+    // bookkeeping at the loop head sees only the steady state: DEPTH - 1 slots in flight.
+    for (;;) {
 #pragma unroll
-    for (int s = 0; s < kDepth; ++s) issue(s);
-    bool live = true;
-    while (live) {
-#pragma unroll
-      for (int s = 0; s < kDepth; ++s) {
-        if (cc[s] < 0) {
-          live = false;
-          break;
-        }
+      for (int s = 0; s < DEPTH; ++s) {
+        if (cc[s] < 0) goto offsets_done;
         consume(s);
         issue(s);
       }
     }
+  offsets_done:
 
     // ---- output rows
-    int orow = -1;
-    if (lane < 16) {
-      const long long g = row0 + lane;
-      const int* pm = p.perm[part];
-      orow = pm ? pm[g] : (g < p.rows ? (int)g : -1);
-    }
     if (p.parts > 1) {
       // fp32 partial sums: lane holds rows 4*(lane/16)+r, column lane%16 of each 16-column block
       int o4[4];
 #pragma unroll
-      for (int r = 0; r < 4; ++r) o4[r] = __shfl(orow, aq * 4 + r);
+      for (int r = 0; r < 4; ++r) o4[r] = __shfl(orow_cur, aq * 4 + r);
 #pragma unroll
       for (int r = 0; r < 4; ++r) {
         if (o4[r] < 0) continue;
@@ -220,10 +278,7 @@ __global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
         }
       }
     } else {
-      // stage the 16 x BN tile in the slab (the map rows are no longer needed), then
-      // write whole 16-byte segments of each output row
-      __builtin_amdgcn_wave_barrier();
-      T* stage = reinterpret_cast<T*>(slab);
+      // stage the 16 x BN tile in the wave's slab, then write whole 16-byte segments of each row
 #pragma unroll
       for (int r = 0; r < 4; ++r)
 #pragma unroll
@@ -234,7 +289,7 @@ __global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
       for (int i = 0; i < (16 * SEGS + 63) / 64; ++i) {
         const int e = lane + 64 * i;
         const int r = e / SEGS, sg = e % SEGS;
-        const int o = __shfl(orow, r & 15);
+        const int o = __shfl(orow_cur, r & 15);
         if (e < 16 * SEGS && o >= 0 && n0 + sg * 8 < c_out)
           *reinterpret_cast<uint4*>(reinterpret_cast<T*>(p.out) + (long long)o * c_out + n0 + sg * 8) =
               *reinterpret_cast<const uint4*>(stage + r * BN + sg * 8);
@@ -244,10 +299,10 @@ __global__ void __launch_bounds__(1024) k_igemm_wave(const WaveParams p) {
   }
 }
 
-template <typename T, int KS, int NB>
-int launch_wave(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+template <typename T, int KS, int NB, int DEPTH>
+int launch_wave_d(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
   static size_t attr_bytes = 0;
-  auto fn = k_igemm_wave<T, KS, NB>;
+  auto fn = k_igemm_wave<T, KS, NB, DEPTH>;
   if (smem > attr_bytes) {
     SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
@@ -256,6 +311,12 @@ int launch_wave(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStr
   hipLaunchKernelGGL(fn, grid, dim3(threads), smem, st, p);
   SPC_LAUNCH_CHECK();
   return SPCONV_OK;
+}
+
+template <typename T, int KS, int NB>
+int launch_wave(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+  if (threads <= 512 && KS <= 2) return launch_wave_d<T, KS, NB, 8>(p, grid, threads, smem, st);
+  return launch_wave_d<T, KS, NB, 4>(p, grid, threads, smem, st);
 }
 
 template <typename T, int KS>
@@ -281,10 +342,10 @@ int launch_wave_ks(int ks, int nb, const WaveParams& p, dim3 grid, int threads, 
 
 constexpr size_t kLdsBudget = 160 * 1024;
 
+size_t map_bytes_for(int max_width) { return (size_t)round_up((int64_t)16 * max_width * 4, 16); }
+
 size_t slab_bytes_for(int max_width, int bn, int parts) {
-  size_t s = (size_t)16 * max_width * 4;
-  if (parts == 1) s = std::max(s, (size_t)16 * bn * 2);
-  return (size_t)round_up((int64_t)s, 16);
+  return map_bytes_for(max_width) + (parts == 1 ? (size_t)16 * bn * 2 : 0);
 }
 
 }  // namespace
@@ -303,7 +364,12 @@ int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int
     if (tile_n == 0 && bn > 16 && bn >= 2 * c_out) continue;  // no point in a tile twice as wide as the layer
     const size_t w = (size_t)max_width * bn * ks * 64;
     const size_t slab = slab_bytes_for(max_width, bn, parts);
+    static const int forced = [] {
+      const char* e = getenv("SPCONV_WAVES");  // developer knob: 8 or 16 waves per workgroup
+      return e ? atoi(e) : 0;
+    }();
     for (int waves : {16, 8}) {
+      if (forced && waves != forced) continue;
       if (w + (size_t)waves * slab <= kLdsBudget) {
         if (waves_out) *waves_out = waves;
         return bn;
@@ -332,6 +398,10 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
   p.mirror = a.mirror;
   p.c_red = a.dgrad ? a.C_out : a.C_in;
   p.c_out = a.dgrad ? a.C_in : a.C_out;
+  const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
+  const uint64_t feats_bytes = (uint64_t)rows_src * p.c_red * 2;
+  if (feats_bytes >= 0xFFFFC000ull) return SPCONV_EINVAL;  // buffer descriptors address 32 bits
+  p.feats_bytes = (unsigned)feats_bytes;
   int waves = 8;
   const int bn = igemm_wave_pick_bn(km->V, plan.n_split, p.c_red, p.c_out, a.tile_n, &waves);
   if (bn == 0) return SPCONV_EINVAL;
@@ -352,6 +422,7 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
     }
   }
   p.slab_bytes = (int)slab_bytes_for(max_width, bn, plan.parts);
+  p.map_bytes = (int)map_bytes_for(max_width);
   const size_t smem = (size_t)max_width * bn * ks * 64 + (size_t)waves * p.slab_bytes;
   const int n_tiles_n = (int)ceil_div(p.c_out, bn);
   // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block

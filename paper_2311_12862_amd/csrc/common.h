@@ -74,16 +74,18 @@ struct IgemmPlan {
 };
 
 struct WgradItem {
-  int32_t k, row_begin, row_end, slot;  // slot: index of the partial tile this item writes
+  int32_t k, pair_begin, pair_end, pad;  // pairs [pair_begin, pair_end) of offset k; item i writes partial tile i
 };
 
+// Weight-stationary view of the map for wgrad: the present pairs of each offset, compacted
+// in row order (the M_delta of Section 2.2.1), cut into work items of about target_pairs.
 struct WgradPlan {
   int64_t target_pairs = 0;
-  DevBuf map_k;   // int32 [V][rows_pad]  offset-major copy of M
-  DevBuf items;   // WgradItem [n_items]
-  DevBuf seg;     // int32 [V+1]: items of offset k are seg[k]..seg[k+1]
-  int n_items = 0;
-  int64_t counts[32] = {0};
+  int max_items = 0;  // launch bound: V + ceil(n_pairs / target_pairs)
+  DevBuf pairs;       // int2 [n_pairs]: (output row n, input row j), offset-major
+  DevBuf seg;         // int32 [V+1]: pairs of offset k are seg[k]..seg[k+1]
+  DevBuf items;       // WgradItem [max_items]
+  DevBuf item_seg;    // int32 [V+2]: items of offset k are item_seg[k]..item_seg[k+1]; [V+1] = n_items
 };
 
 struct SideMap {      // one output-stationary table: rows x V
@@ -122,6 +124,8 @@ int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or nu
 // result ended up (0: buffer a, 1: buffer b).  hist must hold
 // sort_hist_elems(n) uint32.
 size_t sort_hist_elems(int64_t n);
+// Exclusive scan in place (one workgroup; meant for up to a few hundred thousand counters).
+int scan_u32_inplace(uint32_t* data, int64_t elems, hipStream_t st);
 int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* val_b, int64_t n,
                    int key_bits, uint32_t* hist, hipStream_t st, int* in_b);
 // Keys only, 64-bit, on the digit positions whose bits are set in `varying`.

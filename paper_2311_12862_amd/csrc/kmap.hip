@@ -20,9 +20,13 @@ constexpr unsigned long long kEmpty = ~0ull;
 
 enum : unsigned long long { FLAG_RANGE = 1, FLAG_DUP = 2, FLAG_FULL = 4 };
 
-// ctl block layout (8 x u64): [0] flags, [1] unique counter, [2] OR of keys, [3] AND of keys
+// Control block read back by the host at the build's synchronisation point.  The pair counter
+// is spread over 64 cache lines (one atomic per probe workgroup) so that the adds do not queue
+// up on one address.
+constexpr int kPairSlots = 64;
 struct Ctl {
-  unsigned long long flags, count, key_or, key_and, pad[4];
+  unsigned long long flags, count, key_or, key_and, pad[12];
+  unsigned long long pairs[kPairSlots * 16];
 };
 
 __device__ __forceinline__ bool coord_ok(int b, int x, int y, int z) {
@@ -89,6 +93,7 @@ __global__ void k_ctl_init(Ctl* ctl) {
     ctl->key_or = 0;
     ctl->key_and = ~0ull;
   }
+  ctl->pairs[threadIdx.x * 16] = 0;  // launched with kPairSlots threads
 }
 
 // Insert key(p_j) -> j for every input row; flags range and duplicate errors.
@@ -181,7 +186,8 @@ __global__ void __launch_bounds__(256) k_assign_rank(const unsigned long long* _
 template <int K, bool TRANSPOSED>
 __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, int n_rows, int stride,
                                                const unsigned long long* __restrict__ tab, int log_cap,
-                                               int* __restrict__ map, unsigned* __restrict__ mask) {
+                                               int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl) {
+  __shared__ unsigned wave_pairs[4];
   constexpr int V = K * K * K;
   constexpr int RPW = 64 / V;
   constexpr int R = (K - 1) / 2;
@@ -212,6 +218,13 @@ __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, in
   }
   const unsigned long long bal = __ballot(found >= 0);
   if (active && k == 0) mask[row] = (unsigned)((bal >> (sub * V)) & ((1ull << V) - 1ull));
+  // number of present pairs: one atomic per workgroup
+  if (lane == 0) wave_pairs[threadIdx.x >> 6] = (unsigned)__popcll(bal);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
+    if (n) atomicAdd(&ctl->pairs[(blockIdx.x % kPairSlots) * 16], (unsigned long long)n);
+  }
 }
 
 // T[j][k] = n for every present pair M[n][k] = j.
@@ -270,17 +283,17 @@ inline unsigned blocks_for(int64_t n, int per_block) { return (unsigned)ceil_div
 
 template <int K>
 int launch_probe(bool transposed, const int4* rows, int64_t n_rows, int stride, const unsigned long long* tab,
-                 int log_cap, int* map, unsigned* mask, hipStream_t st) {
+                 int log_cap, int* map, unsigned* mask, Ctl* ctl, hipStream_t st) {
   constexpr int V = K * K * K;
   constexpr int RPW = 64 / V;
   const int64_t waves = ceil_div(n_rows, RPW);
   const unsigned blocks = blocks_for(waves, 4);
   if (transposed)
     hipLaunchKernelGGL((k_probe<K, true>), dim3(blocks), dim3(256), 0, st, rows, (int)n_rows, stride, tab, log_cap,
-                       map, mask);
+                       map, mask, ctl);
   else
     hipLaunchKernelGGL((k_probe<K, false>), dim3(blocks), dim3(256), 0, st, rows, (int)n_rows, stride, tab,
-                       log_cap, map, mask);
+                       log_cap, map, mask, ctl);
   SPC_LAUNCH_CHECK();
   return SPCONV_OK;
 }
@@ -326,7 +339,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   DevBuf ctl_buf, tab_fine, tab_coarse, ukeys_a, ukeys_b, hist;
   SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
   Ctl* ctl = ctl_buf.as<Ctl>();
-  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(64), 0, st, ctl);
+  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kPairSlots), 0, st, ctl);
   SPC_LAUNCH_CHECK();
 
   // fine table: key(p_j) -> j.  Also the duplicate / range check of the caller's rows.
@@ -385,9 +398,9 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     const int4* qrows = needs_coarse ? coarse_rows.as<int4>() : rows;
     SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
     status = (K == 3) ? launch_probe<3>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
-                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), st)
+                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), ctl, st)
                       : launch_probe<1>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
-                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), st);
+                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), ctl, st);
     SPC_TRY(status);
   } else {
     km->n_in = needs_coarse ? U : N;
@@ -396,9 +409,9 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
                                                  : tab_fine.as<unsigned long long>();
     SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
     status = (K == 3) ? launch_probe<3>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
-                                        km->out_side.mask.as<unsigned>(), st)
+                                        km->out_side.mask.as<unsigned>(), ctl, st)
                       : launch_probe<1>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
-                                        km->out_side.mask.as<unsigned>(), st);
+                                        km->out_side.mask.as<unsigned>(), ctl, st);
     SPC_TRY(status);
   }
   km->out_side.ready = true;
@@ -409,6 +422,9 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
     if (h.flags & FLAG_DUP) return SPCONV_EDUP;
     if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+    int64_t pairs = 0;  // the probe ran before this synchronisation: its pair count is final
+    for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+    km->n_pairs = pairs;
   }
 
   // coordinate sets kept for the export calls and for the next layer of a network

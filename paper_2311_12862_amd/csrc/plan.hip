@@ -82,13 +82,75 @@ __global__ void __launch_bounds__(256)
   if ((threadIdx.x & 63) == 0 && mine) atomicAdd(executed, mine);
 }
 
-// map_k[k][n] = map[n][k]
+// Per-offset pair counts of each wave's 256 rows: counts[k][w].  A ballot per offset turns the
+// 64 masks held by the lanes into that offset's count; lane k keeps the running count of offset k.
 __global__ void __launch_bounds__(256)
-    k_offset_major(const int* __restrict__ map, int V, long long rows_pad, int* __restrict__ map_k) {
-  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= rows_pad * V) return;
-  const long long k = e / rows_pad, n = e - k * rows_pad;
-  map_k[e] = map[n * V + k];
+    k_pair_count(const unsigned* __restrict__ mask, long long rows, int V, int n_waves,
+                 unsigned* __restrict__ counts) {
+  const int lane = threadIdx.x & 63;
+  const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (w >= n_waves) return;
+  unsigned mine = 0;
+  for (int it = 0; it < 4; ++it) {
+    const long long r = w * 256 + it * 64 + lane;
+    const unsigned m = r < rows ? mask[r] : 0u;
+    for (int k = 0; k < V; ++k) {
+      const unsigned long long bal = __ballot((m >> k) & 1u);
+      if (lane == k) mine += (unsigned)__popcll(bal);
+    }
+  }
+  if (lane < V) counts[(long long)lane * n_waves + w] = mine;
+}
+
+// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.
+__global__ void __launch_bounds__(256)
+    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int V, int n_waves,
+                const unsigned* __restrict__ offs, int2* __restrict__ pairs) {
+  const int lane = threadIdx.x & 63;
+  const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  if (w >= n_waves) return;
+  unsigned base = lane < V ? offs[(long long)lane * n_waves + w] : 0u;  // lane k: next slot of offset k
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  for (int it = 0; it < 4; ++it) {
+    const long long r = w * 256 + it * 64 + lane;
+    const unsigned m = r < rows ? mask[r] : 0u;
+    for (int k = 0; k < V; ++k) {
+      const bool bit = (m >> k) & 1u;
+      const unsigned long long bal = __ballot(bit);
+      const unsigned start = __shfl(base, k);
+      if (bit) pairs[start + (unsigned)__popcll(bal & lt)] = make_int2((int)r, map[r * V + k]);
+      if (lane == k) base += (unsigned)__popcll(bal);
+    }
+  }
+}
+
+// Cuts every offset's pair range into ceil(count / target) nearly equal work items.
+__global__ void __launch_bounds__(64)
+    k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
+                 int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
+  const int lane = threadIdx.x;
+  const unsigned begin = lane <= V ? scanned[(long long)(lane < V ? lane : V) * n_waves] : 0u;
+  const unsigned next = __shfl_down(begin, 1);
+  const unsigned cnt = lane < V ? next - begin : 0u;
+  if (lane <= V) seg[lane] = (int)begin;
+  const unsigned pieces = cnt ? (cnt + target - 1) / target : 0u;
+  unsigned incl = pieces;
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  const unsigned first = incl - pieces;
+  if (lane <= V) item_seg[lane] = (int)(first < (unsigned)max_items ? first : (unsigned)max_items);
+  if (lane == V) item_seg[V + 1] = (int)(first < (unsigned)max_items ? first : (unsigned)max_items);
+  for (unsigned q = 0; q < pieces; ++q) {
+    if (first + q >= (unsigned)max_items) break;  // cannot happen: max_items bounds the sum
+    WgradItem w;
+    w.k = lane;
+    w.pair_begin = (int)(begin + (unsigned)(((unsigned long long)cnt * q) / pieces));
+    w.pair_end = (int)(begin + (unsigned)(((unsigned long long)cnt * (q + 1)) / pieces));
+    w.pad = 0;
+    items[first + q] = w;
+  }
 }
 
 }  // namespace
@@ -194,39 +256,35 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
     *out = it->second.get();
     return SPCONV_OK;
   }
+  if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));  // only maps built with stride > 1
   std::unique_ptr<WgradPlan> p(new (std::nothrow) WgradPlan);
   if (!p) return SPCONV_ENOMEM;
   const int V = km->V;
   const SideMap& side = km->out_side;
   p->target_pairs = target_pairs;
-  SPC_TRY(p->map_k.alloc((size_t)side.rows_pad * V * sizeof(int)));
-  hipLaunchKernelGGL(k_offset_major, dim3(blocks_for(side.rows_pad * V, 256)), dim3(256), 0, st, side.map.as<int>(),
-                     V, (long long)side.rows_pad, p->map_k.as<int>());
+  p->max_items = (int)std::min<int64_t>(V + ceil_div(km->n_pairs, target_pairs), 1 << 20);
+  const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, 256));
+  const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
+  DevBuf counts;
+  SPC_TRY(counts.alloc(n_counts * sizeof(unsigned)));
+  SPC_TRY(p->pairs.alloc(std::max<size_t>(1, (size_t)km->n_pairs) * sizeof(int2)));
+  SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int)));
+  SPC_TRY(p->items.alloc((size_t)p->max_items * sizeof(WgradItem)));
+  SPC_TRY(p->item_seg.alloc((size_t)(V + 2) * sizeof(int)));
+  // (fill kernels instead of memsets keep these calls usable under stream capture)
+  SPC_HIP(hipMemsetAsync(counts.p, 0, n_counts * sizeof(unsigned), st));
+  const unsigned blocks = blocks_for(n_waves, 4);
+  hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
+                     n_waves, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
-  SPC_TRY(kmap_count_pairs(km, st, p->counts));  // synchronises
-  std::vector<WgradItem> items;
-  std::vector<int32_t> seg(V + 1, 0);
-  for (int k = 0; k < V; ++k) {
-    seg[k] = (int32_t)items.size();
-    if (p->counts[k] == 0) continue;
-    const int64_t pieces = std::max<int64_t>(1, ceil_div(p->counts[k], target_pairs));
-    for (int64_t q = 0; q < pieces; ++q) {
-      WgradItem w;
-      w.k = k;
-      w.row_begin = (int32_t)((km->n_out * q) / pieces);
-      w.row_end = (int32_t)((km->n_out * (q + 1)) / pieces);
-      w.slot = (int32_t)items.size();
-      if (w.row_end > w.row_begin) items.push_back(w);
-    }
-  }
-  seg[V] = (int32_t)items.size();
-  p->n_items = (int)items.size();
-  SPC_TRY(p->items.alloc(std::max<size_t>(1, items.size()) * sizeof(WgradItem)));
-  SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int32_t)));
-  if (!items.empty())
-    SPC_HIP(hipMemcpyAsync(p->items.p, items.data(), items.size() * sizeof(WgradItem), hipMemcpyHostToDevice, st));
-  SPC_HIP(hipMemcpyAsync(p->seg.p, seg.data(), seg.size() * sizeof(int32_t), hipMemcpyHostToDevice, st));
-  SPC_HIP(hipStreamSynchronize(st));  // the host vectors go out of scope
+  SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, st));
+  hipLaunchKernelGGL(k_pair_fill, dim3(blocks), dim3(256), 0, st, side.map.as<int>(), side.mask.as<unsigned>(),
+                     (long long)km->n_out, V, n_waves, counts.as<unsigned>(), p->pairs.as<int2>());
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_make_items, dim3(1), dim3(64), 0, st, counts.as<unsigned>(), V, n_waves,
+                     (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
+                     p->item_seg.as<int>());
+  SPC_LAUNCH_CHECK();
   *out = p.get();
   km->wplans[target_pairs] = std::move(p);
   return SPCONV_OK;

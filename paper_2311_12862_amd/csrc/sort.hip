@@ -37,28 +37,58 @@ __global__ void __launch_bounds__(256) k_radix_hist(const KeyT* __restrict__ key
     for (int d = lane; d < bins; d += 64) hist[(long long)d * n_waves + w] = cnt[wib][d];
 }
 
-// Exclusive scan of `elems` counters in place, one workgroup of 1024 threads.
-__global__ void __launch_bounds__(1024) k_radix_scan(unsigned* __restrict__ hist, long long elems) {
-  __shared__ unsigned part[1024];
-  const int t = threadIdx.x;
-  const long long per = (elems + 1023) / 1024;
-  const long long begin = t * per;
-  const long long end = begin + per < elems ? begin + per : elems;
-  unsigned sum = 0;
-  for (long long i = begin; i < end; ++i) sum += hist[i];
-  part[t] = sum;
+// Exclusive scan of `elems` counters in place, one workgroup of 1024 threads.  Tiles of 8192
+// counters pass through LDS so that global accesses are coalesced; each thread scans 8
+// consecutive counters (LDS index skewed by one word per 32 to stay off bank conflicts), a
+// wave-shuffle scan combines the threads, and a running carry links the tiles.
+constexpr int kScanPer = 8;
+constexpr int kScanTile = 1024 * kScanPer;
+__device__ __forceinline__ int scan_skew(int x) { return x + (x >> 5); }
+
+__global__ void __launch_bounds__(1024) k_scan_u32(unsigned* __restrict__ data, long long elems) {
+  __shared__ unsigned tile[kScanTile + kScanTile / 32 + 8];
+  __shared__ unsigned wave_sum[16];
+  __shared__ unsigned carry_s;
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  if (t == 0) carry_s = 0;
   __syncthreads();
-  for (int off = 1; off < 1024; off <<= 1) {
-    const unsigned v = (t >= off) ? part[t - off] : 0u;
+  for (long long base = 0; base < elems; base += kScanTile) {
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) {
+      const long long g = base + i * 1024 + t;
+      tile[scan_skew(i * 1024 + t)] = g < elems ? data[g] : 0u;
+    }
     __syncthreads();
-    part[t] += v;
+    unsigned v[kScanPer], sum = 0;
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) {
+      v[i] = tile[scan_skew(t * kScanPer + i)];
+      sum += v[i];
+    }
+    unsigned incl = sum;  // inclusive scan across the wave
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    if (lane == 63) wave_sum[wave] = incl;
     __syncthreads();
-  }
-  unsigned run = part[t] - sum;
-  for (long long i = begin; i < end; ++i) {
-    const unsigned v = hist[i];
-    hist[i] = run;
-    run += v;
+    unsigned before = carry_s;
+    for (int w = 0; w < wave; ++w) before += wave_sum[w];
+    unsigned run = before + incl - sum;
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) {
+      tile[scan_skew(t * kScanPer + i)] = run;
+      run += v[i];
+    }
+    __syncthreads();
+    if (t == 1023) carry_s = run;  // the last thread ends with the tile's grand total added
+#pragma unroll
+    for (int i = 0; i < kScanPer; ++i) {
+      const long long g = base + i * 1024 + t;
+      if (g < elems) data[g] = tile[scan_skew(i * 1024 + t)];
+    }
+    __syncthreads();
   }
 }
 
@@ -110,7 +140,7 @@ int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n
   hipLaunchKernelGGL((k_radix_hist<KeyT>), dim3(blocks), dim3(256), 0, st, kin, (long long)n, shift, bits, hist,
                      n_waves);
   SPC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_radix_scan, dim3(1), dim3(1024), 0, st, hist, ((long long)n_waves) << bits);
+  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, st, hist, ((long long)n_waves) << bits);
   SPC_LAUNCH_CHECK();
   hipLaunchKernelGGL((k_radix_scatter<KeyT, HAS_VAL>), dim3(blocks), dim3(256), 0, st, kin, kout, vin, vout,
                      (long long)n, shift, bits, hist, n_waves);
@@ -119,6 +149,13 @@ int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n
 }
 
 }  // namespace
+
+int scan_u32_inplace(uint32_t* data, int64_t elems, hipStream_t st) {
+  if (elems <= 0) return SPCONV_OK;
+  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, st, data, (long long)elems);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
 
 size_t sort_hist_elems(int64_t n) { return (size_t)ceil_div(n > 0 ? n : 1, kItemsPerWave) * kMaxBins; }
 

@@ -1,16 +1,18 @@
 // Weight-gradient kernels (Sections 4.2, 6.2): dW[k] = sum over present pairs
 // (n, j = M[n][k]) of x[j]^T . dy[n].
 //
-// The reduction runs over output rows, which is the long inner loop the paper
-// singles out.  Here a workgroup takes one offset k and a range of rows from
-// the offset-major map, compacts the present pairs of 256 rows at a time into
-// an LDS ring with a wave ballot and a four-entry prefix, and feeds the matrix
-// cores dense batches of 128 pairs: no multiply is spent on absent
-// neighbours, whatever the row order, so wgrad needs no sorted map.  Both
-// operands are gathered row-wise and transposed on their way into LDS
-// (the MFMA wants the reduction index contiguous per lane).  Each work item
+// The reduction runs over output rows, the long inner loop the paper singles
+// out.  Here it walks the compacted pair list of one offset (the
+// weight-stationary view of the map, Section 2.2.1), so no multiply is spent
+// on absent neighbours and the row order of the map does not matter.  A
+// workgroup owns a 64 x 64 tile of dW[k] and a range of pairs.  Per batch of 64
+// pairs it gathers 64 rows of x and of dy (16-byte segments, out-of-range
+// buffer loads for the ragged tail), one batch ahead of the matrix cores, and
+// stores them row-major in LDS; the MFMA operands need the reduction index
+// (the pair) contiguous per lane, which the CDNA4 transposing LDS read
+// (ds_read_b64_tr_b16) delivers without a software transpose.  Each work item
 // writes an fp32 partial tile; a second kernel adds the tiles of each offset
-// in a fixed order, so results are bit-reproducible.
+// in item order, so results are bit-reproducible.
 #include "common.h"
 
 namespace spc {
@@ -19,156 +21,181 @@ namespace {
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 template <typename T> struct Mfma;
 template <> struct Mfma<_Float16> {
-  typedef f16x8 vec;
-  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_f16(a, b, c, 0, 0, 0);
+  static __device__ __forceinline__ f32x4 run(s16x8 a, s16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0,
+                                                  0);
   }
 };
 template <> struct Mfma<__bf16> {
-  typedef bf16x8 vec;
-  static __device__ __forceinline__ f32x4 run(vec a, vec b, f32x4 c) {
-    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(a, b, c, 0, 0, 0);
+  static __device__ __forceinline__ f32x4 run(s16x8 a, s16x8 b, f32x4 c) {
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0,
+                                                   0, 0);
   }
 };
 
 struct WgradParams {
   const void* feats;   // [n_in][C_in]
   const void* dout;    // [n_out][C_out]
-  const int* map_k;    // [V][rows_pad]
+  const int2* pairs;   // (n, j), offset-major
   const WgradItem* items;
-  float* partial;      // [n_items][C_in][C_out]
-  long long rows_pad;
-  int C_in, C_out;
+  const int* item_seg; // [V+2], [V] = number of items
+  float* partial;      // [max_items][C_in][C_out]
+  unsigned feats_bytes, dout_bytes, pairs_bytes;
+  int C_in, C_out, V;
 };
 
-constexpr int WG_BK = 128;             // pairs per MFMA batch
-constexpr int WG_LD = WG_BK + 8;       // LDS pitch of the transposed operand tiles
-constexpr int WG_RING = 512;
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ int2 buf_load8(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, byte_off, 0, 0);
+  return make_int2((int)v.x, (int)v.y);
+}
+
+constexpr int WG_BK = 64;   // pairs per batch
+constexpr int WG_LD = 80;   // LDS row pitch in 2-byte elements: 64 channels + 32 bytes, so that the four
+                            // rows a transposing read touches fall on disjoint banks
+
+// Transposing read: the 16 lanes of a group together fetch a 4 (rows) x 16 (columns) block,
+// lane a pointing at row a/4, columns 4*(a%4)..+3; lane a receives column a of the block,
+// i.e. four consecutive rows of one channel.  Two reads give the 8 reduction steps of a lane.
+__device__ __forceinline__ s16x8 read_frag(const unsigned short* tile, int row0, int col0, int lane) {
+  const int a = lane & 15, g = lane >> 4;
+  const unsigned short* p = tile + (row0 + 8 * g + (a >> 2)) * WG_LD + col0 + 4 * (a & 3);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4*)(p));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+      (__attribute__((address_space(3))) s16x4*)(p + 4 * WG_LD));
+  return s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+}
 
 template <typename T>
 __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
-  typedef typename Mfma<T>::vec vec8;
-  __shared__ __align__(16) unsigned short XT[64 * WG_LD];  // [ci][pair]
-  __shared__ __align__(16) unsigned short DT[64 * WG_LD];  // [co][pair]
-  __shared__ int ringN[WG_RING], ringJ[WG_RING];
-  __shared__ int wave_cnt[4];
+  __shared__ __align__(16) unsigned short Xs[2][WG_BK * WG_LD];  // [pair][ci]
+  __shared__ __align__(16) unsigned short Ds[2][WG_BK * WG_LD];  // [pair][co]
 
+  if ((int)blockIdx.x >= p.item_seg[p.V]) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WgradItem item = p.items[blockIdx.x];
   const int ci0 = blockIdx.y * 64, co0 = blockIdx.z * 64;
-  const unsigned short* feats = reinterpret_cast<const unsigned short*>(p.feats);
-  const unsigned short* dout = reinterpret_cast<const unsigned short*>(p.dout);
-  const int* col = p.map_k + (long long)item.k * p.rows_pad;
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
+  const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dout, p.dout_bytes);
+  const __amdgpu_buffer_rsrc_t p_rsrc = make_rsrc(p.pairs, p.pairs_bytes);
+  const unsigned x_row = (unsigned)p.C_in * 2u, d_row = (unsigned)p.C_out * 2u;
 
-  f32x4 acc[4];
+  // this wave's 32 x 32 quadrant of the 64 x 64 tile
+  const int wci = (wave >> 1) * 32, wco = (wave & 1) * 32;
+  f32x4 acc[2][2];
 #pragma unroll
-  for (int nb = 0; nb < 4; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
+  for (int i = 0; i < 2; ++i)
+#pragma unroll
+    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  const int seg = tid % 8, q0 = tid / 8;
+  // staging: thread (q, seg) moves segment seg (8 channels) of pair rows q and q + 32
+  const int seg = tid & 7, q0 = tid >> 3;
+  const bool x_ok = ci0 + seg * 8 < p.C_in, d_ok = co0 + seg * 8 < p.C_out;
+  const int n_batches = (item.pair_end - item.pair_begin + WG_BK - 1) / WG_BK;
 
-  auto batch = [&](int head, int cnt) {
-    // gather the two operands of up to WG_BK pairs and store them transposed
+  int2 pr[2];       // pair indices of the batch after next
+  uint4 rx[2], rd[2];  // rows of the next batch
+  auto load_pairs = [&](int batch) {
 #pragma unroll
-    for (int ps = 0; ps < WG_BK / 32; ++ps) {
-      const int q = q0 + ps * 32;
-      uint4 vx = make_uint4(0, 0, 0, 0), vd = make_uint4(0, 0, 0, 0);
-      if (q < cnt) {
-        const int n = ringN[(head + q) & (WG_RING - 1)], j = ringJ[(head + q) & (WG_RING - 1)];
-        if (ci0 + seg * 8 < p.C_in)
-          vx = *reinterpret_cast<const uint4*>(feats + (long long)j * p.C_in + ci0 + seg * 8);
-        if (co0 + seg * 8 < p.C_out)
-          vd = *reinterpret_cast<const uint4*>(dout + (long long)n * p.C_out + co0 + seg * 8);
-      }
-      const unsigned wx[4] = {vx.x, vx.y, vx.z, vx.w}, wd[4] = {vd.x, vd.y, vd.z, vd.w};
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        XT[(seg * 8 + 2 * i) * WG_LD + q] = (unsigned short)(wx[i] & 0xFFFFu);
-        XT[(seg * 8 + 2 * i + 1) * WG_LD + q] = (unsigned short)(wx[i] >> 16);
-        DT[(seg * 8 + 2 * i) * WG_LD + q] = (unsigned short)(wd[i] & 0xFFFFu);
-        DT[(seg * 8 + 2 * i + 1) * WG_LD + q] = (unsigned short)(wd[i] >> 16);
-      }
+    for (int h = 0; h < 2; ++h) {
+      const int e = item.pair_begin + batch * WG_BK + q0 + 32 * h;
+      pr[h] = buf_load8(p_rsrc, (batch < n_batches && e < item.pair_end) ? (unsigned)e * 8u : 0xFFFFFFFFu);
     }
-    __syncthreads();
-    const unsigned short* a = XT + (wave * 16 + (lane & 15)) * WG_LD + (lane >> 4) * 8;
-    const unsigned short* b = DT + (lane & 15) * WG_LD + (lane >> 4) * 8;
-    const int steps = (cnt + 31) / 32;
-    for (int ks = 0; ks < steps; ++ks) {
-      const vec8 af = *reinterpret_cast<const vec8*>(a + ks * 32);
+  };
+  auto load_rows = [&](int batch) {
 #pragma unroll
-      for (int nb = 0; nb < 4; ++nb) {
-        const vec8 bf = *reinterpret_cast<const vec8*>(b + nb * 16 * WG_LD + ks * 32);
-        acc[nb] = Mfma<T>::run(af, bf, acc[nb]);
-      }
+    for (int h = 0; h < 2; ++h) {
+      const int e = item.pair_begin + batch * WG_BK + q0 + 32 * h;
+      const bool live = batch < n_batches && e < item.pair_end;
+      rx[h] = buf_load16(x_rsrc, (live && x_ok) ? (unsigned)pr[h].y * x_row + (unsigned)(ci0 + seg * 8) * 2u
+                                                 : 0xFFFFFFFFu);
+      rd[h] = buf_load16(d_rsrc, (live && d_ok) ? (unsigned)pr[h].x * d_row + (unsigned)(co0 + seg * 8) * 2u
+                                                 : 0xFFFFFFFFu);
     }
-    __syncthreads();
+  };
+  auto store_rows = [&](int buf) {
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      *reinterpret_cast<uint4*>(&Xs[buf][(q0 + 32 * h) * WG_LD + seg * 8]) = rx[h];
+      *reinterpret_cast<uint4*>(&Ds[buf][(q0 + 32 * h) * WG_LD + seg * 8]) = rd[h];
+    }
   };
 
-  int head = 0, tail = 0;
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  for (int base = item.row_begin; base < item.row_end; base += 256) {
-    const int n = base + tid;
-    const int j = (n < item.row_end) ? col[n] : -1;
-    const bool valid = j >= 0;
-    const unsigned long long bal = __ballot(valid);
-    if (lane == 0) wave_cnt[wave] = __popcll(bal);
-    __syncthreads();
-    int off = 0, total = 0;
+  load_pairs(0);
+  load_rows(0);
+  load_pairs(1);
+  store_rows(0);
+  __syncthreads();
+  for (int b = 0; b < n_batches; ++b) {
+    load_rows(b + 1);   // out-of-range (zero, no traffic) past the last batch
+    load_pairs(b + 2);
+    const unsigned short* xs = Xs[b & 1];
+    const unsigned short* ds = Ds[b & 1];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      const int c = wave_cnt[w];
-      off += (w < wave) ? c : 0;
-      total += c;
+    for (int ks = 0; ks < WG_BK / 32; ++ks) {
+      s16x8 af[2], bf[2];
+#pragma unroll
+      for (int i = 0; i < 2; ++i) af[i] = read_frag(xs, ks * 32, wci + i * 16, lane);
+#pragma unroll
+      for (int j = 0; j < 2; ++j) bf[j] = read_frag(ds, ks * 32, wco + j * 16, lane);
+#pragma unroll
+      for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(af[i], bf[j], acc[i][j]);
     }
-    if (valid) {
-      const int pos = (tail + off + __popcll(bal & lt)) & (WG_RING - 1);
-      ringN[pos] = n;
-      ringJ[pos] = j;
-    }
-    tail += total;
+    store_rows((b + 1) & 1);
     __syncthreads();
-    while (tail - head >= WG_BK) {
-      batch(head, WG_BK);
-      head += WG_BK;
-    }
   }
-  if (tail > head) batch(head, tail - head);
 
-  float* dst = p.partial + (long long)item.slot * p.C_in * p.C_out;
+  float* dst = p.partial + (long long)blockIdx.x * p.C_in * p.C_out;
 #pragma unroll
-  for (int r = 0; r < 4; ++r) {
-    const int ci = ci0 + wave * 16 + (lane >> 4) * 4 + r;
-    if (ci >= p.C_in) continue;
+  for (int i = 0; i < 2; ++i)
 #pragma unroll
-    for (int nb = 0; nb < 4; ++nb) {
-      const int co = co0 + nb * 16 + (lane & 15);
-      if (co < p.C_out) dst[(long long)ci * p.C_out + co] = acc[nb][r];
+    for (int r = 0; r < 4; ++r) {
+      const int ci = ci0 + wci + i * 16 + (lane >> 4) * 4 + r;
+      if (ci >= p.C_in) continue;
+#pragma unroll
+      for (int j = 0; j < 2; ++j) {
+        const int co = co0 + wco + j * 16 + (lane & 15);
+        if (co < p.C_out) dst[(long long)ci * p.C_out + co] = acc[i][j][r];
+      }
     }
-  }
 }
 
-// fp32 path: 16 rows at a time, absent neighbours contribute zeros.
+// fp32 path: plain FMA arithmetic, 16 pairs at a time.
 __global__ void __launch_bounds__(256) k_wgrad_f32(const WgradParams p) {
   __shared__ float Xs[16][64 + 4];
   __shared__ float Ds[16][64 + 4];
+  if ((int)blockIdx.x >= p.item_seg[p.V]) return;
   const int tid = threadIdx.x;
   const WgradItem item = p.items[blockIdx.x];
   const int ci0 = blockIdx.y * 64, co0 = blockIdx.z * 64;
   const float* feats = reinterpret_cast<const float*>(p.feats);
   const float* dout = reinterpret_cast<const float*>(p.dout);
-  const int* col = p.map_k + (long long)item.k * p.rows_pad;
   const int ty = tid / 16, tx = tid % 16;
   const int q = tid / 16, seg4 = (tid % 16) * 4;
   float acc[4][4] = {};
-  for (int base = item.row_begin; base < item.row_end; base += 16) {
-    const int n = base + q;
-    const int j = (n < item.row_end) ? col[n] : -1;
+  for (int base = item.pair_begin; base < item.pair_end; base += 16) {
+    const int e = base + q;
     float4 vx = make_float4(0.f, 0.f, 0.f, 0.f), vd = vx;
-    if (j >= 0) {
-      if (ci0 + seg4 < p.C_in) vx = *reinterpret_cast<const float4*>(feats + (long long)j * p.C_in + ci0 + seg4);
-      if (co0 + seg4 < p.C_out) vd = *reinterpret_cast<const float4*>(dout + (long long)n * p.C_out + co0 + seg4);
+    if (e < item.pair_end) {
+      const int2 pr = p.pairs[e];
+      if (ci0 + seg4 < p.C_in) vx = *reinterpret_cast<const float4*>(feats + (long long)pr.y * p.C_in + ci0 + seg4);
+      if (co0 + seg4 < p.C_out) vd = *reinterpret_cast<const float4*>(dout + (long long)pr.x * p.C_out + co0 + seg4);
     }
     *reinterpret_cast<float4*>(&Xs[q][seg4]) = vx;
     *reinterpret_cast<float4*>(&Ds[q][seg4]) = vd;
@@ -187,7 +214,7 @@ __global__ void __launch_bounds__(256) k_wgrad_f32(const WgradParams p) {
     }
     __syncthreads();
   }
-  float* dst = p.partial + (long long)item.slot * p.C_in * p.C_out;
+  float* dst = p.partial + (long long)blockIdx.x * p.C_in * p.C_out;
   for (int i = 0; i < 4; ++i) {
     const int ci = ci0 + ty * 4 + i;
     if (ci >= p.C_in) continue;
@@ -199,13 +226,14 @@ __global__ void __launch_bounds__(256) k_wgrad_f32(const WgradParams p) {
 }
 
 // dW[k][e] = sum of the partial tiles of offset k, in item order
-__global__ void __launch_bounds__(256) k_wgrad_reduce(const float* __restrict__ partial, const int* __restrict__ seg,
-                                                      int elems, float* __restrict__ dw) {
+__global__ void __launch_bounds__(256) k_wgrad_reduce(const float* __restrict__ partial,
+                                                      const int* __restrict__ item_seg, int elems,
+                                                      float* __restrict__ dw) {
   const int e4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
   if (e4 >= elems) return;
   const int k = blockIdx.y;
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int it = seg[k]; it < seg[k + 1]; ++it) {
+  for (int it = item_seg[k]; it < item_seg[k + 1]; ++it) {
     const float4 v = *reinterpret_cast<const float4*>(partial + (long long)it * elems + e4);
     s.x += v.x;
     s.y += v.y;
@@ -221,18 +249,27 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
               spconv_dtype dtype, float* dweights, hipStream_t st) {
   const int V = km->V;
   const int elems = C_in * C_out;
-  if (wp.n_items > 0) {
-    SPC_TRY(km->scratch.reserve((size_t)wp.n_items * elems * sizeof(float)));
-    WgradParams p{};
-    p.feats = feats;
-    p.dout = dout;
-    p.map_k = wp.map_k.as<int>();
-    p.items = wp.items.as<WgradItem>();
-    p.partial = km->scratch.as<float>();
-    p.rows_pad = km->out_side.rows_pad;
-    p.C_in = C_in;
-    p.C_out = C_out;
-    dim3 grid((unsigned)wp.n_items, (unsigned)ceil_div(C_in, 64), (unsigned)ceil_div(C_out, 64));
+  const size_t e = dtype == SPCONV_F32 ? 4 : 2;
+  const uint64_t feats_bytes = (uint64_t)km->n_in * C_in * e, dout_bytes = (uint64_t)km->n_out * C_out * e;
+  const uint64_t pairs_bytes = (uint64_t)std::max<int64_t>(km->n_pairs, 0) * 8;
+  if (dtype != SPCONV_F32 && (feats_bytes >= 0xFFFFC000ull || dout_bytes >= 0xFFFFC000ull || pairs_bytes >= 0xFFFFC000ull))
+    return SPCONV_EINVAL;  // buffer descriptors address 32 bits
+  SPC_TRY(km->scratch.reserve((size_t)wp.max_items * elems * sizeof(float)));
+  WgradParams p{};
+  p.feats = feats;
+  p.dout = dout;
+  p.pairs = wp.pairs.as<int2>();
+  p.items = wp.items.as<WgradItem>();
+  p.item_seg = wp.item_seg.as<int>();
+  p.partial = km->scratch.as<float>();
+  p.feats_bytes = (unsigned)feats_bytes;
+  p.dout_bytes = (unsigned)dout_bytes;
+  p.pairs_bytes = (unsigned)pairs_bytes;
+  p.C_in = C_in;
+  p.C_out = C_out;
+  p.V = V;
+  if (km->n_pairs > 0) {
+    dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, 64), (unsigned)ceil_div(C_out, 64));
     switch (dtype) {
       case SPCONV_F32: hipLaunchKernelGGL(k_wgrad_f32, grid, dim3(256), 0, st, p); break;
       case SPCONV_F16: hipLaunchKernelGGL((k_wgrad<_Float16>), grid, dim3(256), 0, st, p); break;
@@ -241,7 +278,7 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
     SPC_LAUNCH_CHECK();
   }
   dim3 rgrid((unsigned)ceil_div(elems / 4, 256), (unsigned)V);
-  hipLaunchKernelGGL(k_wgrad_reduce, rgrid, dim3(256), 0, st, km->scratch.as<float>(), wp.seg.as<int>(), elems,
+  hipLaunchKernelGGL(k_wgrad_reduce, rgrid, dim3(256), 0, st, km->scratch.as<float>(), wp.item_seg.as<int>(), elems,
                      dweights);
   SPC_LAUNCH_CHECK();
   return SPCONV_OK;

@@ -11,6 +11,7 @@
 #include "common.h"
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 
 namespace spc {
@@ -98,10 +99,12 @@ __global__ void k_ctl_init(Ctl* ctl) {
 
 // Insert key(p_j) -> j for every input row; flags range and duplicate errors.
 __global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ coords, int n,
-                                                     unsigned long long* tab, int log_cap, Ctl* ctl) {
+                                                     unsigned long long* tab, int log_cap, Ctl* ctl,
+                                                     int4* __restrict__ keep) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   if (j >= n) return;
   const int4 c = coords[j];
+  keep[j] = c;  // the kmap's own copy of the caller's rows
   if (!coord_ok(c.x, c.y, c.z, c.w)) {
     atomicOr(&ctl->flags, FLAG_RANGE);
     return;
@@ -227,6 +230,70 @@ __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, in
   }
 }
 
+// One launch that prepares a submanifold build: empties the hash table, presets the whole map
+// to "absent" and the masks to zero, and clears the control block.
+__global__ void __launch_bounds__(256)
+    k_build_init(ulonglong2* __restrict__ tab, long long slots, int4* __restrict__ map4, long long map_vec4,
+                 unsigned* __restrict__ mask, long long mask_n, Ctl* ctl) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  for (long long i = t; i < slots; i += stride) tab[i] = make_ulonglong2(kEmpty, kEmpty);
+  for (long long i = t; i < map_vec4; i += stride) map4[i] = make_int4(-1, -1, -1, -1);
+  for (long long i = t; i < mask_n; i += stride) mask[i] = 0u;
+  if (blockIdx.x == 0) {
+    if (threadIdx.x == 0) {
+      ctl->flags = 0;
+      ctl->count = 0;
+      ctl->key_or = 0;
+      ctl->key_and = ~0ull;
+    }
+    if (threadIdx.x < kPairSlots) ctl->pairs[threadIdx.x * 16] = 0;
+  }
+}
+
+// Submanifold probe that uses the symmetry M[n][k] = j  <=>  M[j][V-1-k] = n: only the offsets
+// below the centre are looked up (13 of 27); a hit writes both entries and both mask bits.  The
+// map was preset to -1 and the masks to 0, so misses write nothing.  Lanes: 14 per row
+// (k = 0..13, the last one being the centre), 4 rows per wave.
+__global__ void __launch_bounds__(256)
+    k_probe_sym3(const int4* __restrict__ rows, int n_rows, const unsigned long long* __restrict__ tab, int log_cap,
+                 int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl) {
+  __shared__ unsigned wave_pairs[4];
+  constexpr int V = 27, HALF = 13, LPR = 14, RPW = 4;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int sub = lane / LPR, k = lane - sub * LPR;
+  const long long row = wave * RPW + sub;
+  const bool active = (sub < RPW) && (row < n_rows);
+  int found = -1;
+  if (active) {
+    if (k == HALF) {
+      found = (int)row;
+      map[row * V + HALF] = found;
+    } else {
+      const int4 c = rows[row];
+      const int tx = c.y + k / 9 - 1, ty = c.z + (k / 3) % 3 - 1, tz = c.w + k % 3 - 1;
+      if (coord_ok(c.x, tx, ty, tz)) found = table_find(tab, log_cap, pack_key(c.x, tx, ty, tz), nullptr);
+      if (found >= 0) {
+        map[row * V + k] = found;
+        map[(long long)found * V + (V - 1 - k)] = (int)row;
+        atomicOr(&mask[found], 1u << (V - 1 - k));
+      }
+    }
+  }
+  const unsigned long long bal = __ballot(found >= 0);
+  if (active && k == 0) atomicOr(&mask[row], (unsigned)((bal >> (sub * LPR)) & ((1ull << LPR) - 1ull)));
+  // pairs: every hit below the centre stands for two, the centre for one
+  const unsigned long long centre = (1ull << HALF) | (1ull << (HALF + LPR)) | (1ull << (HALF + 2 * LPR)) |
+                                    (1ull << (HALF + 3 * LPR));
+  if (lane == 0) wave_pairs[threadIdx.x >> 6] = 2u * (unsigned)__popcll(bal & ~centre) + (unsigned)__popcll(bal & centre);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
+    if (n) atomicAdd(&ctl->pairs[(blockIdx.x % kPairSlots) * 16], (unsigned long long)n);
+  }
+}
+
 // T[j][k] = n for every present pair M[n][k] = j.
 __global__ void __launch_bounds__(256) k_scatter_in_side(const int* __restrict__ map, long long n_entries, int V,
                                                          int* __restrict__ tmap) {
@@ -310,6 +377,72 @@ int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st) {
   return SPCONV_OK;
 }
 
+// Reads the control block back through a pinned staging buffer (one per process) and
+// synchronises the stream.
+int read_ctl(const Ctl* ctl, Ctl* host, hipStream_t st) {
+  static std::mutex mu;
+  static Ctl* pinned = nullptr;
+  std::lock_guard<std::mutex> lk(mu);
+  if (!pinned) {
+    void* p = nullptr;
+    if (hipHostMalloc(&p, sizeof(Ctl), hipHostMallocDefault) != hipSuccess) {
+      (void)hipGetLastError();
+      p = nullptr;
+    }
+    pinned = static_cast<Ctl*>(p);
+  }
+  Ctl* dst = pinned ? pinned : host;
+  SPC_HIP(hipMemcpyAsync(dst, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+  SPC_HIP(hipStreamSynchronize(st));
+  if (pinned) *host = *pinned;
+  return SPCONV_OK;
+}
+
+int flags_status(const Ctl& h) {
+  if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
+  if (h.flags & FLAG_DUP) return SPCONV_EDUP;
+  if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+  return SPCONV_OK;
+}
+
+// Submanifold 3x3x3 build: three launches (init, insert, symmetric probe) and one readback.
+int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, hipStream_t st) {
+  const int V = 27;
+  DevBuf ctl_buf, tab, own_rows;
+  SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
+  Ctl* ctl = ctl_buf.as<Ctl>();
+  const int lc = log2_capacity(N);
+  SPC_TRY(tab.alloc((size_t)16 << lc));
+  SPC_TRY(own_rows.alloc((size_t)N * 16));
+  SideMap& side = km->out_side;
+  side.rows = N;
+  side.rows_pad = round_up(N, kRowPad);
+  SPC_TRY(side.map.alloc((size_t)side.rows_pad * V * sizeof(int)));
+  SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
+  const long long slots = 1ll << lc, map_vec4 = side.rows_pad * V / 4;
+  const unsigned init_blocks = (unsigned)std::min<int64_t>(ceil_div(std::max<long long>(slots, map_vec4), 256), 4096);
+  hipLaunchKernelGGL(k_build_init, dim3(init_blocks), dim3(256), 0, st, tab.as<ulonglong2>(), slots,
+                     side.map.as<int4>(), map_vec4, side.mask.as<unsigned>(), (long long)side.rows_pad, ctl);
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
+                     tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>());
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_probe_sym3, dim3(blocks_for(ceil_div(N, 4), 4)), dim3(256), 0, st, rows, (int)N,
+                     tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl);
+  SPC_LAUNCH_CHECK();
+  Ctl h{};
+  SPC_TRY(read_ctl(ctl, &h, st));
+  SPC_TRY(flags_status(h));
+  int64_t pairs = 0;
+  for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+  km->n_in = km->n_out = N;
+  km->n_pairs = pairs;
+  side.ready = true;
+  std::swap(km->in_coords.p, own_rows.p);  // P_out == P_in: out_coords stays empty
+  std::swap(km->in_coords.bytes, own_rows.bytes);
+  return SPCONV_OK;
+}
+
 }  // namespace
 
 int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, hipStream_t st,
@@ -336,6 +469,11 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   }
 
   const int4* rows = reinterpret_cast<const int4*>(coords);
+  if (K == 3 && stride == 1 && !transposed) {
+    SPC_TRY(build_submanifold3(km.get(), rows, N, st));
+    *out = km.release();
+    return SPCONV_OK;
+  }
   DevBuf ctl_buf, tab_fine, tab_coarse, ukeys_a, ukeys_b, hist;
   SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
   Ctl* ctl = ctl_buf.as<Ctl>();
@@ -346,14 +484,12 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   const int lc_fine = log2_capacity(N);
   SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
   SPC_HIP(hipMemsetAsync(tab_fine.p, 0xFF, (size_t)16 << lc_fine, st));
-  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                     tab_fine.as<unsigned long long>(), lc_fine, ctl);
-  SPC_LAUNCH_CHECK();
-
   // the caller's rows are kept: they are P_in (and P_out for stride 1), or the fine output set
   DevBuf own_rows;
   SPC_TRY(own_rows.alloc((size_t)N * 16));
-  SPC_HIP(hipMemcpyAsync(own_rows.p, coords, (size_t)N * 16, hipMemcpyDeviceToDevice, st));
+  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
+                     tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>());
+  SPC_LAUNCH_CHECK();
 
   Ctl h{};
   int64_t U = 0;
@@ -369,11 +505,8 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   }
   if (needs_coarse) {
     // the one synchronisation of a strided build: error flags, U, varying key bits
-    SPC_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-    SPC_HIP(hipStreamSynchronize(st));
-    if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
-    if (h.flags & FLAG_DUP) return SPCONV_EDUP;
-    if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+    SPC_TRY(read_ctl(ctl, &h, st));
+    SPC_TRY(flags_status(h));
     U = (int64_t)h.count;
     SPC_TRY(hist.alloc(sort_hist_elems(U) * sizeof(uint32_t)));
     int in_b = 0;
@@ -417,11 +550,8 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   km->out_side.ready = true;
 
   if (!needs_coarse) {
-    SPC_HIP(hipMemcpyAsync(&h, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-    SPC_HIP(hipStreamSynchronize(st));
-    if (h.flags & FLAG_RANGE) return SPCONV_ERANGE;
-    if (h.flags & FLAG_DUP) return SPCONV_EDUP;
-    if (h.flags & FLAG_FULL) return SPCONV_ENOMEM;
+    SPC_TRY(read_ctl(ctl, &h, st));
+    SPC_TRY(flags_status(h));
     int64_t pairs = 0;  // the probe ran before this synchronisation: its pair count is final
     for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
     km->n_pairs = pairs;

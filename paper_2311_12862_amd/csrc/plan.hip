@@ -102,34 +102,52 @@ __global__ void __launch_bounds__(256)
   if (lane < V) counts[(long long)lane * n_waves + w] = mine;
 }
 
-// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.
+// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.  The 64
+// map rows of a step are first copied to LDS with coalesced loads that are all in flight
+// together; the per-offset ballots then rank the present entries.
+template <int V>
 __global__ void __launch_bounds__(256)
-    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int V, int n_waves,
+    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_waves,
                 const unsigned* __restrict__ offs, int2* __restrict__ pairs) {
-  const int lane = threadIdx.x & 63;
+  __shared__ int slab[4][64 * V];
+  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
   const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   if (w >= n_waves) return;
   unsigned base = lane < V ? offs[(long long)lane * n_waves + w] : 0u;  // lane k: next slot of offset k
   const unsigned long long lt = (1ull << lane) - 1ull;
+  int* ms = slab[wib];
   for (int it = 0; it < 4; ++it) {
-    const long long r = w * 256 + it * 64 + lane;
+    const long long r0 = w * 256 + it * 64;
+    if (r0 >= rows) break;
+    const long long r = r0 + lane;
     const unsigned m = r < rows ? mask[r] : 0u;
+    // rows r0 .. r0+63 are contiguous in the padded map (rows_pad is a multiple of 256)
+    const int* src = map + r0 * V;
+    int tmp[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) tmp[i] = src[lane + 64 * i];
+#pragma unroll
+    for (int i = 0; i < V; ++i) ms[lane + 64 * i] = tmp[i];
+    __builtin_amdgcn_wave_barrier();
     for (int k = 0; k < V; ++k) {
       const bool bit = (m >> k) & 1u;
       const unsigned long long bal = __ballot(bit);
       const unsigned start = __shfl(base, k);
-      if (bit) pairs[start + (unsigned)__popcll(bal & lt)] = make_int2((int)r, map[r * V + k]);
+      if (bit) pairs[start + (unsigned)__popcll(bal & lt)] = make_int2((int)r, ms[lane * V + k]);
       if (lane == k) base += (unsigned)__popcll(bal);
     }
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
 // Cuts every offset's pair range into ceil(count / target) nearly equal work items.
+// One wave: lanes 0..V hold the per-offset figures, then all lanes write items in parallel.
 __global__ void __launch_bounds__(64)
     k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
                  int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
+  __shared__ unsigned s_begin[33], s_cnt[33], s_first[34];
   const int lane = threadIdx.x;
-  const unsigned begin = lane <= V ? scanned[(long long)(lane < V ? lane : V) * n_waves] : 0u;
+  const unsigned begin = lane <= V ? scanned[(long long)lane * n_waves] : 0u;  // [V * n_waves] holds the total
   const unsigned next = __shfl_down(begin, 1);
   const unsigned cnt = lane < V ? next - begin : 0u;
   if (lane <= V) seg[lane] = (int)begin;
@@ -139,17 +157,30 @@ __global__ void __launch_bounds__(64)
     const unsigned up = __shfl_up(incl, o);
     if (lane >= o) incl += up;
   }
-  const unsigned first = incl - pieces;
-  if (lane <= V) item_seg[lane] = (int)(first < (unsigned)max_items ? first : (unsigned)max_items);
-  if (lane == V) item_seg[V + 1] = (int)(first < (unsigned)max_items ? first : (unsigned)max_items);
-  for (unsigned q = 0; q < pieces; ++q) {
-    if (first + q >= (unsigned)max_items) break;  // cannot happen: max_items bounds the sum
+  unsigned first = incl - pieces;
+  if (first > (unsigned)max_items) first = (unsigned)max_items;
+  if (lane <= V) {
+    s_begin[lane] = begin;
+    s_cnt[lane] = cnt;
+    s_first[lane] = first;
+    item_seg[lane] = (int)first;
+  }
+  if (lane == V) {
+    s_first[V + 1] = first;
+    item_seg[V + 1] = (int)first;
+  }
+  __syncthreads();
+  const unsigned n_items = s_first[V];
+  for (unsigned i = lane; i < n_items; i += 64) {
+    int k = 0;
+    while (k + 1 < V && s_first[k + 1] <= i) ++k;
+    const unsigned c = s_cnt[k], pc = s_first[k + 1] - s_first[k], q = i - s_first[k];
     WgradItem w;
-    w.k = lane;
-    w.pair_begin = (int)(begin + (unsigned)(((unsigned long long)cnt * q) / pieces));
-    w.pair_end = (int)(begin + (unsigned)(((unsigned long long)cnt * (q + 1)) / pieces));
+    w.k = k;
+    w.pair_begin = (int)(s_begin[k] + (unsigned)(((unsigned long long)c * q) / pc));
+    w.pair_end = (int)(s_begin[k] + (unsigned)(((unsigned long long)c * (q + 1)) / pc));
     w.pad = 0;
-    items[first + q] = w;
+    items[i] = w;
   }
 }
 
@@ -278,8 +309,14 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
                      n_waves, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
   SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, st));
-  hipLaunchKernelGGL(k_pair_fill, dim3(blocks), dim3(256), 0, st, side.map.as<int>(), side.mask.as<unsigned>(),
-                     (long long)km->n_out, V, n_waves, counts.as<unsigned>(), p->pairs.as<int2>());
+  if (V == 27)
+    hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
+                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),
+                       p->pairs.as<int2>());
+  else
+    hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
+                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),
+                       p->pairs.as<int2>());
   SPC_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_make_items, dim3(1), dim3(64), 0, st, counts.as<unsigned>(), V, n_waves,
                      (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),

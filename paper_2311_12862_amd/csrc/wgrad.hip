@@ -225,22 +225,53 @@ __global__ void __launch_bounds__(256) k_wgrad_f32(const WgradParams p) {
   }
 }
 
-// dW[k][e] = sum of the partial tiles of offset k, in item order
+// dW[k][e] = sum of the partial tiles of offset k.  A workgroup covers 64 float4 columns; its four
+// waves take the items of the offset round-robin (four loads in flight each) and their sums are
+// added in wave order, so the order of additions is fixed and results are bit-reproducible.
 __global__ void __launch_bounds__(256) k_wgrad_reduce(const float* __restrict__ partial,
                                                       const int* __restrict__ item_seg, int elems,
                                                       float* __restrict__ dw) {
-  const int e4 = (blockIdx.x * blockDim.x + threadIdx.x) * 4;
-  if (e4 >= elems) return;
+  __shared__ float4 part[4][64];
+  const int col = threadIdx.x & 63, stripe = threadIdx.x >> 6;
+  const int e4 = (blockIdx.x * 64 + col) * 4;
   const int k = blockIdx.y;
+  const int first = item_seg[k], last = item_seg[k + 1];
   float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-  for (int it = item_seg[k]; it < item_seg[k + 1]; ++it) {
-    const float4 v = *reinterpret_cast<const float4*>(partial + (long long)it * elems + e4);
-    s.x += v.x;
-    s.y += v.y;
-    s.z += v.z;
-    s.w += v.w;
+  if (e4 < elems) {
+    int it = first + stripe;
+    for (; it + 12 < last; it += 16) {
+      float4 v[4];
+#pragma unroll
+      for (int u = 0; u < 4; ++u) v[u] = *reinterpret_cast<const float4*>(partial + (long long)(it + 4 * u) * elems + e4);
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        s.x += v[u].x;
+        s.y += v[u].y;
+        s.z += v[u].z;
+        s.w += v[u].w;
+      }
+    }
+    for (; it < last; it += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(partial + (long long)it * elems + e4);
+      s.x += v.x;
+      s.y += v.y;
+      s.z += v.z;
+      s.w += v.w;
+    }
   }
-  *reinterpret_cast<float4*>(dw + (long long)k * elems + e4) = s;
+  part[stripe][col] = s;
+  __syncthreads();
+  if (stripe == 0 && e4 < elems) {
+    float4 t = part[0][col];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      t.x += part[w][col].x;
+      t.y += part[w][col].y;
+      t.z += part[w][col].z;
+      t.w += part[w][col].w;
+    }
+    *reinterpret_cast<float4*>(dw + (long long)k * elems + e4) = t;
+  }
 }
 
 }  // namespace
@@ -277,7 +308,7 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
     }
     SPC_LAUNCH_CHECK();
   }
-  dim3 rgrid((unsigned)ceil_div(elems / 4, 256), (unsigned)V);
+  dim3 rgrid((unsigned)ceil_div(elems / 4, 64), (unsigned)V);
   hipLaunchKernelGGL(k_wgrad_reduce, rgrid, dim3(256), 0, st, km->scratch.as<float>(), wp.item_seg.as<int>(), elems,
                      dweights);
   SPC_LAUNCH_CHECK();

@@ -87,6 +87,7 @@ def _check(status: int, where: str):
 
 
 def _stream(stream):
+    """None: torch's current stream; a torch stream; or a raw hipStream_t handle as int (0 = null stream)."""
     if stream is None:
         return torch.cuda.current_stream().cuda_stream
     return stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream)

@@ -397,26 +397,40 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
       default: return spconv_wgrad(x.p, y.p, km, C_in, C_out, dtype, &c, dw.as<float>(), st);
     }
   };
+  auto elapsed = [&](float* ms) {
+    (void)hipEventRecord(e1, st);
+    (void)hipEventSynchronize(e1);
+    (void)hipEventElapsedTime(ms, e0, e1);
+  };
   for (const auto& c : cands) {
-    // mapping time: first call on dropped plans, minus a warm call
-    float t_first = 0.f, t_warm = 0.f;
-    (void)spconv_kmap_drop_plans(km);
-    (void)hipEventRecord(e0, st);
+    // mapping time: building the plan from scratch (best of two), timed apart from the kernel
+    float t_map = 1e30f;
+    for (int rep = 0; rep < 2 && status == SPCONV_OK; ++rep) {
+      (void)spconv_kmap_drop_plans(km);
+      (void)hipEventRecord(e0, st);
+      if (op == SPCONV_OP_WGRAD) {
+        WgradPlan* wp = nullptr;
+        status = wplan_get(km, c.wgrad_pairs, st, &wp);
+      } else {
+        status = spconv_kmap_prepare(km, op, &c, st);
+      }
+      float ms = 0.f;
+      elapsed(&ms);
+      t_map = std::min(t_map, ms);
+    }
+    if (status != SPCONV_OK) break;
+    // kernel time: warm, best of three groups of five
     status = run_once(c);
     if (status != SPCONV_OK) break;
-    (void)hipEventRecord(e1, st);
-    (void)hipEventSynchronize(e1);
-    (void)hipEventElapsedTime(&t_first, e0, e1);
-    const int reps = 5;
-    (void)run_once(c);
-    (void)hipEventRecord(e0, st);
-    for (int r = 0; r < reps; ++r) (void)run_once(c);
-    (void)hipEventRecord(e1, st);
-    (void)hipEventSynchronize(e1);
-    (void)hipEventElapsedTime(&t_warm, e0, e1);
-    t_warm /= reps;
-    const float mapping = std::max(0.f, t_first - t_warm);
-    const float t = t_warm + mapping / (float)layers_sharing_kmap;
+    float t_k = 1e30f;
+    for (int grp = 0; grp < 3; ++grp) {
+      (void)hipEventRecord(e0, st);
+      for (int r = 0; r < 5; ++r) (void)run_once(c);
+      float ms = 0.f;
+      elapsed(&ms);
+      t_k = std::min(t_k, ms / 5.f);
+    }
+    const float t = t_k + t_map / (float)layers_sharing_kmap;
     if (t < best_t) {
       best_t = t;
       *best = c;

@@ -140,7 +140,8 @@ int side_for(spconv_kmap* km, spconv_op op, hipStream_t st, OpSide* o) {
 }
 
 int64_t auto_wgrad_pairs(spconv_kmap* km, int C_in, int C_out) {
-  const int64_t tiles = ceil_div(C_in, 64) * ceil_div(C_out, 64);
+  const int tile = (C_in > 64 || C_out > 64) ? 128 : 64;
+  const int64_t tiles = ceil_div(C_in, tile) * ceil_div(C_out, tile);
   const int64_t want_items = std::max<int64_t>(32, 1536 / tiles);
   const int64_t pairs = km->n_pairs > 0 ? km->n_pairs : km->n_out;
   return std::max<int64_t>(1024, ceil_div(pairs, want_items));

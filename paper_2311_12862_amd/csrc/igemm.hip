@@ -1,5 +1,6 @@
 // Implicit-GEMM sparse convolution kernels (Sections 2.2.3, 3.1, 3.2, 4.1):
-// forward and input-gradient.
+// forward and input-gradient with workgroup tiles, for channel counts whose
+// weights do not fit in LDS, plus the fp32 path.
 //
 // One workgroup owns BM consecutive rows of the (possibly bitmask-sorted)
 // output-stationary map and BN output channels.  The tile's map slab is copied
@@ -7,11 +8,14 @@
 // the loop over kernel offsets visits only offsets whose bit is set in the
 // tile's mask, and every 16-row MFMA block of a wave skips offsets none of its
 // rows has (the lock-step unit of Section 2.2.3 is a 16-row block here, not a
-// 32-thread warp).  Gathered feature rows and the weight slice are staged
-// through double-buffered LDS; global loads for step i+1 are in flight while
-// step i runs on the matrix cores.  Rows of absent neighbours are zero-filled
-// by predicated loads, and the map is padded to whole tiles so that no map
-// access needs a bounds check (the padding of Section 3.2).
+// 32-thread warp).  Gathered feature rows and the weight slice of the next step
+// are loaded into registers (raw buffer loads: an absent neighbour is an
+// out-of-range offset that reads as zero, no branch) while the current step
+// runs on the matrix cores out of a single LDS stage; the small LDS footprint
+// lets several workgroups share a CU and hide each other's load latency.
+// Forward weights are stored as they arrive ([ci][co]) and read with the
+// transposing LDS read, so no software transpose is needed.  The map is padded
+// to whole tiles so that no map access needs a bounds check (Section 3.2).
 #include "common.h"
 
 namespace spc {
@@ -35,6 +39,7 @@ struct IgemmParams {
   int c_red, c_out;  // reduced / produced channel counts
   int C_in, C_out;   // of the layer
   int dgrad, mirror;
+  unsigned feats_bytes;  // size of the gathered tensor (16-bit kernels address it through a buffer descriptor)
 };
 
 template <typename T> struct Mfma;
@@ -51,10 +56,27 @@ template <> struct Mfma<__bf16> {
   }
 };
 
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+// Raw buffer loads: an absent neighbour (index -1) or a channel past the end becomes an
+// out-of-range offset, which returns zeros without touching memory and without a branch.
+__device__ __forceinline__ __amdgpu_buffer_rsrc_t make_rsrc(const void* base, unsigned bytes) {
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, bytes, 0x00020000);
+}
+__device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned byte_off) {
+  const u32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, byte_off, 0, 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
+// LDS plan of the tiled kernel.  One stage of operands (the next stage waits in registers):
+// more workgroups fit on a CU, and they hide each other's load latency.
 template <int BM, int BN, int KC> struct IgemmSmem {
-  static constexpr int LDA = KC + 8;  // row pitch in 2-byte elements (+16 B against bank conflicts)
-  static constexpr size_t a_bytes = (size_t)2 * BM * LDA * 2;
-  static constexpr size_t b_bytes = (size_t)2 * BN * LDA * 2;
+  static constexpr int LDA = KC + 8;   // A rows and dgrad weight rows: reduction index contiguous, +16 B pad
+  static constexpr int LDB = BN + 16;  // forward weight rows: output channel contiguous; pitch = 8 words mod 32
+  static constexpr size_t a_bytes = (size_t)BM * LDA * 2;
+  static constexpr size_t b_fwd = (size_t)KC * LDB * 2, b_dgrad = (size_t)BN * LDA * 2;
+  static constexpr size_t b_bytes = b_fwd > b_dgrad ? b_fwd : b_dgrad;
   static constexpr size_t map_bytes = (size_t)BM * 27 * 4;
   static constexpr size_t perm_bytes = (size_t)BM * 4;
   static constexpr size_t total = a_bytes + b_bytes + map_bytes + perm_bytes;
@@ -64,11 +86,11 @@ template <typename T, int BM, int BN, int KC>
 __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   typedef IgemmSmem<BM, BN, KC> S;
   typedef typename Mfma<T>::vec vec8;
-  constexpr int LDA = S::LDA;
+  constexpr int LDA = S::LDA, LDB = S::LDB;
   constexpr int WM = BM / 4;    // rows per wave
   constexpr int MB = WM / 16;   // 16-row MFMA blocks per wave
   constexpr int NB = BN / 16;   // 16-column MFMA blocks
-  constexpr int SEG = KC / 8;   // 16-byte segments per staged row
+  constexpr int SEG = KC / 8;   // 16-byte segments per staged A row
   constexpr int A_RPP = 256 / SEG;
   constexpr int A_PASSES = BM / A_RPP;
   constexpr int B_PASSES = (KC * BN / 8 + 255) / 256;
@@ -87,9 +109,10 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   const int width = p.width[part], lo = p.lo[part];
   const long long row0 = tile * BM;
   const unsigned tmask = p.tilemask[part][tile];
-  const unsigned short* feats = reinterpret_cast<const unsigned short*>(p.feats);
-  const unsigned short* wts = reinterpret_cast<const unsigned short*>(p.weights);
   const int c_red = p.c_red;
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 2));
+  const unsigned row_bytes = (unsigned)c_red * 2u, slice_bytes = (unsigned)(p.C_in * p.C_out) * 2u;
 
   {  // map slab and output rows of this tile
     const int* mp = p.map[part] + row0 * width;
@@ -131,65 +154,51 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   const int a_seg = tid % SEG, a_row = tid / SEG;
 
   auto load_regs = [&](int c, int chunk) {
-    const int col = chunk * KC + a_seg * 8;
+    const unsigned col = (unsigned)(chunk * KC + a_seg * 8);
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps) {
       const int idx = mapS[(a_row + ps * A_RPP) * width + c];
-      uint4 v = make_uint4(0, 0, 0, 0);
-      if (idx >= 0 && col < c_red) v = *reinterpret_cast<const uint4*>(feats + (long long)idx * c_red + col);
-      ra[ps] = v;
+      // idx = -1 wraps to just below 2^32: out of range
+      ra[ps] = buf_load16(x_rsrc, col < (unsigned)c_red ? (unsigned)idx * row_bytes + col * 2u : 0xFFFFFFFFu);
     }
     const int k = lo + c;
-    const long long wk = (long long)(p.mirror ? p.V - 1 - k : k) * p.C_in * p.C_out;
-    if (!p.dgrad) {
+    const unsigned wk = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice_bytes;
+    if (!p.dgrad) {  // rows of W[k]: reduction channel ci, 8 output channels per load
       const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
         const int kk = kk0 + ps * BF_RPP;
         const int ci = chunk * KC + kk, co = n0 + nseg * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (kk < KC && ci < p.C_in && co < p.C_out)
-          v = *reinterpret_cast<const uint4*>(wts + wk + (long long)ci * p.C_out + co);
-        rb[ps] = v;
+        const bool ok = kk < KC && ci < p.C_in && co < p.C_out;
+        rb[ps] = buf_load16(w_rsrc, ok ? wk + (unsigned)(ci * p.C_out + co) * 2u : 0xFFFFFFFFu);
       }
-    } else {
+    } else {  // rows of W[k]: output channel n = ci, 8 reduction channels (co) per load
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
         const int n = a_row + ps * A_RPP;
         const int ci = n0 + n, co = chunk * KC + a_seg * 8;
-        uint4 v = make_uint4(0, 0, 0, 0);
-        if (n < BN && ci < p.C_in && co < p.C_out)
-          v = *reinterpret_cast<const uint4*>(wts + wk + (long long)ci * p.C_out + co);
-        rb[ps] = v;
+        const bool ok = n < BN && ci < p.C_in && co < p.C_out;
+        rb[ps] = buf_load16(w_rsrc, ok ? wk + (unsigned)(ci * p.C_out + co) * 2u : 0xFFFFFFFFu);
       }
     }
   };
 
-  auto store_lds = [&](int buf) {
-    unsigned short* a = As + buf * BM * LDA;
-    unsigned short* b = Bs + buf * BN * LDA;
+  auto store_lds = [&]() {
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps)
-      *reinterpret_cast<uint4*>(a + (a_row + ps * A_RPP) * LDA + a_seg * 8) = ra[ps];
-    if (!p.dgrad) {  // forward: the weight slice arrives [ci][co]; the MFMA wants [co][ci]
+      *reinterpret_cast<uint4*>(As + (a_row + ps * A_RPP) * LDA + a_seg * 8) = ra[ps];
+    if (!p.dgrad) {  // forward: stored as loaded, [ci][co]; the transposing LDS read does the rest
       const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
         const int kk = kk0 + ps * BF_RPP;
-        if (kk < KC) {
-          const unsigned w[4] = {rb[ps].x, rb[ps].y, rb[ps].z, rb[ps].w};
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            b[(nseg * 8 + 2 * i) * LDA + kk] = (unsigned short)(w[i] & 0xFFFFu);
-            b[(nseg * 8 + 2 * i + 1) * LDA + kk] = (unsigned short)(w[i] >> 16);
-          }
-        }
+        if (kk < KC) *reinterpret_cast<uint4*>(Bs + kk * LDB + nseg * 8) = rb[ps];
       }
     } else {
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
         const int n = a_row + ps * A_RPP;
-        if (n < BN) *reinterpret_cast<uint4*>(b + n * LDA + a_seg * 8) = rb[ps];
+        if (n < BN) *reinterpret_cast<uint4*>(Bs + n * LDA + a_seg * 8) = rb[ps];
       }
     }
   };
@@ -200,27 +209,45 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
     cur_c = __ffs((int)m_rem) - 1;
     m_rem &= m_rem - 1;
     load_regs(cur_c, 0);
-    store_lds(0);
+    store_lds();
   }
   __syncthreads();
 
+  const int fa = lane & 15, fg = lane >> 4;
   for (int it = 0; it < total; ++it) {
     int nxt_c = cur_c, nxt_chunk = cur_chunk + 1;
     if (nxt_chunk == n_chunks) {
       nxt_chunk = 0;
-      nxt_c = __ffs((int)m_rem) - 1;
+      nxt_c = m_rem ? __ffs((int)m_rem) - 1 : 0;
       m_rem &= m_rem - 1;
     }
-    const bool more = (it + 1 < total);
-    if (more) load_regs(nxt_c, nxt_chunk);
+    // the loads of the next step travel while this one is on the matrix cores (past the
+    // last step they are harmless repeats of a valid step)
+    load_regs(nxt_c, nxt_chunk);
 
-    const unsigned short* a = As + (it & 1) * BM * LDA + (wave * WM + (lane & 15)) * LDA + (lane >> 4) * 8;
-    const unsigned short* b = Bs + (it & 1) * BN * LDA + (lane & 15) * LDA + (lane >> 4) * 8;
+    const unsigned short* a = As + (wave * WM + fa) * LDA + fg * 8;
 #pragma unroll
     for (int ks = 0; ks < KC / 32; ++ks) {
       vec8 bf[NB];
+      if (!p.dgrad) {
+        // 16 lanes fetch a 4 x 16 block of [ci][co] and each receives one column: 4 reduction
+        // steps of its output channel; two reads give the lane's 8 steps (ci = 8*fg .. 8*fg+7)
+        const unsigned short* b = Bs + (ks * 32 + 8 * fg + (fa >> 2)) * LDB + 4 * (fa & 3);
 #pragma unroll
-      for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDA + ks * 32);
+        for (int nb = 0; nb < NB; ++nb) {
+          const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(b + nb * 16));
+          const s16x4 hi4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+              (__attribute__((address_space(3))) s16x4*)(b + nb * 16 + 4 * LDB));
+          typedef short s16x8 __attribute__((ext_vector_type(8)));
+          const s16x8 v = {lo4[0], lo4[1], lo4[2], lo4[3], hi4[0], hi4[1], hi4[2], hi4[3]};
+          bf[nb] = __builtin_bit_cast(vec8, v);
+        }
+      } else {
+        const unsigned short* b = Bs + fa * LDA + fg * 8;
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDA + ks * 32);
+      }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         if ((blk_mask[mb] >> cur_c) & 1u) {
@@ -230,7 +257,8 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
         }
       }
     }
-    if (more) store_lds((it + 1) & 1);
+    __syncthreads();  // everyone is done reading this step's tiles
+    store_lds();
     __syncthreads();
     cur_c = nxt_c;
     cur_chunk = nxt_chunk;
@@ -454,6 +482,12 @@ int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan,
     hipLaunchKernelGGL(k_igemm_f32, grid, dim3(256), 0, st, p);
     SPC_LAUNCH_CHECK();
     return SPCONV_OK;
+  }
+  {
+    const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
+    const uint64_t bytes = (uint64_t)rows_src * p.c_red * 2;
+    if (bytes >= 0xFFFFC000ull) return SPCONV_EINVAL;  // buffer descriptors address 32 bits
+    p.feats_bytes = (unsigned)bytes;
   }
   int bn = a.tile_n;
   if (bn == 0) bn = p.c_out <= 32 ? 32 : (p.c_out <= 64 ? 64 : 128);

@@ -64,62 +64,70 @@ __device__ __forceinline__ int2 buf_load8(__amdgpu_buffer_rsrc_t r, unsigned byt
 }
 
 constexpr int WG_BK = 64;   // pairs per batch
-constexpr int WG_LD = 80;   // LDS row pitch in 2-byte elements: 64 channels + 32 bytes, so that the four
-                            // rows a transposing read touches fall on disjoint banks
 
 // Transposing read: the 16 lanes of a group together fetch a 4 (rows) x 16 (columns) block,
 // lane a pointing at row a/4, columns 4*(a%4)..+3; lane a receives column a of the block,
 // i.e. four consecutive rows of one channel.  Two reads give the 8 reduction steps of a lane.
+template <int LD>
 __device__ __forceinline__ s16x8 read_frag(const unsigned short* tile, int row0, int col0, int lane) {
   const int a = lane & 15, g = lane >> 4;
-  const unsigned short* p = tile + (row0 + 8 * g + (a >> 2)) * WG_LD + col0 + 4 * (a & 3);
+  const unsigned short* p = tile + (row0 + 8 * g + (a >> 2)) * LD + col0 + 4 * (a & 3);
   const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
       (__attribute__((address_space(3))) s16x4*)(p));
   const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-      (__attribute__((address_space(3))) s16x4*)(p + 4 * WG_LD));
+      (__attribute__((address_space(3))) s16x4*)(p + 4 * LD));
   return s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 }
 
-template <typename T>
+// TILE x TILE outputs of dW[k] per workgroup (64 or 128); each of the four waves owns a
+// TILE/2 x TILE/2 quadrant as QB x QB MFMA blocks.  A larger tile gathers every pair's rows
+// fewer times when the layer has more than 64 channels.
+template <typename T, int TILE>
 __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
-  __shared__ __align__(16) unsigned short Xs[2][WG_BK * WG_LD];  // [pair][ci]
-  __shared__ __align__(16) unsigned short Ds[2][WG_BK * WG_LD];  // [pair][co]
+  constexpr int QB = TILE / 32;        // 16 x 16 blocks per quadrant side
+  constexpr int LD = TILE + 16;        // LDS row pitch in 2-byte elements: 8 words mod 32, so that the
+                                       // four rows a transposing read touches fall on disjoint banks
+  constexpr int SEGS = TILE / 8;       // 16-byte segments per staged row
+  constexpr int PASSES = WG_BK * SEGS / 256;
+  constexpr int RPP = 256 / SEGS;      // pair rows covered per pass
+  extern __shared__ __align__(16) unsigned char smem_w[];
+  unsigned short* Xs = reinterpret_cast<unsigned short*>(smem_w);  // [2][pair][ci]
+  unsigned short* Ds = Xs + 2 * WG_BK * LD;                        // [2][pair][co]
 
   if ((int)blockIdx.x >= p.item_seg[p.V]) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const WgradItem item = p.items[blockIdx.x];
-  const int ci0 = blockIdx.y * 64, co0 = blockIdx.z * 64;
+  const int ci0 = blockIdx.y * TILE, co0 = blockIdx.z * TILE;
   const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
   const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dout, p.dout_bytes);
   const __amdgpu_buffer_rsrc_t p_rsrc = make_rsrc(p.pairs, p.pairs_bytes);
   const unsigned x_row = (unsigned)p.C_in * 2u, d_row = (unsigned)p.C_out * 2u;
 
-  // this wave's 32 x 32 quadrant of the 64 x 64 tile
-  const int wci = (wave >> 1) * 32, wco = (wave & 1) * 32;
-  f32x4 acc[2][2];
+  const int wci = (wave >> 1) * (TILE / 2), wco = (wave & 1) * (TILE / 2);
+  f32x4 acc[QB][QB];
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < QB; ++i)
 #pragma unroll
-    for (int j = 0; j < 2; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < QB; ++j) acc[i][j] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-  // staging: thread (q, seg) moves segment seg (8 channels) of pair rows q and q + 32
-  const int seg = tid & 7, q0 = tid >> 3;
+  // staging: thread (q, seg) moves segment seg (8 channels) of pair rows q, q + RPP, ...
+  const int seg = tid % SEGS, q0 = tid / SEGS;
   const bool x_ok = ci0 + seg * 8 < p.C_in, d_ok = co0 + seg * 8 < p.C_out;
   const int n_batches = (item.pair_end - item.pair_begin + WG_BK - 1) / WG_BK;
 
-  int2 pr[2];       // pair indices of the batch after next
-  uint4 rx[2], rd[2];  // rows of the next batch
+  int2 pr[PASSES];            // pair indices of the batch after next
+  uint4 rx[PASSES], rd[PASSES];  // rows of the next batch
   auto load_pairs = [&](int batch) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int e = item.pair_begin + batch * WG_BK + q0 + 32 * h;
+    for (int h = 0; h < PASSES; ++h) {
+      const int e = item.pair_begin + batch * WG_BK + q0 + RPP * h;
       pr[h] = buf_load8(p_rsrc, (batch < n_batches && e < item.pair_end) ? (unsigned)e * 8u : 0xFFFFFFFFu);
     }
   };
   auto load_rows = [&](int batch) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      const int e = item.pair_begin + batch * WG_BK + q0 + 32 * h;
+    for (int h = 0; h < PASSES; ++h) {
+      const int e = item.pair_begin + batch * WG_BK + q0 + RPP * h;
       const bool live = batch < n_batches && e < item.pair_end;
       rx[h] = buf_load16(x_rsrc, (live && x_ok) ? (unsigned)pr[h].y * x_row + (unsigned)(ci0 + seg * 8) * 2u
                                                  : 0xFFFFFFFFu);
@@ -129,9 +137,9 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
   };
   auto store_rows = [&](int buf) {
 #pragma unroll
-    for (int h = 0; h < 2; ++h) {
-      *reinterpret_cast<uint4*>(&Xs[buf][(q0 + 32 * h) * WG_LD + seg * 8]) = rx[h];
-      *reinterpret_cast<uint4*>(&Ds[buf][(q0 + 32 * h) * WG_LD + seg * 8]) = rd[h];
+    for (int h = 0; h < PASSES; ++h) {
+      *reinterpret_cast<uint4*>(Xs + (buf * WG_BK + q0 + RPP * h) * LD + seg * 8) = rx[h];
+      *reinterpret_cast<uint4*>(Ds + (buf * WG_BK + q0 + RPP * h) * LD + seg * 8) = rd[h];
     }
   };
 
@@ -143,19 +151,19 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
   for (int b = 0; b < n_batches; ++b) {
     load_rows(b + 1);   // out-of-range (zero, no traffic) past the last batch
     load_pairs(b + 2);
-    const unsigned short* xs = Xs[b & 1];
-    const unsigned short* ds = Ds[b & 1];
+    const unsigned short* xs = Xs + (b & 1) * WG_BK * LD;
+    const unsigned short* ds = Ds + (b & 1) * WG_BK * LD;
 #pragma unroll
     for (int ks = 0; ks < WG_BK / 32; ++ks) {
-      s16x8 af[2], bf[2];
+      s16x8 af[QB], bf[QB];
 #pragma unroll
-      for (int i = 0; i < 2; ++i) af[i] = read_frag(xs, ks * 32, wci + i * 16, lane);
+      for (int i = 0; i < QB; ++i) af[i] = read_frag<LD>(xs, ks * 32, wci + i * 16, lane);
 #pragma unroll
-      for (int j = 0; j < 2; ++j) bf[j] = read_frag(ds, ks * 32, wco + j * 16, lane);
+      for (int j = 0; j < QB; ++j) bf[j] = read_frag<LD>(ds, ks * 32, wco + j * 16, lane);
 #pragma unroll
-      for (int i = 0; i < 2; ++i)
+      for (int i = 0; i < QB; ++i)
 #pragma unroll
-        for (int j = 0; j < 2; ++j) acc[i][j] = Mfma<T>::run(af[i], bf[j], acc[i][j]);
+        for (int j = 0; j < QB; ++j) acc[i][j] = Mfma<T>::run(af[i], bf[j], acc[i][j]);
     }
     store_rows((b + 1) & 1);
     __syncthreads();
@@ -163,13 +171,13 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
 
   float* dst = p.partial + (long long)blockIdx.x * p.C_in * p.C_out;
 #pragma unroll
-  for (int i = 0; i < 2; ++i)
+  for (int i = 0; i < QB; ++i)
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int ci = ci0 + wci + i * 16 + (lane >> 4) * 4 + r;
       if (ci >= p.C_in) continue;
 #pragma unroll
-      for (int j = 0; j < 2; ++j) {
+      for (int j = 0; j < QB; ++j) {
         const int co = co0 + wco + j * 16 + (lane & 15);
         if (co < p.C_out) dst[(long long)ci * p.C_out + co] = acc[i][j][r];
       }
@@ -300,11 +308,29 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
   p.C_out = C_out;
   p.V = V;
   if (km->n_pairs > 0) {
-    dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, 64), (unsigned)ceil_div(C_out, 64));
-    switch (dtype) {
-      case SPCONV_F32: hipLaunchKernelGGL(k_wgrad_f32, grid, dim3(256), 0, st, p); break;
-      case SPCONV_F16: hipLaunchKernelGGL((k_wgrad<_Float16>), grid, dim3(256), 0, st, p); break;
-      case SPCONV_BF16: hipLaunchKernelGGL((k_wgrad<__bf16>), grid, dim3(256), 0, st, p); break;
+    if (dtype == SPCONV_F32) {
+      dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, 64), (unsigned)ceil_div(C_out, 64));
+      hipLaunchKernelGGL(k_wgrad_f32, grid, dim3(256), 0, st, p);
+    } else {
+      // 128 x 128 tiles as soon as a 64 x 64 tile would gather every pair's rows more than once
+      const int tile = (C_in > 64 || C_out > 64) ? 128 : 64;
+      dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, tile), (unsigned)ceil_div(C_out, tile));
+      const size_t smem = (size_t)2 * 2 * WG_BK * (tile + 16) * 2;
+      static bool attr_set = false;
+      if (!attr_set) {
+        SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad<_Float16, 128>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)8 * WG_BK * 144)));
+        SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad<__bf16, 128>),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)8 * WG_BK * 144)));
+        attr_set = true;
+      }
+      if (dtype == SPCONV_F16) {
+        if (tile == 64) hipLaunchKernelGGL((k_wgrad<_Float16, 64>), grid, dim3(256), smem, st, p);
+        else hipLaunchKernelGGL((k_wgrad<_Float16, 128>), grid, dim3(256), smem, st, p);
+      } else {
+        if (tile == 64) hipLaunchKernelGGL((k_wgrad<__bf16, 64>), grid, dim3(256), smem, st, p);
+        else hipLaunchKernelGGL((k_wgrad<__bf16, 128>), grid, dim3(256), smem, st, p);
+      }
     }
     SPC_LAUNCH_CHECK();
   }

@@ -194,6 +194,20 @@ SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km
 SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype, spconv_op op,
                 int layers_sharing_kmap, spconv_config* best, float* best_us, void* stream);
 
+/* Element-wise glue between layers of a network (not part of the paper's method: activation,
+ * residual add and their gradients), so that a whole network can run on this library's kernels.
+ *   op 0: out = max(a, 0)            (b ignored, may be NULL)
+ *   op 1: out = a + b
+ *   op 2: out = max(a + b, 0)
+ *   op 3: out = b > 0 ? a : 0        (gradient a through a ReLU whose output was b)
+ * a, b, out: device, n elements of dtype; out may alias a or b. */
+SPCONV_API int spconv_ew(int op, const void* a, const void* b, void* out, int64_t n, spconv_dtype dtype, void* stream);
+
+/* dst[r][dst_off + c] = src[r][src_off + c] for r < rows, c < cols: channel concat / split of
+ * row-major tensors with row lengths src_ld / dst_ld (elements). */
+SPCONV_API int spconv_copy_cols(const void* src, int src_ld, int src_off, void* dst, int dst_ld, int dst_off, int cols,
+                                int64_t rows, spconv_dtype dtype, void* stream);
+
 /* Device allocations made by the library go through these callbacks when set
  * (so that a framework's caching allocator can back them); NULL restores
  * hipMalloc / hipFree. */

@@ -68,6 +68,8 @@ def load_library():
         "spconv_dgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_wgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_tune": (i32, [vp, i32, i32, i32, i32, i32, cfgp, C.POINTER(C.c_float), vp]),
+        "spconv_ew": (i32, [i32, vp, vp, vp, i64, i32, vp]),
+        "spconv_copy_cols": (i32, [vp, i32, i32, vp, i32, i32, i32, i64, i32, vp]),
         "spconv_set_allocator": (i32, [vp, vp, vp]),
         "spconv_strerror": (C.c_char_p, [i32]),
         "spconv_last_hip_error": (C.c_char_p, []),
@@ -248,3 +250,31 @@ def tune(kmap: KMap, c_in: int, c_out: int, dtype, op: int, layers_sharing_kmap:
     _check(load_library().spconv_tune(kmap.handle, c_in, c_out, _DTYPES[dtype], op, layers_sharing_kmap,
                                       C.byref(best), C.byref(us), _stream(stream)), "spconv_tune")
     return best, us.value
+
+
+EW_RELU, EW_ADD, EW_ADD_RELU, EW_RELU_BWD = 0, 1, 2, 3
+
+
+def ew(op: int, a, b=None, out=None, stream=None):
+    """spconv_ew: element-wise glue (see include/spconv.h); out defaults to a new tensor like a."""
+    _dev_tensor(a)
+    if b is not None:
+        _dev_tensor(b, a.dtype)
+        if b.shape != a.shape:
+            raise ValueError("shape mismatch")
+    if out is None:
+        out = torch.empty_like(a)
+    _check(load_library().spconv_ew(op, _ptr(a), _ptr(b), _ptr(out), a.numel(), _DTYPES[a.dtype], _stream(stream)),
+           "spconv_ew")
+    return out
+
+
+def copy_cols(src, src_off: int, dst, dst_off: int, cols: int, stream=None):
+    """spconv_copy_cols on two [rows, ld] tensors."""
+    _dev_tensor(src)
+    _dev_tensor(dst, src.dtype)
+    if src.shape[0] != dst.shape[0]:
+        raise ValueError("row mismatch")
+    _check(load_library().spconv_copy_cols(_ptr(src), src.shape[1], src_off, _ptr(dst), dst.shape[1], dst_off, cols,
+                                           src.shape[0], _DTYPES[src.dtype], _stream(stream)), "spconv_copy_cols")
+    return dst

@@ -124,8 +124,9 @@ int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or nu
 // result ended up (0: buffer a, 1: buffer b).  hist must hold
 // sort_hist_elems(n) uint32.
 size_t sort_hist_elems(int64_t n);
-// Exclusive scan in place (one workgroup; meant for up to a few hundred thousand counters).
-int scan_u32_inplace(uint32_t* data, int64_t elems, hipStream_t st);
+// Exclusive scan in place; `sums` is scratch of scan_sums_elems(elems) counters.
+size_t scan_sums_elems(int64_t elems);
+int scan_u32_inplace(uint32_t* data, int64_t elems, uint32_t* sums, hipStream_t st);
 int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* val_b, int64_t n,
                    int key_bits, uint32_t* hist, hipStream_t st, int* in_b);
 // Keys only, 64-bit, on the digit positions whose bits are set in `varying`.

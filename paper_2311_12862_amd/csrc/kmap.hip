@@ -26,8 +26,9 @@ enum : unsigned long long { FLAG_RANGE = 1, FLAG_DUP = 2, FLAG_FULL = 4 };
 // up on one address.
 constexpr int kPairSlots = 64;
 struct Ctl {
-  unsigned long long flags, count, key_or, key_and, pad[12];
+  unsigned long long flags, count, pad[14];
   unsigned long long pairs[kPairSlots * 16];
+  unsigned long long key_or[kPairSlots * 16], key_and[kPairSlots * 16];  // spread like pairs
 };
 
 __device__ __forceinline__ bool coord_ok(int b, int x, int y, int z) {
@@ -91,10 +92,10 @@ __global__ void k_ctl_init(Ctl* ctl) {
   if (threadIdx.x == 0) {
     ctl->flags = 0;
     ctl->count = 0;
-    ctl->key_or = 0;
-    ctl->key_and = ~0ull;
   }
   ctl->pairs[threadIdx.x * 16] = 0;  // launched with kPairSlots threads
+  ctl->key_or[threadIdx.x * 16] = 0;
+  ctl->key_and[threadIdx.x * 16] = ~0ull;
 }
 
 // Insert key(p_j) -> j for every input row; flags range and duplicate errors.
@@ -136,15 +137,11 @@ __global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ 
       k_and = key;
     }
   }
-  // wave-aggregated append
+  // workgroup-aggregated append: one counter atomic per workgroup, ranks from ballots
+  __shared__ unsigned wave_cnt[4];
+  __shared__ unsigned long long block_base;
   const unsigned long long bal = __ballot(fresh);
-  unsigned long long base = 0;
-  if (bal != 0) {
-    const int leader = __ffsll((long long)bal) - 1;
-    if (lane == leader) base = atomicAdd(&ctl->count, (unsigned long long)__popcll(bal));
-    base = __shfl(base, leader);
-    if (fresh) ukeys[base + __popcll(bal & ((1ull << lane) - 1ull))] = key;
-  }
+  if (lane == 0) wave_cnt[wave] = (unsigned)__popcll(bal);
   for (int o = 32; o > 0; o >>= 1) {
     k_or |= __shfl_xor(k_or, o);
     k_and &= __shfl_xor(k_and, o);
@@ -155,8 +152,17 @@ __global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ 
   }
   __syncthreads();
   if (threadIdx.x == 0) {
-    atomicOr(&ctl->key_or, s_or[0] | s_or[1] | s_or[2] | s_or[3]);
-    atomicAnd(&ctl->key_and, s_and[0] & s_and[1] & s_and[2] & s_and[3]);
+    const unsigned total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    block_base = total ? atomicAdd(&ctl->count, (unsigned long long)total) : 0ull;
+    const int slot = (blockIdx.x % kPairSlots) * 16;
+    atomicOr(&ctl->key_or[slot], s_or[0] | s_or[1] | s_or[2] | s_or[3]);
+    atomicAnd(&ctl->key_and[slot], s_and[0] & s_and[1] & s_and[2] & s_and[3]);
+  }
+  __syncthreads();
+  if (fresh) {
+    unsigned before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    ukeys[block_base + before + __popcll(bal & ((1ull << lane) - 1ull))] = key;
   }
 }
 
@@ -244,8 +250,6 @@ __global__ void __launch_bounds__(256)
     if (threadIdx.x == 0) {
       ctl->flags = 0;
       ctl->count = 0;
-      ctl->key_or = 0;
-      ctl->key_and = ~0ull;
     }
     if (threadIdx.x < kPairSlots) ctl->pairs[threadIdx.x * 16] = 0;
   }
@@ -510,7 +514,12 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     U = (int64_t)h.count;
     SPC_TRY(hist.alloc(sort_hist_elems(U) * sizeof(uint32_t)));
     int in_b = 0;
-    SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, h.key_or ^ h.key_and,
+    unsigned long long key_or = 0, key_and = ~0ull;
+    for (int i = 0; i < kPairSlots; ++i) {
+      key_or |= h.key_or[i * 16];
+      key_and &= h.key_and[i * 16];
+    }
+    SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, key_or ^ key_and,
                            hist.as<uint32_t>(), st, &in_b));
     const unsigned long long* sorted = in_b ? ukeys_b.as<unsigned long long>() : ukeys_a.as<unsigned long long>();
     SPC_TRY(coarse_rows.alloc((size_t)U * 16));

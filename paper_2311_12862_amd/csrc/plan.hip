@@ -297,7 +297,8 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, 256));
   const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
   DevBuf counts;
-  SPC_TRY(counts.alloc(n_counts * sizeof(unsigned)));
+  const size_t n_sums = scan_sums_elems((int64_t)n_counts);
+  SPC_TRY(counts.alloc((n_counts + n_sums) * sizeof(unsigned)));
   SPC_TRY(p->pairs.alloc(std::max<size_t>(1, (size_t)km->n_pairs) * sizeof(int2)));
   SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int)));
   SPC_TRY(p->items.alloc((size_t)p->max_items * sizeof(WgradItem)));
@@ -308,7 +309,7 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
                      n_waves, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
-  SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, st));
+  SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, counts.as<uint32_t>() + n_counts, st));
   if (V == 27)
     hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
                        side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),

@@ -37,58 +37,67 @@ __global__ void __launch_bounds__(256) k_radix_hist(const KeyT* __restrict__ key
     for (int d = lane; d < bins; d += 64) hist[(long long)d * n_waves + w] = cnt[wib][d];
 }
 
-// Exclusive scan of `elems` counters in place, one workgroup of 1024 threads.  Tiles of 8192
-// counters pass through LDS so that global accesses are coalesced; each thread scans 8
-// consecutive counters (LDS index skewed by one word per 32 to stay off bank conflicts), a
-// wave-shuffle scan combines the threads, and a running carry links the tiles.
+// Exclusive scan of `elems` counters in place.  A workgroup of 1024 threads scans one tile of
+// 8192 counters through LDS so that global accesses are coalesced: each thread scans 8
+// consecutive counters (LDS index skewed by one word per 32 to stay off bank conflicts) and a
+// wave-shuffle scan combines the threads.  One tile: a single launch.  More: every tile is
+// scanned by its own workgroup, the tile totals are scanned by one more launch, and a third
+// adds each tile's offset.
 constexpr int kScanPer = 8;
 constexpr int kScanTile = 1024 * kScanPer;
 __device__ __forceinline__ int scan_skew(int x) { return x + (x >> 5); }
 
-__global__ void __launch_bounds__(1024) k_scan_u32(unsigned* __restrict__ data, long long elems) {
+__global__ void __launch_bounds__(1024) k_scan_tile(unsigned* __restrict__ data, long long elems,
+                                                    unsigned* __restrict__ tile_sums) {
   __shared__ unsigned tile[kScanTile + kScanTile / 32 + 8];
   __shared__ unsigned wave_sum[16];
-  __shared__ unsigned carry_s;
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  if (t == 0) carry_s = 0;
+  const long long base = (long long)blockIdx.x * kScanTile;
+#pragma unroll
+  for (int i = 0; i < kScanPer; ++i) {
+    const long long g = base + i * 1024 + t;
+    tile[scan_skew(i * 1024 + t)] = g < elems ? data[g] : 0u;
+  }
   __syncthreads();
-  for (long long base = 0; base < elems; base += kScanTile) {
+  unsigned v[kScanPer], sum = 0;
 #pragma unroll
-    for (int i = 0; i < kScanPer; ++i) {
-      const long long g = base + i * 1024 + t;
-      tile[scan_skew(i * 1024 + t)] = g < elems ? data[g] : 0u;
-    }
-    __syncthreads();
-    unsigned v[kScanPer], sum = 0;
+  for (int i = 0; i < kScanPer; ++i) {
+    v[i] = tile[scan_skew(t * kScanPer + i)];
+    sum += v[i];
+  }
+  unsigned incl = sum;  // inclusive scan across the wave
 #pragma unroll
-    for (int i = 0; i < kScanPer; ++i) {
-      v[i] = tile[scan_skew(t * kScanPer + i)];
-      sum += v[i];
-    }
-    unsigned incl = sum;  // inclusive scan across the wave
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();
+  unsigned before = 0;
+  for (int w = 0; w < wave; ++w) before += wave_sum[w];
+  unsigned run = before + incl - sum;
 #pragma unroll
-    for (int o = 1; o < 64; o <<= 1) {
-      const unsigned up = __shfl_up(incl, o);
-      if (lane >= o) incl += up;
-    }
-    if (lane == 63) wave_sum[wave] = incl;
-    __syncthreads();
-    unsigned before = carry_s;
-    for (int w = 0; w < wave; ++w) before += wave_sum[w];
-    unsigned run = before + incl - sum;
+  for (int i = 0; i < kScanPer; ++i) {
+    tile[scan_skew(t * kScanPer + i)] = run;
+    run += v[i];
+  }
+  if (t == 1023 && tile_sums) tile_sums[blockIdx.x] = run;  // the tile's total
+  __syncthreads();
 #pragma unroll
-    for (int i = 0; i < kScanPer; ++i) {
-      tile[scan_skew(t * kScanPer + i)] = run;
-      run += v[i];
-    }
-    __syncthreads();
-    if (t == 1023) carry_s = run;  // the last thread ends with the tile's grand total added
+  for (int i = 0; i < kScanPer; ++i) {
+    const long long g = base + i * 1024 + t;
+    if (g < elems) data[g] = tile[scan_skew(i * 1024 + t)];
+  }
+}
+
+__global__ void __launch_bounds__(1024) k_scan_add(unsigned* __restrict__ data, long long elems,
+                                                   const unsigned* __restrict__ tile_offs) {
+  const unsigned off = tile_offs[blockIdx.x];
+  const long long base = (long long)blockIdx.x * kScanTile;
 #pragma unroll
-    for (int i = 0; i < kScanPer; ++i) {
-      const long long g = base + i * 1024 + t;
-      if (g < elems) data[g] = tile[scan_skew(i * 1024 + t)];
-    }
-    __syncthreads();
+  for (int i = 0; i < kScanPer; ++i) {
+    const long long g = base + i * 1024 + threadIdx.x;
+    if (g < elems) data[g] += off;
   }
 }
 
@@ -132,6 +141,10 @@ __global__ void __launch_bounds__(256)
   }
 }
 
+// the histogram matrix is followed by the scan's tile-total scratch
+size_t hist_matrix_elems(int64_t n) { return (size_t)ceil_div(n > 0 ? n : 1, kItemsPerWave) * kMaxBins; }
+uint32_t* hist_sums_of(uint32_t* hist, int64_t n) { return hist + hist_matrix_elems(n); }
+
 template <typename KeyT, bool HAS_VAL>
 int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n, int shift, int bits,
                uint32_t* hist, hipStream_t st) {
@@ -140,8 +153,7 @@ int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n
   hipLaunchKernelGGL((k_radix_hist<KeyT>), dim3(blocks), dim3(256), 0, st, kin, (long long)n, shift, bits, hist,
                      n_waves);
   SPC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, st, hist, ((long long)n_waves) << bits);
-  SPC_LAUNCH_CHECK();
+  SPC_TRY(scan_u32_inplace(hist, ((int64_t)n_waves) << bits, hist_sums_of(hist, n), st));
   hipLaunchKernelGGL((k_radix_scatter<KeyT, HAS_VAL>), dim3(blocks), dim3(256), 0, st, kin, kout, vin, vout,
                      (long long)n, shift, bits, hist, n_waves);
   SPC_LAUNCH_CHECK();
@@ -150,14 +162,28 @@ int radix_pass(const KeyT* kin, KeyT* kout, const int* vin, int* vout, int64_t n
 
 }  // namespace
 
-int scan_u32_inplace(uint32_t* data, int64_t elems, hipStream_t st) {
+// `sums` must hold scan_sums_elems(elems) counters of scratch.
+size_t scan_sums_elems(int64_t elems) { return (size_t)ceil_div(elems > 0 ? elems : 1, kScanTile); }
+
+int scan_u32_inplace(uint32_t* data, int64_t elems, uint32_t* sums, hipStream_t st) {
   if (elems <= 0) return SPCONV_OK;
-  hipLaunchKernelGGL(k_scan_u32, dim3(1), dim3(1024), 0, st, data, (long long)elems);
+  const int64_t tiles = ceil_div(elems, kScanTile);
+  if (tiles == 1) {
+    hipLaunchKernelGGL(k_scan_tile, dim3(1), dim3(1024), 0, st, data, (long long)elems, (unsigned*)nullptr);
+    SPC_LAUNCH_CHECK();
+    return SPCONV_OK;
+  }
+  if (tiles > kScanTile) return SPCONV_EINVAL;  // 67M counters: far beyond what the callers produce
+  hipLaunchKernelGGL(k_scan_tile, dim3((unsigned)tiles), dim3(1024), 0, st, data, (long long)elems, sums);
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_scan_tile, dim3(1), dim3(1024), 0, st, sums, (long long)tiles, (unsigned*)nullptr);
+  SPC_LAUNCH_CHECK();
+  hipLaunchKernelGGL(k_scan_add, dim3((unsigned)tiles), dim3(1024), 0, st, data, (long long)elems, sums);
   SPC_LAUNCH_CHECK();
   return SPCONV_OK;
 }
 
-size_t sort_hist_elems(int64_t n) { return (size_t)ceil_div(n > 0 ? n : 1, kItemsPerWave) * kMaxBins; }
+size_t sort_hist_elems(int64_t n) { return hist_matrix_elems(n) + scan_sums_elems((int64_t)hist_matrix_elems(n)); }
 
 int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* val_b, int64_t n, int key_bits,
                    uint32_t* hist, hipStream_t st, int* in_b) {

@@ -116,6 +116,20 @@ typedef struct spconv_config {
 SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int stride, int transposed,
                       void* stream, spconv_kmap** out);
 
+/* The same build without the synchronisation, for pipelines that must not stall: for K = 3,
+ * stride 1, transposed 0 the call only enqueues work and returns a usable kmap at once; range
+ * and duplicate errors stay on the device until spconv_kmap_status is called (any time later,
+ * typically one iteration behind).  Until then the pair count is unknown: wgrad sizes its work
+ * list from the bound n_out * K^3 (surplus workgroups exit immediately).  A kmap built from
+ * invalid rows is safe to run (all indices stay in range) but its results are meaningless.
+ * Other map kinds are built synchronously, exactly as by spconv_build_kmap. */
+SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, int stride, int transposed,
+                                       void* stream, spconv_kmap** out);
+
+/* Resolves an asynchronous build: synchronises `stream`, returns SPCONV_OK, SPCONV_ERANGE or
+ * SPCONV_EDUP, and makes the pair count available.  SPCONV_OK at once for other kmaps. */
+SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream);
+
 /* Row counts of the two sides of the map and the number of present pairs
  * sum_k |M_k| (the "effective MACs" of Section 2.2.3 in units of
  * C_in*C_out).  Any pointer may be NULL.  Asking for n_pairs the first time

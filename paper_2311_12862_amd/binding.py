@@ -54,6 +54,8 @@ def load_library():
     cfgp = C.POINTER(Config)
     protos = {
         "spconv_build_kmap": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
+        "spconv_build_kmap_async": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
+        "spconv_kmap_status": (i32, [vp, vp]),
         "spconv_kmap_sizes": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]),
         "spconv_kmap_out_coords": (i32, [vp, vp, vp]),
         "spconv_kmap_in_coords": (i32, [vp, vp, vp]),
@@ -128,6 +130,10 @@ class KMap:
             raise ValueError("kmap was destroyed")
         return self._h
 
+    def status(self, stream=None):
+        """spconv_kmap_status: raises on a range / duplicate error of an asynchronous build."""
+        _check(load_library().spconv_kmap_status(self.handle, _stream(stream)), "spconv_kmap_status")
+
     def n_pairs(self) -> int:
         v = C.c_int64()
         _check(load_library().spconv_kmap_sizes(self.handle, None, None, C.byref(v)), "spconv_kmap_sizes")
@@ -184,14 +190,17 @@ class KMap:
             pass
 
 
-def build_kmap(coords, K: int = 3, stride: int = 1, transposed: bool = False, stream=None) -> KMap:
-    """spconv_build_kmap: coords is an int32 device tensor [N, 4] = (b, x, y, z)."""
+def build_kmap(coords, K: int = 3, stride: int = 1, transposed: bool = False, stream=None,
+               asynchronous: bool = False) -> KMap:
+    """spconv_build_kmap (or spconv_build_kmap_async): coords is an int32 device tensor [N, 4] = (b, x, y, z)."""
     _dev_tensor(coords, torch.int32)
     if coords.ndim != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be [N, 4]")
     h = C.c_void_p()
-    _check(load_library().spconv_build_kmap(_ptr(coords), coords.shape[0], K, stride, int(transposed),
-                                            _stream(stream), C.byref(h)), "spconv_build_kmap")
+    lib = load_library()
+    fn, name = (lib.spconv_build_kmap_async, "spconv_build_kmap_async") if asynchronous else \
+               (lib.spconv_build_kmap, "spconv_build_kmap")
+    _check(fn(_ptr(coords), coords.shape[0], K, stride, int(transposed), _stream(stream), C.byref(h)), name)
     return KMap(h, K)
 
 

@@ -143,7 +143,7 @@ int64_t auto_wgrad_pairs(spconv_kmap* km, int C_in, int C_out) {
   const int tile = (C_in > 64 || C_out > 64) ? 128 : 64;
   const int64_t tiles = ceil_div(C_in, tile) * ceil_div(C_out, tile);
   const int64_t want_items = std::max<int64_t>(32, 1536 / tiles);
-  const int64_t pairs = km->n_pairs > 0 ? km->n_pairs : km->n_out;
+  const int64_t pairs = km->n_pairs > 0 ? km->n_pairs : km->n_out * 4;  // unknown while a build is pending
   return std::max<int64_t>(1024, ceil_div(pairs, want_items));
 }
 
@@ -203,7 +203,23 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
   if (K != 1 && K != 3) return SPCONV_EINVAL;
   if (stride < 1 || stride > 64) return SPCONV_EINVAL;
   if (transposed != 0 && transposed != 1) return SPCONV_EINVAL;
-  return kmap_build(coords, N, K, stride, transposed, (hipStream_t)stream, out);
+  return kmap_build(coords, N, K, stride, transposed, false, (hipStream_t)stream, out);
+}
+
+SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, int stride, int transposed,
+                                       void* stream, spconv_kmap** out) {
+  if (!out) return SPCONV_EINVAL;
+  *out = nullptr;
+  if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
+  if (K != 1 && K != 3) return SPCONV_EINVAL;
+  if (stride < 1 || stride > 64) return SPCONV_EINVAL;
+  if (transposed != 0 && transposed != 1) return SPCONV_EINVAL;
+  return kmap_build(coords, N, K, stride, transposed, true, (hipStream_t)stream, out);
+}
+
+SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream) {
+  if (!km) return SPCONV_EINVAL;
+  return kmap_status(km, (hipStream_t)stream);
 }
 
 SPCONV_API int spconv_kmap_sizes(const spconv_kmap* km, int64_t* n_in, int64_t* n_out, int64_t* n_pairs) {
@@ -330,7 +346,7 @@ SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
-  if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));
+  if (km->n_pairs < 0 && !km->pending) SPC_TRY(kmap_count_pairs(km, st, nullptr));
   const int64_t target = c.wgrad_pairs > 0 ? c.wgrad_pairs : auto_wgrad_pairs(km, C_in, C_out);
   WgradPlan* wp = nullptr;
   SPC_TRY(wplan_get(km, target, st, &wp));

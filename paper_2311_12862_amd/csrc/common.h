@@ -82,7 +82,8 @@ struct WgradItem {
 struct WgradPlan {
   int64_t target_pairs = 0;
   int max_items = 0;  // launch bound: V + ceil(n_pairs / target_pairs)
-  DevBuf pairs;       // int2 [n_pairs]: (output row n, input row j), offset-major
+  DevBuf pairs;       // int2 [pairs_cap]: (output row n, input row j), offset-major
+  int64_t pairs_cap = 0;  // n_pairs, or the bound n_out * V while an asynchronous build is pending
   DevBuf seg;         // int32 [V+1]: pairs of offset k are seg[k]..seg[k+1]
   DevBuf items;       // WgradItem [max_items]
   DevBuf item_seg;    // int32 [V+2]: items of offset k are item_seg[k]..item_seg[k+1]; [V+1] = n_items
@@ -107,14 +108,21 @@ struct spconv_kmap {
   spc::SideMap in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)
   std::map<int64_t, std::unique_ptr<spc::WgradPlan>> wplans;  // by target_pairs
   spc::DevBuf scratch;    // split partial sums / wgrad partial tiles
+  // asynchronous build whose status was not read yet: device control block, its pinned host
+  // copy (already enqueued behind the build) and the event that marks the copy's completion
+  spc::DevBuf pending_ctl;
+  void* pending_host = nullptr;
+  bool pending = false;
+  ~spconv_kmap();
   bool submanifold() const { return stride == 1 && !transposed; }
 };
 
 namespace spc {
 
 // ---- kmap.hip
-int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, hipStream_t st,
+int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
                spconv_kmap** out);
+int kmap_status(spconv_kmap* km, hipStream_t st);  // resolves a pending asynchronous build (synchronises)
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);
 

@@ -13,6 +13,7 @@
 #include <algorithm>
 #include <mutex>
 #include <new>
+#include <vector>
 
 namespace spc {
 namespace {
@@ -381,6 +382,42 @@ int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st) {
   return SPCONV_OK;
 }
 
+// Pool of pinned control blocks, each with the event that marks the end of its copy.
+struct HostCtl {
+  Ctl ctl;
+  hipEvent_t done;
+};
+std::mutex g_host_mu;
+std::vector<HostCtl*> g_host_free;
+
+HostCtl* host_ctl_acquire() {
+  {
+    std::lock_guard<std::mutex> lk(g_host_mu);
+    if (!g_host_free.empty()) {
+      HostCtl* h = g_host_free.back();
+      g_host_free.pop_back();
+      return h;
+    }
+  }
+  void* p = nullptr;
+  if (hipHostMalloc(&p, sizeof(HostCtl), hipHostMallocDefault) != hipSuccess) {
+    (void)hipGetLastError();
+    return nullptr;
+  }
+  HostCtl* h = static_cast<HostCtl*>(p);
+  if (hipEventCreateWithFlags(&h->done, hipEventDisableTiming) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipHostFree(p);
+    return nullptr;
+  }
+  return h;
+}
+
+void host_ctl_release(HostCtl* h) {
+  std::lock_guard<std::mutex> lk(g_host_mu);
+  g_host_free.push_back(h);
+}
+
 // Reads the control block back through a pinned staging buffer (one per process) and
 // synchronises the stream.
 int read_ctl(const Ctl* ctl, Ctl* host, hipStream_t st) {
@@ -410,7 +447,7 @@ int flags_status(const Ctl& h) {
 }
 
 // Submanifold 3x3x3 build: three launches (init, insert, symmetric probe) and one readback.
-int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, hipStream_t st) {
+int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async, hipStream_t st) {
   const int V = 27;
   DevBuf ctl_buf, tab, own_rows;
   SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
@@ -434,14 +471,27 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, hipStream_t
   hipLaunchKernelGGL(k_probe_sym3, dim3(blocks_for(ceil_div(N, 4), 4)), dim3(256), 0, st, rows, (int)N,
                      tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl);
   SPC_LAUNCH_CHECK();
-  Ctl h{};
-  SPC_TRY(read_ctl(ctl, &h, st));
-  SPC_TRY(flags_status(h));
-  int64_t pairs = 0;
-  for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
   km->n_in = km->n_out = N;
-  km->n_pairs = pairs;
   side.ready = true;
+  HostCtl* hc = async ? host_ctl_acquire() : nullptr;
+  if (hc) {
+    // the control block travels to pinned memory right behind the probe; spconv_kmap_status
+    // later waits for that copy only, not for whatever else has been enqueued since
+    SPC_HIP(hipMemcpyAsync(&hc->ctl, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
+    SPC_HIP(hipEventRecord(hc->done, st));
+    std::swap(km->pending_ctl.p, ctl_buf.p);
+    std::swap(km->pending_ctl.bytes, ctl_buf.bytes);
+    km->pending_host = hc;
+    km->pending = true;
+    km->n_pairs = -1;
+  } else {
+    Ctl h{};
+    SPC_TRY(read_ctl(ctl, &h, st));
+    SPC_TRY(flags_status(h));
+    int64_t pairs = 0;
+    for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+    km->n_pairs = pairs;
+  }
   std::swap(km->in_coords.p, own_rows.p);  // P_out == P_in: out_coords stays empty
   std::swap(km->in_coords.bytes, own_rows.bytes);
   return SPCONV_OK;
@@ -449,7 +499,32 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, hipStream_t
 
 }  // namespace
 
-int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, hipStream_t st,
+struct HostCtlHandle {
+  static void finish(void* p) {
+    HostCtl* hc = static_cast<HostCtl*>(p);
+    (void)hipEventSynchronize(hc->done);
+    host_ctl_release(hc);
+  }
+};
+
+int kmap_status(spconv_kmap* km, hipStream_t st) {
+  (void)st;
+  if (!km->pending) return SPCONV_OK;
+  HostCtl* hc = static_cast<HostCtl*>(km->pending_host);
+  SPC_HIP(hipEventSynchronize(hc->done));
+  const Ctl& h = hc->ctl;
+  int64_t pairs = 0;
+  for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+  const int status = flags_status(h);
+  km->n_pairs = pairs;
+  km->pending = false;
+  km->pending_host = nullptr;
+  km->pending_ctl.release();
+  host_ctl_release(hc);
+  return status;
+}
+
+int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
                spconv_kmap** out) {
   std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
   if (!km) return SPCONV_ENOMEM;
@@ -474,7 +549,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
 
   const int4* rows = reinterpret_cast<const int4*>(coords);
   if (K == 3 && stride == 1 && !transposed) {
-    SPC_TRY(build_submanifold3(km.get(), rows, N, st));
+    SPC_TRY(build_submanifold3(km.get(), rows, N, async, st));
     *out = km.release();
     return SPCONV_OK;
   }
@@ -618,6 +693,7 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
 }
 
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
+  if (km->pending && !per_k) return kmap_status(km, st) == SPCONV_EHIP ? SPCONV_EHIP : SPCONV_OK;
   unsigned long long h[32] = {0};
   if (km->n_out > 0) {
     DevBuf counts;
@@ -640,3 +716,9 @@ int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
 }
 
 }  // namespace spc
+
+spconv_kmap::~spconv_kmap() {
+  if (pending_host) {  // the copy into the pinned block must have landed before the block is reused
+    spc::HostCtlHandle::finish(pending_host);
+  }
+}

@@ -100,6 +100,7 @@ __global__ void __launch_bounds__(256)
     }
   }
   if (lane < V) counts[(long long)lane * n_waves + w] = mine;
+  if (w == 0 && lane == 63) counts[(long long)V * n_waves] = 0;  // the slot that will receive the total
 }
 
 // Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.  The 64
@@ -142,43 +143,47 @@ __global__ void __launch_bounds__(256)
 
 // Cuts every offset's pair range into ceil(count / target) nearly equal work items.
 // One wave: lanes 0..V hold the per-offset figures, then all lanes write items in parallel.
-__global__ void __launch_bounds__(64)
+__global__ void __launch_bounds__(256)
     k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
                  int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
   __shared__ unsigned s_begin[33], s_cnt[33], s_first[34];
   const int lane = threadIdx.x;
-  const unsigned begin = lane <= V ? scanned[(long long)lane * n_waves] : 0u;  // [V * n_waves] holds the total
-  const unsigned next = __shfl_down(begin, 1);
-  const unsigned cnt = lane < V ? next - begin : 0u;
-  if (lane <= V) seg[lane] = (int)begin;
-  const unsigned pieces = cnt ? (cnt + target - 1) / target : 0u;
-  unsigned incl = pieces;
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  unsigned first = incl - pieces;
-  if (first > (unsigned)max_items) first = (unsigned)max_items;
-  if (lane <= V) {
-    s_begin[lane] = begin;
-    s_cnt[lane] = cnt;
-    s_first[lane] = first;
-    item_seg[lane] = (int)first;
-  }
-  if (lane == V) {
-    s_first[V + 1] = first;
-    item_seg[V + 1] = (int)first;
+  if (lane < 64) {  // the first wave works out the per-offset figures
+    const unsigned begin = lane <= V ? scanned[(long long)lane * n_waves] : 0u;  // [V * n_waves] holds the total
+    const unsigned next = __shfl_down(begin, 1);
+    const unsigned cnt = lane < V ? next - begin : 0u;
+    if (lane <= V) seg[lane] = (int)begin;
+    const unsigned pieces = cnt ? (cnt + target - 1) / target : 0u;
+    unsigned incl = pieces;
+    for (int o = 1; o < 64; o <<= 1) {
+      const unsigned up = __shfl_up(incl, o);
+      if (lane >= o) incl += up;
+    }
+    unsigned first = incl - pieces;
+    if (first > (unsigned)max_items) first = (unsigned)max_items;
+    if (lane <= V) {
+      s_begin[lane] = begin;
+      s_cnt[lane] = cnt;
+      s_first[lane] = first;
+      item_seg[lane] = (int)first;
+    }
+    if (lane == V) {
+      s_first[V + 1] = first;
+      item_seg[V + 1] = (int)first;
+    }
   }
   __syncthreads();
   const unsigned n_items = s_first[V];
-  for (unsigned i = lane; i < n_items; i += 64) {
+  for (unsigned i = lane; i < n_items; i += blockDim.x) {
     int k = 0;
     while (k + 1 < V && s_first[k + 1] <= i) ++k;
     const unsigned c = s_cnt[k], pc = s_first[k + 1] - s_first[k], q = i - s_first[k];
+    // c * q / pc without 64-bit division: c = a * pc + r
+    const unsigned a = c / pc, r = c - a * pc;
     WgradItem w;
     w.k = k;
-    w.pair_begin = (int)(s_begin[k] + (unsigned)(((unsigned long long)c * q) / pc));
-    w.pair_end = (int)(s_begin[k] + (unsigned)(((unsigned long long)c * (q + 1)) / pc));
+    w.pair_begin = (int)(s_begin[k] + a * q + (unsigned)(((unsigned long long)r * q) / pc));
+    w.pair_end = (int)(s_begin[k] + a * (q + 1) + (unsigned)(((unsigned long long)r * (q + 1)) / pc));
     w.pad = 0;
     items[i] = w;
   }
@@ -287,24 +292,26 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
     *out = it->second.get();
     return SPCONV_OK;
   }
-  if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));  // only maps built with stride > 1
+  // The pair count is known after a synchronous submanifold build.  While an asynchronous build is
+  // pending, sizes come from the bound n_out * V (surplus workgroups exit at once); maps built with
+  // stride > 1 count their pairs here (one synchronisation).
+  if (km->n_pairs < 0 && !km->pending) SPC_TRY(kmap_count_pairs(km, st, nullptr));
   std::unique_ptr<WgradPlan> p(new (std::nothrow) WgradPlan);
   if (!p) return SPCONV_ENOMEM;
   const int V = km->V;
   const SideMap& side = km->out_side;
   p->target_pairs = target_pairs;
-  p->max_items = (int)std::min<int64_t>(V + ceil_div(km->n_pairs, target_pairs), 1 << 20);
+  p->pairs_cap = km->n_pairs >= 0 ? km->n_pairs : km->n_out * V;
+  p->max_items = (int)std::min<int64_t>(V + ceil_div(p->pairs_cap, target_pairs), 1 << 20);
   const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, 256));
   const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
   DevBuf counts;
   const size_t n_sums = scan_sums_elems((int64_t)n_counts);
   SPC_TRY(counts.alloc((n_counts + n_sums) * sizeof(unsigned)));
-  SPC_TRY(p->pairs.alloc(std::max<size_t>(1, (size_t)km->n_pairs) * sizeof(int2)));
+  SPC_TRY(p->pairs.alloc(std::max<size_t>(1, (size_t)p->pairs_cap) * sizeof(int2)));
   SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int)));
   SPC_TRY(p->items.alloc((size_t)p->max_items * sizeof(WgradItem)));
   SPC_TRY(p->item_seg.alloc((size_t)(V + 2) * sizeof(int)));
-  // (fill kernels instead of memsets keep these calls usable under stream capture)
-  SPC_HIP(hipMemsetAsync(counts.p, 0, n_counts * sizeof(unsigned), st));
   const unsigned blocks = blocks_for(n_waves, 4);
   hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
                      n_waves, counts.as<unsigned>());
@@ -319,7 +326,7 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
                        side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),
                        p->pairs.as<int2>());
   SPC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_make_items, dim3(1), dim3(64), 0, st, counts.as<unsigned>(), V, n_waves,
+  hipLaunchKernelGGL(k_make_items, dim3(1), dim3(256), 0, st, counts.as<unsigned>(), V, n_waves,
                      (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
                      p->item_seg.as<int>());
   SPC_LAUNCH_CHECK();

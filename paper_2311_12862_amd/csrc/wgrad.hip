@@ -290,7 +290,7 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
   const int elems = C_in * C_out;
   const size_t e = dtype == SPCONV_F32 ? 4 : 2;
   const uint64_t feats_bytes = (uint64_t)km->n_in * C_in * e, dout_bytes = (uint64_t)km->n_out * C_out * e;
-  const uint64_t pairs_bytes = (uint64_t)std::max<int64_t>(km->n_pairs, 0) * 8;
+  const uint64_t pairs_bytes = (uint64_t)std::max<int64_t>(wp.pairs_cap, 0) * 8;
   if (dtype != SPCONV_F32 && (feats_bytes >= 0xFFFFC000ull || dout_bytes >= 0xFFFFC000ull || pairs_bytes >= 0xFFFFC000ull))
     return SPCONV_EINVAL;  // buffer descriptors address 32 bits
   SPC_TRY(km->scratch.reserve((size_t)wp.max_items * elems * sizeof(float)));
@@ -307,7 +307,7 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
   p.C_in = C_in;
   p.C_out = C_out;
   p.V = V;
-  if (km->n_pairs > 0) {
+  if (wp.pairs_cap > 0) {
     if (dtype == SPCONV_F32) {
       dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, 64), (unsigned)ceil_div(C_out, 64));
       hipLaunchKernelGGL(k_wgrad_f32, grid, dim3(256), 0, st, p);

@@ -222,3 +222,17 @@ def test_tune_returns_a_valid_config(sp, cloud):
         assert 0 <= best.n_split <= 4
     best, _ = sp.tune(km, 64, 64, torch.float16, sp.OP_FWD, 1)
     assert norm_err(sp.fwd(x, w, km, best), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+
+
+def test_layer_on_a_pending_asynchronous_kmap(sp, cloud):
+    """fwd / dgrad / wgrad may run before the build's status has been read (wgrad then sizes its
+    work list from the bound n_out * 27)."""
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 81)
+    km = sp.build_kmap(coords_dev(c), 3, 1, asynchronous=True)
+    y, dx, dw = sp.fwd(x, w, km), sp.dgrad(g, w, km), sp.wgrad(x, g, km)
+    km.status()
+    assert norm_err(y, oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(dx, oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    assert norm_err(dw, oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    assert torch.equal(dw, sp.wgrad(x, g, km))

@@ -108,3 +108,30 @@ def test_build_is_deterministic(sp):
     b = sp.build_kmap(coords_dev(c), 3, 2)
     assert torch.equal(a.export(), b.export())
     assert torch.equal(a.out_coords(), b.out_coords())
+
+
+def test_asynchronous_build(sp):
+    """spconv_build_kmap_async returns at once; errors and the pair count arrive with spconv_kmap_status."""
+    c = gen.lidar_scene(11, target_n=6000)
+    ref = oc.build_kmap(c, 3, 1)
+    km = sp.build_kmap(coords_dev(c), 3, 1, asynchronous=True)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    np.testing.assert_array_equal(km.export_mask().cpu().numpy().view(np.uint32), oc.bitmask(ref.M))
+    km.status()
+    assert km.n_pairs() == int((ref.M >= 0).sum())
+    dup = c.copy()
+    dup[5] = dup[77]
+    km = sp.build_kmap(coords_dev(dup), 3, 1, asynchronous=True)
+    with pytest.raises(sp.SpconvError) as e:
+        km.status()
+    assert e.value.status == -3
+    km.status()  # the error was delivered once; the handle stays usable for destroy
+    bad = c.copy()
+    bad[9, 2] = 40000
+    km = sp.build_kmap(coords_dev(bad), 3, 1, asynchronous=True)
+    with pytest.raises(sp.SpconvError) as e:
+        km.status()
+    assert e.value.status == -2
+    # map kinds without an asynchronous path are built synchronously by the same call
+    km = sp.build_kmap(coords_dev(c), 3, 2, asynchronous=True)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)

@@ -108,10 +108,10 @@ struct spconv_kmap {
   spc::SideMap in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)
   std::map<int64_t, std::unique_ptr<spc::WgradPlan>> wplans;  // by target_pairs
   spc::DevBuf scratch;    // split partial sums / wgrad partial tiles
-  // asynchronous build whose status was not read yet: device control block, its pinned host
-  // copy (already enqueued behind the build) and the event that marks the copy's completion
-  spc::DevBuf pending_ctl;
+  // build whose status was not read yet: the pinned block the probe kernel publishes flags and
+  // pair count to, with the event that marks the probe's completion
   void* pending_host = nullptr;
+  spc::DevBuf pending_ctl;  // device control block, kept until the publish kernel has read it
   bool pending = false;
   ~spconv_kmap();
   bool submanifold() const { return stride == 1 && !transposed; }

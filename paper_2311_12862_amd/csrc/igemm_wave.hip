@@ -52,6 +52,7 @@ struct WaveParams {
   const int* map[kMaxSplit];
   const int* perm[kMaxSplit];
   const unsigned* blkmask[kMaxSplit];
+  const unsigned* rowmask;  // unsorted maps: per-row masks; the 16-row block mask is their OR (no plan kernel)
   int lo[kMaxSplit], width[kMaxSplit];
   long long rows, n_blocks;
   int parts, V;
@@ -130,7 +131,7 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       const int e = lane + 64 * i;
       mreg[i] = mp[e < map_len ? e : map_len - 1];
     }
-    bm_next = bmask[b];
+    bm_next = p.rowmask ? p.rowmask[b * 16 + arow] : bmask[b];  // OR-reduced when the block starts
     const long long g = b * 16 + arow;
     orow_next = pm ? pm[g] : (g < p.rows ? (int)g : -1);
   };
@@ -159,7 +160,14 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       const int e = lane + 64 * i;
       if (e < map_len) mapW[e] = mreg[i];
     }
-    m = __builtin_amdgcn_readfirstlane(bm_next);
+    unsigned bm = bm_next;
+    if (p.rowmask) {  // lanes 0..15 (and their three copies) hold the rows' masks
+      bm |= __shfl_xor(bm, 1);
+      bm |= __shfl_xor(bm, 2);
+      bm |= __shfl_xor(bm, 4);
+      bm |= __shfl_xor(bm, 8);
+    }
+    m = __builtin_amdgcn_readfirstlane(bm);
     prefetch_block(b_next_next < p.n_blocks ? b_next_next : p.n_blocks - 1);
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
@@ -416,6 +424,7 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
     if (plan.n_split == 0) {
       p.map[i] = side.map.as<int>();
       p.perm[i] = nullptr;
+      p.rowmask = side.mask.as<unsigned>();
     } else {
       p.map[i] = plan.maps.as<int>() + plan.map_off[i];
       p.perm[i] = plan.perm.as<int>() + (size_t)i * plan.rows_pad;

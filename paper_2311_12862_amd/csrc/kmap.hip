@@ -30,6 +30,14 @@ struct Ctl {
   unsigned long long flags, count, pad[14];
   unsigned long long pairs[kPairSlots * 16];
   unsigned long long key_or[kPairSlots * 16], key_and[kPairSlots * 16];  // spread like pairs
+  unsigned tick[kPairSlots * 16];  // arrivals per pair slot (submanifold probe)
+  unsigned tick_top, pad2[15];     // pair slots whose workgroups have all arrived
+};
+
+// What a submanifold build hands to the host: written by the probe straight into pinned host
+// memory, so that no copy has to be enqueued behind the build.
+struct HostResult {
+  unsigned long long flags, pairs;
 };
 
 __device__ __forceinline__ bool coord_ok(int b, int x, int y, int z) {
@@ -252,7 +260,11 @@ __global__ void __launch_bounds__(256)
       ctl->flags = 0;
       ctl->count = 0;
     }
-    if (threadIdx.x < kPairSlots) ctl->pairs[threadIdx.x * 16] = 0;
+    if (threadIdx.x < kPairSlots) {
+      ctl->pairs[threadIdx.x * 16] = 0;
+      ctl->tick[threadIdx.x * 16] = 0;
+    }
+    if (threadIdx.x == 0) ctl->tick_top = 0;
   }
 }
 
@@ -262,7 +274,7 @@ __global__ void __launch_bounds__(256)
 // (k = 0..13, the last one being the centre), 4 rows per wave.
 __global__ void __launch_bounds__(256)
     k_probe_sym3(const int4* __restrict__ rows, int n_rows, const unsigned long long* __restrict__ tab, int log_cap,
-                 int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl) {
+                 int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl, HostResult* host) {
   __shared__ unsigned wave_pairs[4];
   constexpr int V = 27, HALF = 13, LPR = 14, RPW = 4;
   const int lane = threadIdx.x & 63;
@@ -293,9 +305,32 @@ __global__ void __launch_bounds__(256)
                                     (1ull << (HALF + 3 * LPR));
   if (lane == 0) wave_pairs[threadIdx.x >> 6] = 2u * (unsigned)__popcll(bal & ~centre) + (unsigned)__popcll(bal & centre);
   __syncthreads();
+  // The workgroup that arrives last sums the pair counters and writes the result into pinned
+  // host memory.  Arrival is counted in two levels (per pair slot, then over the slots) so that
+  // no address sees more than gridDim/64 or 64 atomics.  Every value the last workgroup reads
+  // was produced by an atomic whose return its producer waited for before counting itself in,
+  // and is read with an atomic, so no cache write-back is needed.
+  __shared__ int is_last;
   if (threadIdx.x == 0) {
     const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
-    if (n) atomicAdd(&ctl->pairs[(blockIdx.x % kPairSlots) * 16], (unsigned long long)n);
+    const unsigned slot = blockIdx.x % kPairSlots;
+    const unsigned long long before = atomicAdd(&ctl->pairs[slot * 16], (unsigned long long)n);
+    const unsigned slot_wgs = (gridDim.x - slot + kPairSlots - 1) / kPairSlots;
+    const unsigned used_slots = gridDim.x < (unsigned)kPairSlots ? gridDim.x : (unsigned)kPairSlots;
+    // (before >> 63) is zero; it ties the arrival to the completed pair add
+    const unsigned arrived = atomicAdd(&ctl->tick[slot * 16], 1u + (unsigned)(before >> 63));
+    int last = 0;
+    if (arrived + 1 == slot_wgs) last = atomicAdd(&ctl->tick_top, 1u) + 1 == used_slots;
+    is_last = last;
+  }
+  __syncthreads();
+  if (is_last && threadIdx.x < 64) {
+    unsigned long long v = atomicAdd(&ctl->pairs[threadIdx.x * 16], 0ull);  // kPairSlots == 64 lanes
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+    if (threadIdx.x == 0) {
+      host->pairs = v;
+      host->flags = ctl->flags;
+    }
   }
 }
 
@@ -384,9 +419,11 @@ int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st) {
 
 // Pool of pinned control blocks, each with the event that marks the end of its copy.
 struct HostCtl {
-  Ctl ctl;
-  hipEvent_t done;
+  HostResult res;
+  hipEvent_t done;  // recorded behind the probe, whose last workgroup writes res
+  HostResult* dev;  // device-side address of res
 };
+
 std::mutex g_host_mu;
 std::vector<HostCtl*> g_host_free;
 
@@ -405,6 +442,13 @@ HostCtl* host_ctl_acquire() {
     return nullptr;
   }
   HostCtl* h = static_cast<HostCtl*>(p);
+  void* dp = nullptr;
+  if (hipHostGetDevicePointer(&dp, p, 0) != hipSuccess) {
+    (void)hipGetLastError();
+    (void)hipHostFree(p);
+    return nullptr;
+  }
+  h->dev = &static_cast<HostCtl*>(dp)->res;
   if (hipEventCreateWithFlags(&h->done, hipEventDisableTiming) != hipSuccess) {
     (void)hipGetLastError();
     (void)hipHostFree(p);
@@ -446,7 +490,12 @@ int flags_status(const Ctl& h) {
   return SPCONV_OK;
 }
 
-// Submanifold 3x3x3 build: three launches (init, insert, symmetric probe) and one readback.
+}  // namespace
+int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream);
+namespace {
+
+// Submanifold 3x3x3 build: init, insert, symmetric probe (whose last workgroup publishes the result
+// to pinned host memory); an event marks the end.
 int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async, hipStream_t st) {
   const int V = 27;
   DevBuf ctl_buf, tab, own_rows;
@@ -468,30 +517,24 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async,
   hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
                      tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>());
   SPC_LAUNCH_CHECK();
+  HostCtl* hc = host_ctl_acquire();
+  if (!hc) return SPCONV_ENOMEM;
   hipLaunchKernelGGL(k_probe_sym3, dim3(blocks_for(ceil_div(N, 4), 4)), dim3(256), 0, st, rows, (int)N,
-                     tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl);
-  SPC_LAUNCH_CHECK();
+                     tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl, hc->dev);
+  const bool ok = hipGetLastError() == hipSuccess && hipEventRecord(hc->done, st) == hipSuccess;
+  if (!ok) {
+    (void)hipGetLastError();
+    (void)hipStreamSynchronize(st);
+    host_ctl_release(hc);
+    return SPCONV_EHIP;
+  }
   km->n_in = km->n_out = N;
   side.ready = true;
-  HostCtl* hc = async ? host_ctl_acquire() : nullptr;
-  if (hc) {
-    // the control block travels to pinned memory right behind the probe; spconv_kmap_status
-    // later waits for that copy only, not for whatever else has been enqueued since
-    SPC_HIP(hipMemcpyAsync(&hc->ctl, ctl, sizeof(Ctl), hipMemcpyDeviceToHost, st));
-    SPC_HIP(hipEventRecord(hc->done, st));
-    std::swap(km->pending_ctl.p, ctl_buf.p);
-    std::swap(km->pending_ctl.bytes, ctl_buf.bytes);
-    km->pending_host = hc;
-    km->pending = true;
-    km->n_pairs = -1;
-  } else {
-    Ctl h{};
-    SPC_TRY(read_ctl(ctl, &h, st));
-    SPC_TRY(flags_status(h));
-    int64_t pairs = 0;
-    for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
-    km->n_pairs = pairs;
-  }
+  km->pending_host = hc;
+  km->pending = true;
+  km->n_pairs = -1;
+  // (ctl_buf returns to the pool here; reuse is ordered behind the probe on this stream)
+  if (!async) SPC_TRY(kmap_status_impl(km, st, true));
   std::swap(km->in_coords.p, own_rows.p);  // P_out == P_in: out_coords stays empty
   std::swap(km->in_coords.bytes, own_rows.bytes);
   return SPCONV_OK;
@@ -507,22 +550,26 @@ struct HostCtlHandle {
   }
 };
 
-int kmap_status(spconv_kmap* km, hipStream_t st) {
-  (void)st;
+// wait_stream: wait for the whole stream (the synchronous build: everything on it is the build,
+// and a stream wait returns sooner than an event wait); otherwise only for the probe's event.
+int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
   if (!km->pending) return SPCONV_OK;
   HostCtl* hc = static_cast<HostCtl*>(km->pending_host);
-  SPC_HIP(hipEventSynchronize(hc->done));
-  const Ctl& h = hc->ctl;
-  int64_t pairs = 0;
-  for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+  if (wait_stream)
+    SPC_HIP(hipStreamSynchronize(st));
+  else
+    SPC_HIP(hipEventSynchronize(hc->done));
+  Ctl h{};
+  h.flags = hc->res.flags;
   const int status = flags_status(h);
-  km->n_pairs = pairs;
+  km->n_pairs = (int64_t)hc->res.pairs;
   km->pending = false;
   km->pending_host = nullptr;
-  km->pending_ctl.release();
   host_ctl_release(hc);
   return status;
 }
+
+int kmap_status(spconv_kmap* km, hipStream_t st) { return kmap_status_impl(km, st, false); }
 
 int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
                spconv_kmap** out) {

@@ -82,17 +82,17 @@ __global__ void __launch_bounds__(256)
   if ((threadIdx.x & 63) == 0 && mine) atomicAdd(executed, mine);
 }
 
-// Per-offset pair counts of each wave's 256 rows: counts[k][w].  A ballot per offset turns the
+// Per-offset pair counts of each wave's wave_rows rows (a multiple of 64): counts[k][w].  A ballot per offset turns the
 // 64 masks held by the lanes into that offset's count; lane k keeps the running count of offset k.
 __global__ void __launch_bounds__(256)
-    k_pair_count(const unsigned* __restrict__ mask, long long rows, int V, int n_waves,
+    k_pair_count(const unsigned* __restrict__ mask, long long rows, int V, int n_waves, int wave_rows,
                  unsigned* __restrict__ counts) {
   const int lane = threadIdx.x & 63;
   const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
   if (w >= n_waves) return;
   unsigned mine = 0;
-  for (int it = 0; it < 4; ++it) {
-    const long long r = w * 256 + it * 64 + lane;
+  for (int it = 0; it < wave_rows / 64; ++it) {
+    const long long r = (long long)w * wave_rows + it * 64 + lane;
     const unsigned m = r < rows ? mask[r] : 0u;
     for (int k = 0; k < V; ++k) {
       const unsigned long long bal = __ballot((m >> k) & 1u);
@@ -109,7 +109,7 @@ __global__ void __launch_bounds__(256)
 template <int V>
 __global__ void __launch_bounds__(256)
     k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_waves,
-                const unsigned* __restrict__ offs, int2* __restrict__ pairs) {
+                int wave_rows, const unsigned* __restrict__ offs, int2* __restrict__ pairs) {
   __shared__ int slab[4][64 * V];
   const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
   const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -117,8 +117,8 @@ __global__ void __launch_bounds__(256)
   unsigned base = lane < V ? offs[(long long)lane * n_waves + w] : 0u;  // lane k: next slot of offset k
   const unsigned long long lt = (1ull << lane) - 1ull;
   int* ms = slab[wib];
-  for (int it = 0; it < 4; ++it) {
-    const long long r0 = w * 256 + it * 64;
+  for (int it = 0; it < wave_rows / 64; ++it) {
+    const long long r0 = (long long)w * wave_rows + it * 64;
     if (r0 >= rows) break;
     const long long r = r0 + lane;
     const unsigned m = r < rows ? mask[r] : 0u;
@@ -141,15 +141,15 @@ __global__ void __launch_bounds__(256)
   }
 }
 
-// Cuts every offset's pair range into ceil(count / target) nearly equal work items.
-// One wave: lanes 0..V hold the per-offset figures, then all lanes write items in parallel.
-__global__ void __launch_bounds__(256)
-    k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
-                 int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
+// Cuts every offset's pair range into ceil(count / target) nearly equal work items.  Called by a
+// whole workgroup; begin_of(k) returns the scanned pair offset of offset k (k = V: the total).
+template <typename BeginOf>
+__device__ __forceinline__ void make_items(BeginOf begin_of, int V, unsigned target, int max_items, int* seg,
+                                           WgradItem* items, int* item_seg) {
   __shared__ unsigned s_begin[33], s_cnt[33], s_first[34];
   const int lane = threadIdx.x;
   if (lane < 64) {  // the first wave works out the per-offset figures
-    const unsigned begin = lane <= V ? scanned[(long long)lane * n_waves] : 0u;  // [V * n_waves] holds the total
+    const unsigned begin = lane <= V ? begin_of(lane) : 0u;
     const unsigned next = __shfl_down(begin, 1);
     const unsigned cnt = lane < V ? next - begin : 0u;
     if (lane <= V) seg[lane] = (int)begin;
@@ -178,7 +178,7 @@ __global__ void __launch_bounds__(256)
     int k = 0;
     while (k + 1 < V && s_first[k + 1] <= i) ++k;
     const unsigned c = s_cnt[k], pc = s_first[k + 1] - s_first[k], q = i - s_first[k];
-    // c * q / pc without 64-bit division: c = a * pc + r
+    // c * q / pc with c = a * pc + r
     const unsigned a = c / pc, r = c - a * pc;
     WgradItem w;
     w.k = k;
@@ -187,6 +187,60 @@ __global__ void __launch_bounds__(256)
     w.pad = 0;
     items[i] = w;
   }
+}
+
+__global__ void __launch_bounds__(256)
+    k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
+                 int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
+  make_items([&](int k) { return scanned[(long long)k * n_waves]; }, V, target, max_items, seg, items, item_seg);
+}
+
+// Up to 16384 counters: exclusive scan in place and the work items in one launch (one workgroup
+// of 1024 threads; 16 consecutive counters per thread through LDS, wave-shuffle scan across threads).
+constexpr int kFusedPer = 16;
+constexpr int kFusedMax = 1024 * kFusedPer;
+constexpr size_t kFusedLds = (size_t)(kFusedMax + kFusedMax / 32 + 8) * sizeof(unsigned);
+__global__ void __launch_bounds__(1024)
+    k_scan_items(unsigned* __restrict__ counts, int n_counts, int V, int n_waves, unsigned target, int max_items,
+                 int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
+  extern __shared__ unsigned tile[];
+  __shared__ unsigned wave_sum[16];
+  auto skew = [](int x) { return x + (x >> 5); };
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+#pragma unroll
+  for (int i = 0; i < kFusedPer; ++i) {
+    const int g = i * 1024 + t;
+    tile[skew(g)] = g < n_counts ? counts[g] : 0u;
+  }
+  __syncthreads();
+  unsigned v[kFusedPer], sum = 0;
+#pragma unroll
+  for (int i = 0; i < kFusedPer; ++i) {
+    v[i] = tile[skew(t * kFusedPer + i)];
+    sum += v[i];
+  }
+  unsigned incl = sum;
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_sum[wave] = incl;
+  __syncthreads();
+  unsigned run = incl - sum;
+  for (int w = 0; w < wave; ++w) run += wave_sum[w];
+#pragma unroll
+  for (int i = 0; i < kFusedPer; ++i) {
+    tile[skew(t * kFusedPer + i)] = run;
+    run += v[i];
+  }
+  __syncthreads();
+#pragma unroll
+  for (int i = 0; i < kFusedPer; ++i) {
+    const int g = i * 1024 + t;
+    if (g < n_counts) counts[g] = tile[skew(g)];
+  }
+  make_items([&](int k) { return tile[skew(k * n_waves)]; }, V, target, max_items, seg, items, item_seg);
 }
 
 }  // namespace
@@ -218,7 +272,8 @@ int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_
   SPC_TRY(p->tilemask.alloc((size_t)p->parts * tiles_alloc * sizeof(unsigned)));
   const unsigned tile_blocks = blocks_for(tiles_alloc, 4);
   if (n_split == 0) {
-    if (p->n_tiles > 0) {
+    // (16-row blocks are the wave kernel's; it ORs the row masks itself, so no launch here)
+    if (p->n_tiles > 0 && tile_m != 16) {
       hipLaunchKernelGGL(k_tile_mask, dim3(tile_blocks), dim3(256), 0, st, side.mask.as<unsigned>(),
                          (const int*)nullptr, (long long)p->rows, tile_m, 0, V, (long long)p->n_tiles,
                          p->tilemask.as<unsigned>());
@@ -303,10 +358,14 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   p->target_pairs = target_pairs;
   p->pairs_cap = km->n_pairs >= 0 ? km->n_pairs : km->n_out * V;
   p->max_items = (int)std::min<int64_t>(V + ceil_div(p->pairs_cap, target_pairs), 1 << 20);
-  const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, 256));
+  // rows per wave: 256, or up to 512 when that lets the counters fit the fused scan-and-items launch
+  int wave_rows = 256;
+  while (wave_rows < 512 && (size_t)V * ceil_div(km->n_out, wave_rows) + 1 > (size_t)kFusedMax) wave_rows += 64;
+  if ((size_t)V * ceil_div(km->n_out, wave_rows) + 1 > (size_t)kFusedMax) wave_rows = 256;
+  const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, wave_rows));
   const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
-  DevBuf counts;
   const size_t n_sums = scan_sums_elems((int64_t)n_counts);
+  DevBuf counts;
   SPC_TRY(counts.alloc((n_counts + n_sums) * sizeof(unsigned)));
   SPC_TRY(p->pairs.alloc(std::max<size_t>(1, (size_t)p->pairs_cap) * sizeof(int2)));
   SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int)));
@@ -314,21 +373,34 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   SPC_TRY(p->item_seg.alloc((size_t)(V + 2) * sizeof(int)));
   const unsigned blocks = blocks_for(n_waves, 4);
   hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
-                     n_waves, counts.as<unsigned>());
+                     n_waves, wave_rows, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
-  SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, counts.as<uint32_t>() + n_counts, st));
+  if (n_counts <= (size_t)kFusedMax) {
+    static bool attr_set = false;
+    if (!attr_set) {
+      SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_scan_items),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds));
+      attr_set = true;
+    }
+    hipLaunchKernelGGL(k_scan_items, dim3(1), dim3(1024), kFusedLds, st, counts.as<unsigned>(), (int)n_counts, V, n_waves,
+                       (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
+                       p->item_seg.as<int>());
+    SPC_LAUNCH_CHECK();
+  } else {
+    SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, counts.as<uint32_t>() + n_counts, st));
+    hipLaunchKernelGGL(k_make_items, dim3(1), dim3(256), 0, st, counts.as<unsigned>(), V, n_waves,
+                       (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
+                       p->item_seg.as<int>());
+    SPC_LAUNCH_CHECK();
+  }
   if (V == 27)
     hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
-                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),
+                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, wave_rows, counts.as<unsigned>(),
                        p->pairs.as<int2>());
   else
     hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
-                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, counts.as<unsigned>(),
+                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, wave_rows, counts.as<unsigned>(),
                        p->pairs.as<int2>());
-  SPC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_make_items, dim3(1), dim3(256), 0, st, counts.as<unsigned>(), V, n_waves,
-                     (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
-                     p->item_seg.as<int>());
   SPC_LAUNCH_CHECK();
   *out = p.get();
   km->wplans[target_pairs] = std::move(p);

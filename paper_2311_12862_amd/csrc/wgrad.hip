@@ -94,10 +94,12 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
   unsigned short* Xs = reinterpret_cast<unsigned short*>(smem_w);  // [2][pair][ci]
   unsigned short* Ds = Xs + 2 * WG_BK * LD;                        // [2][pair][co]
 
-  if ((int)blockIdx.x >= p.item_seg[p.V]) return;
+  const int n_items = p.item_seg[p.V];
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const WgradItem item = p.items[blockIdx.x];
   const int ci0 = blockIdx.y * TILE, co0 = blockIdx.z * TILE;
+  // the grid is bounded; a workgroup takes items blockIdx.x, blockIdx.x + gridDim.x, ...
+  for (int item_id = blockIdx.x; item_id < n_items; item_id += gridDim.x) {
+  const WgradItem item = p.items[item_id];
   const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
   const __amdgpu_buffer_rsrc_t d_rsrc = make_rsrc(p.dout, p.dout_bytes);
   const __amdgpu_buffer_rsrc_t p_rsrc = make_rsrc(p.pairs, p.pairs_bytes);
@@ -169,7 +171,7 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
     __syncthreads();
   }
 
-  float* dst = p.partial + (long long)blockIdx.x * p.C_in * p.C_out;
+  float* dst = p.partial + (long long)item_id * p.C_in * p.C_out;
 #pragma unroll
   for (int i = 0; i < QB; ++i)
 #pragma unroll
@@ -182,6 +184,8 @@ __global__ void __launch_bounds__(256) k_wgrad(const WgradParams p) {
         if (co < p.C_out) dst[(long long)ci * p.C_out + co] = acc[i][j][r];
       }
     }
+  __syncthreads();  // the LDS tiles are reused by the next item
+  }
 }
 
 // fp32 path: plain FMA arithmetic, 16 pairs at a time.
@@ -314,7 +318,9 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
     } else {
       // 128 x 128 tiles as soon as a 64 x 64 tile would gather every pair's rows more than once
       const int tile = (C_in > 64 || C_out > 64) ? 128 : 64;
-      dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(C_in, tile), (unsigned)ceil_div(C_out, tile));
+      const unsigned tiles = (unsigned)(ceil_div(C_in, tile) * ceil_div(C_out, tile));
+      const unsigned gx = (unsigned)std::min<int64_t>(wp.max_items, std::max<unsigned>(64u, 512u / tiles));
+      dim3 grid(gx, (unsigned)ceil_div(C_in, tile), (unsigned)ceil_div(C_out, tile));
       const size_t smem = (size_t)2 * 2 * WG_BK * (tile + 16) * 2;
       static bool attr_set = false;
       if (!attr_set) {

@@ -95,7 +95,8 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   constexpr int ROW_HALFS = 32 * KS;
   extern __shared__ __align__(16) unsigned char smem[];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform, and known to be
   const int n_waves = blockDim.x >> 6;
   const int arow = lane & 15, aq = lane >> 4;  // fragment row and 8-channel group within a k-step
   const int part = blockIdx.z;
@@ -110,15 +111,33 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 2));
   const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
 
-  const long long wave_global = (long long)blockIdx.x * n_waves + wave;
-  const long long wave_stride = (long long)gridDim.x * n_waves;
-  const bool has_work = wave_global < p.n_blocks;
+  // Blocks of this workgroup: b = j * gridDim.x + blockIdx.x, j < nj, handed to its waves one at
+  // a time in descending j (a bitmask-sorted map has its widest masks at the end, so the heaviest
+  // blocks go first and the tail of the kernel is made of light ones).  A wave's first ticket is
+  // its index; further ones come from a counter in LDS.
+  __shared__ unsigned next_ticket;
+  const int nj = p.n_blocks > blockIdx.x ? (int)((p.n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
+  auto block_of = [&](int t) { return (long long)(nj - 1 - t) * gridDim.x + blockIdx.x; };
+  const bool has_work = wave < nj;
+  if (tid == 0) next_ticket = (unsigned)n_waves;
   const unsigned row_bytes = (unsigned)c_red * 2u;
   const int map_len = 16 * width;
   const int* map_part = p.map[part];
   const int* pm = p.perm[part];
   const unsigned* bmask = p.blkmask[part];
   T* stage = reinterpret_cast<T*>(slab + p.map_bytes);
+
+  // per-lane constants of the offset loop
+  constexpr unsigned kAbsent = 0xFFFF0000u;  // byte offset that is out of range with any lane offset added
+  const unsigned lane_map = (unsigned)(arow * width) * 4u;  // this lane's map row in the slab
+  unsigned lane_col[KS];  // this lane's 8 channels within a gathered row (bytes), or out of range
+  unsigned lane_b[KS];    // this lane's weight chunk within an offset's slice (bytes, first 16 columns)
+#pragma unroll
+  for (int ks = 0; ks < KS; ++ks) {
+    const unsigned col = (unsigned)(ks * 4 + aq) * 8u;
+    lane_col[ks] = col < (unsigned)c_red ? col * 2u : 0x80000000u;
+    lane_b[ks] = (unsigned)(arow * ROW_HALFS + swz<KS>(ks * 4 + aq, arow) * 8) * 2u;
+  }
 
   // registers holding the next block's map rows, mask and output rows
   int mreg[kMapVecs];
@@ -140,25 +159,24 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   int cc[DEPTH];
   unsigned m = 0;
   // Always issues KS loads: with no offset left they are out-of-range loads (zeros, no traffic).
+  // The slab holds byte offsets of the gathered rows (kAbsent for a missing neighbour).
   auto issue = [&](int s) {
     const int c = m ? __ffs((int)m) - 1 : -1;
     m &= m - 1;  // 0 stays 0
     cc[s] = c;
-    const int idx = mapW[arow * width + (c < 0 ? 0 : c)];
-    const unsigned base = (unsigned)idx * row_bytes;  // idx = -1 wraps to just below 2^32: out of range
+    unsigned rowb = kAbsent;
+    if (c >= 0) rowb = *reinterpret_cast<const unsigned*>(slab + lane_map + (unsigned)c * 4u);
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-      const unsigned col = (unsigned)(ks * 4 + aq) * 8u;
-      const bool ok = c >= 0 && col < (unsigned)c_red;
-      fr[s][ks] = buf_load16(x_rsrc, ok ? base + col * 2u : 0xFFFFFFFFu);
-    }
+    for (int ks = 0; ks < KS; ++ks) fr[s][ks] = buf_load16(x_rsrc, rowb + lane_col[ks]);
   };
-  // Publishes the prefetched block in the wave's slab and puts its first DEPTH offsets in flight.
-  auto start_block = [&](long long b_next_next) {
+  // Publishes the prefetched block in the wave's slab, takes the ticket of the block after it and
+  // starts that block's prefetch, then puts the first DEPTH offsets in flight.
+  int t_next = 0;
+  auto start_block = [&]() {
 #pragma unroll
     for (int i = 0; i < kMapVecs; ++i) {
       const int e = lane + 64 * i;
-      if (e < map_len) mapW[e] = mreg[i];
+      if (e < map_len) mapW[e] = mreg[i] < 0 ? (int)kAbsent : (int)((unsigned)mreg[i] * row_bytes);
     }
     unsigned bm = bm_next;
     if (p.rowmask) {  // lanes 0..15 (and their three copies) hold the rows' masks
@@ -168,14 +186,17 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       bm |= __shfl_xor(bm, 8);
     }
     m = __builtin_amdgcn_readfirstlane(bm);
-    prefetch_block(b_next_next < p.n_blocks ? b_next_next : p.n_blocks - 1);
+    unsigned t = 0;
+    if (lane == 0) t = atomicAdd(&next_ticket, 1u);
+    t_next = (int)__builtin_amdgcn_readfirstlane(t);
+    prefetch_block(block_of(t_next < nj ? t_next : nj - 1));
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
     for (int s = 0; s < DEPTH; ++s) issue(s);
   };
 
   // the first block's map rows travel while the weights are being staged
-  if (has_work) prefetch_block(wave_global);
+  if (has_work) prefetch_block(block_of(wave));
 
   // ---- weights of this part -> LDS (once per workgroup), four loads in flight per thread
   {
@@ -237,22 +258,20 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   __syncthreads();  // weights visible
   if (!has_work) return;
 
-  for (long long b = wave_global; b < p.n_blocks; b += wave_stride) {
+  for (int t_cur = wave; t_cur < nj; t_cur = t_next) {
     const int orow_cur = orow_next;
-    start_block(b + wave_stride);
+    start_block();
     f32x4 acc[NB];
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     auto consume = [&](int s) {
-      const unsigned short* wrow = Ws + (size_t)(cc[s] * BN + arow) * ROW_HALFS;
+      const unsigned char* wk = smem + (unsigned)cc[s] * (unsigned)(BN * ROW_HALFS * 2);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
-          const int n = nb * 16 + arow;
-          const uint4 bf = *reinterpret_cast<const uint4*>(wrow + (size_t)nb * 16 * ROW_HALFS +
-                                                           swz<KS>(ks * 4 + aq, n) * 8);
+          const uint4 bf = *reinterpret_cast<const uint4*>(wk + lane_b[ks] + nb * (16 * ROW_HALFS * 2));
           acc[nb] = MfmaW<T>::run(fr[s][ks], bf, acc[nb]);
         }
       }
@@ -348,7 +367,7 @@ int launch_wave_ks(int ks, int nb, const WaveParams& p, dim3 grid, int threads, 
   return SPCONV_EINVAL;
 }
 
-constexpr size_t kLdsBudget = 160 * 1024;
+constexpr size_t kLdsBudget = 160 * 1024 - 64;  // (64 bytes for the static ticket counter)
 
 size_t map_bytes_for(int max_width) { return (size_t)round_up((int64_t)16 * max_width * 4, 16); }
 
@@ -408,7 +427,9 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
   p.c_out = a.dgrad ? a.C_in : a.C_out;
   const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
   const uint64_t feats_bytes = (uint64_t)rows_src * p.c_red * 2;
-  if (feats_bytes >= 0xFFFFC000ull) return SPCONV_EINVAL;  // buffer descriptors address 32 bits
+  // buffer descriptors address 32 bits; "absent" is the byte offset 0xFFFF0000, and lanes beyond a
+  // channel count that is not a multiple of 32 add 2^31 to stay out of range
+  if (feats_bytes >= (p.c_red % 32 ? 0x7FFF0000ull : 0xFFFF0000ull)) return SPCONV_EINVAL;
   p.feats_bytes = (unsigned)feats_bytes;
   int waves = 8;
   const int bn = igemm_wave_pick_bn(km->V, plan.n_split, p.c_red, p.c_out, a.tile_n, &waves);

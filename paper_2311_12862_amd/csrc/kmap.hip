@@ -30,6 +30,7 @@ struct Ctl {
   unsigned long long flags, count, pad[14];
   unsigned long long pairs[kPairSlots * 16];
   unsigned long long key_or[kPairSlots * 16], key_and[kPairSlots * 16];  // spread like pairs
+  unsigned long long entries[kPairSlots * 16];  // present map entries, counted from the finished map
   unsigned tick[kPairSlots * 16];  // arrivals per pair slot (submanifold probe)
   unsigned tick_top, pad2[15];     // pair slots whose workgroups have all arrived
 };
@@ -103,6 +104,7 @@ __global__ void k_ctl_init(Ctl* ctl) {
     ctl->count = 0;
   }
   ctl->pairs[threadIdx.x * 16] = 0;  // launched with kPairSlots threads
+  ctl->entries[threadIdx.x * 16] = 0;
   ctl->key_or[threadIdx.x * 16] = 0;
   ctl->key_and[threadIdx.x * 16] = ~0ull;
 }
@@ -129,7 +131,8 @@ __global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ co
 // keys so that the host knows which key bytes vary.
 __global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ coords, int n, int stride,
                                                        unsigned long long* tab, int log_cap,
-                                                       unsigned long long* __restrict__ ukeys, Ctl* ctl) {
+                                                       unsigned long long* __restrict__ ukeys, Ctl* ctl,
+                                                       int4* __restrict__ keep) {
   __shared__ unsigned long long s_or[4], s_and[4];
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -137,6 +140,8 @@ __global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ 
   unsigned long long key = 0, k_or = 0, k_and = ~0ull;
   if (j < n) {
     const int4 c = coords[j];
+    if (keep) keep[j] = c;  // the kmap's own copy of the caller's rows (builds without a fine table)
+    if (!coord_ok(c.x, c.y, c.z, c.w)) atomicOr(&ctl->flags, FLAG_RANGE);
     if (coord_ok(c.x, c.y, c.z, c.w)) {
       key = pack_key(c.x, floor_div(c.y, stride), floor_div(c.z, stride), floor_div(c.w, stride));
       const int r = table_insert(tab, log_cap, key, 0, nullptr);
@@ -245,6 +250,62 @@ __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, in
   }
 }
 
+// Strided 3x3x3 map built from the input side.  Input p meets output q exactly when
+// p = s*q + delta with delta in {-1, 0, 1}^3 (Eq. 1 with stride s), so per axis q is floor(p/s)
+// (delta = p - s*q, if that is <= 1) or floor(p/s) + 1 (delta = p - s*q, if that is >= -1): at most
+// 2x2x2 candidates, tried by 8 lanes per input row, each one lookup of q's rank in the table of
+// coarse points.  At stride 2 that is 3.4 lookups per input on average, against 27 per output when
+// probing from the output side.  The map was preset to -1; the masks are derived from it
+// afterwards.  Plain stores: duplicate input rows write one entry twice, which shows as fewer
+// present entries in the finished map than hits counted here.
+__global__ void __launch_bounds__(256)
+    k_scatter_down3(const int4* __restrict__ rows, int n_rows, int stride, const unsigned long long* __restrict__ tab,
+                    int log_cap, int* __restrict__ map, Ctl* ctl) {
+  __shared__ unsigned wave_pairs[4];
+  constexpr int V = 27;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const long long row = wave * 8 + (lane >> 3);
+  const int cand = lane & 7;
+  bool found = false;
+  if (row < n_rows) {
+    const int4 c = rows[row];
+    if (coord_ok(c.x, c.y, c.z, c.w)) {
+      const int pc[3] = {c.y, c.z, c.w};
+      int q[3], d[3];
+      bool ok = true;
+#pragma unroll
+      for (int a = 0; a < 3; ++a) {
+        const int up = (cand >> (2 - a)) & 1;
+        q[a] = floor_div(pc[a], stride) + up;
+        d[a] = pc[a] - stride * q[a];
+        ok = ok && d[a] >= -1 && d[a] <= 1;
+      }
+      if (ok && coord_ok(c.x, q[0], q[1], q[2])) {
+        const int n = table_find(tab, log_cap, pack_key(c.x, q[0], q[1], q[2]), nullptr);
+        if (n >= 0) {
+          const int k = ((d[0] + 1) * 3 + (d[1] + 1)) * 3 + (d[2] + 1);
+          map[(long long)n * V + k] = (int)row;
+          found = true;
+        }
+      }
+    }
+  }
+  const unsigned long long bal = __ballot(found);
+  if (lane == 0) wave_pairs[threadIdx.x >> 6] = (unsigned)__popcll(bal);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
+    if (n) atomicAdd(&ctl->pairs[(blockIdx.x % kPairSlots) * 16], (unsigned long long)n);
+  }
+}
+
+// Plain fills (in place of memset calls, which must stay out of anything a caller may capture).
+__global__ void __launch_bounds__(256) k_fill_u32(unsigned* __restrict__ dst, long long n, unsigned v) {
+  const long long stride = (long long)gridDim.x * blockDim.x;
+  for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = v;
+}
+
 // One launch that prepares a submanifold build: empties the hash table, presets the whole map
 // to "absent" and the masks to zero, and clears the control block.
 __global__ void __launch_bounds__(256)
@@ -349,7 +410,8 @@ __global__ void __launch_bounds__(256) k_scatter_in_side(const int* __restrict__
 
 template <int V>
 __global__ void __launch_bounds__(256) k_mask_from_map(const int* __restrict__ map, int n_rows,
-                                                       unsigned* __restrict__ mask) {
+                                                       unsigned* __restrict__ mask, Ctl* ctl) {
+  __shared__ unsigned wave_cnt[4];
   constexpr int RPW = 64 / V;
   const int lane = threadIdx.x & 63;
   const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
@@ -359,6 +421,51 @@ __global__ void __launch_bounds__(256) k_mask_from_map(const int* __restrict__ m
   const bool hit = active && map[row * V + k] >= 0;
   const unsigned long long bal = __ballot(hit);
   if (active && k == 0) mask[row] = (unsigned)((bal >> (sub * V)) & ((1ull << V) - 1ull));
+  if (!ctl) return;  // (uniform) otherwise count the present entries, one atomic per workgroup
+  if (lane == 0) wave_cnt[threadIdx.x >> 6] = (unsigned)__popcll(bal);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned n = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    if (n) atomicAdd(&ctl->entries[(blockIdx.x % kPairSlots) * 16], (unsigned long long)n);
+  }
+}
+
+// The unique coarse keys vary in a few bit ranges only (per 16-bit field: lowest to highest
+// varying bit).  Squeezing those ranges together gives a dense key of usually <= 32 bits whose
+// order is the order of the full keys, so the sort moves half the bytes in half the passes.
+struct BitRuns {
+  int n, total;
+  int pos[4], len[4], out[4];
+  unsigned long long base;  // the constant bits
+};
+__global__ void __launch_bounds__(256) k_compress_keys(const unsigned long long* __restrict__ keys, int n, BitRuns r,
+                                                       unsigned* __restrict__ out) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const unsigned long long k = keys[i];
+  unsigned c = 0;
+  for (int j = 0; j < r.n; ++j) c |= (unsigned)((k >> r.pos[j]) & ((1ull << r.len[j]) - 1ull)) << r.out[j];
+  out[i] = c;
+}
+// Sorted dense keys -> coordinates of the coarse points, and each key's rank as its table value.
+__global__ void __launch_bounds__(256) k_expand_keys(const unsigned* __restrict__ dense, int n, BitRuns r,
+                                                     int4* __restrict__ coords, unsigned long long* tab,
+                                                     int log_cap) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const unsigned c = dense[i];
+  unsigned long long k = r.base;
+  for (int j = 0; j < r.n; ++j) k |= ((unsigned long long)((c >> r.out[j]) & ((1u << r.len[j]) - 1u))) << r.pos[j];
+  int4 q;
+  q.x = (int)(k >> 48);
+  q.y = (int)((k >> 32) & 0xFFFF) - 32768;
+  q.z = (int)((k >> 16) & 0xFFFF) - 32768;
+  q.w = (int)(k & 0xFFFF) - 32768;
+  coords[i] = q;
+  if (tab) {
+    unsigned slot = 0;
+    if (table_find(tab, log_cap, k, &slot) >= 0) tab[2 * (size_t)slot + 1] = (unsigned long long)(unsigned)i;
+  }
 }
 
 // Per-offset pair counts from the bitmasks.
@@ -405,15 +512,24 @@ int launch_probe(bool transposed, const int4* rows, int64_t n_rows, int stride, 
   return SPCONV_OK;
 }
 
-int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st) {
+int fill_u32(void* dst, int64_t n, unsigned v, hipStream_t st) {
+  if (n <= 0) return SPCONV_OK;
+  hipLaunchKernelGGL(k_fill_u32, dim3((unsigned)std::min<int64_t>(ceil_div(n, 256), 2048)), dim3(256), 0, st,
+                     static_cast<unsigned*>(dst), (long long)n, v);
+  SPC_LAUNCH_CHECK();
+  return SPCONV_OK;
+}
+
+// Allocates map and masks; presets the padding rows (no neighbours), or every row when the
+// builder only writes the entries that are present.
+int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st, bool preset_all = false) {
   side.rows = rows;
   side.rows_pad = round_up(rows > 0 ? rows : 1, kRowPad);
   SPC_TRY(side.map.alloc((size_t)side.rows_pad * V * sizeof(int)));
   SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
-  // padding rows: no neighbours
-  const size_t pad_rows = (size_t)(side.rows_pad - rows);
-  SPC_HIP(hipMemsetAsync(side.map.as<int>() + (size_t)rows * V, 0xFF, pad_rows * V * sizeof(int), st));
-  SPC_HIP(hipMemsetAsync(side.mask.as<unsigned>() + rows, 0, pad_rows * sizeof(unsigned), st));
+  const int64_t first = preset_all ? 0 : rows;
+  SPC_TRY(fill_u32(side.map.as<int>() + first * V, (side.rows_pad - first) * V, 0xFFFFFFFFu, st));
+  SPC_TRY(fill_u32(side.mask.as<unsigned>() + first, side.rows_pad - first, 0u, st));
   return SPCONV_OK;
 }
 
@@ -606,27 +722,32 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kPairSlots), 0, st, ctl);
   SPC_LAUNCH_CHECK();
 
+  // Strided 3x3x3 maps are built from the input side and need no table of the fine points.
+  const bool from_inputs = (K == 3 && stride > 1 && !transposed);
   // fine table: key(p_j) -> j.  Also the duplicate / range check of the caller's rows.
   const int lc_fine = log2_capacity(N);
-  SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
-  SPC_HIP(hipMemsetAsync(tab_fine.p, 0xFF, (size_t)16 << lc_fine, st));
   // the caller's rows are kept: they are P_in (and P_out for stride 1), or the fine output set
   DevBuf own_rows;
   SPC_TRY(own_rows.alloc((size_t)N * 16));
-  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                     tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>());
-  SPC_LAUNCH_CHECK();
+  if (!from_inputs) {
+    SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
+    SPC_TRY(fill_u32(tab_fine.p, (int64_t)4 << lc_fine, 0xFFFFFFFFu, st));
+    hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
+                       tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>());
+    SPC_LAUNCH_CHECK();
+  }
 
   Ctl h{};
   int64_t U = 0;
   DevBuf coarse_rows;
   if (needs_coarse) {
     SPC_TRY(tab_coarse.alloc((size_t)16 << lc_fine));
-    SPC_HIP(hipMemsetAsync(tab_coarse.p, 0xFF, (size_t)16 << lc_fine, st));
+    SPC_TRY(fill_u32(tab_coarse.p, (int64_t)4 << lc_fine, 0xFFFFFFFFu, st));
     SPC_TRY(ukeys_a.alloc((size_t)N * 8));
     SPC_TRY(ukeys_b.alloc((size_t)N * 8));
     hipLaunchKernelGGL(k_coarse_unique, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N, stride,
-                       tab_coarse.as<unsigned long long>(), lc_fine, ukeys_a.as<unsigned long long>(), ctl);
+                       tab_coarse.as<unsigned long long>(), lc_fine, ukeys_a.as<unsigned long long>(), ctl,
+                       from_inputs ? own_rows.as<int4>() : nullptr);
     SPC_LAUNCH_CHECK();
   }
   if (needs_coarse) {
@@ -641,22 +762,64 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
       key_or |= h.key_or[i * 16];
       key_and &= h.key_and[i * 16];
     }
-    SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, key_or ^ key_and,
-                           hist.as<uint32_t>(), st, &in_b));
-    const unsigned long long* sorted = in_b ? ukeys_b.as<unsigned long long>() : ukeys_a.as<unsigned long long>();
+    const unsigned long long varying = key_or ^ key_and;
+    BitRuns runs{};
+    runs.base = key_and & ~varying;
+    for (int f = 0; f < 4; ++f) {
+      const unsigned v = (unsigned)((varying >> (16 * f)) & 0xFFFFu);
+      if (!v) continue;
+      int lo = 0, hi = 15;
+      while (!((v >> lo) & 1u)) ++lo;
+      while (!((v >> hi) & 1u)) --hi;
+      runs.pos[runs.n] = 16 * f + lo;
+      runs.len[runs.n] = hi - lo + 1;
+      runs.out[runs.n] = runs.total;
+      runs.total += hi - lo + 1;
+      // (bits inside a span that do not vary travel with the dense key; base must not repeat them)
+      runs.base &= ~(((1ull << (hi - lo + 1)) - 1ull) << (16 * f + lo));
+      ++runs.n;
+    }
     SPC_TRY(coarse_rows.alloc((size_t)U * 16));
-    hipLaunchKernelGGL(k_decode_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
-                       coarse_rows.as<int4>());
-    SPC_LAUNCH_CHECK();
-    if (transposed) {
-      hipLaunchKernelGGL(k_assign_rank, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
-                         tab_coarse.as<unsigned long long>(), lc_fine);
+    const bool want_rank = transposed || from_inputs;
+    if (runs.total <= 32) {
+      // ukeys_b's N * 8 bytes hold both dense key buffers
+      uint32_t* dense_a = ukeys_b.as<uint32_t>();
+      uint32_t* dense_b = dense_a + N;
+      hipLaunchKernelGGL(k_compress_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st,
+                         ukeys_a.as<unsigned long long>(), (int)U, runs, dense_a);
       SPC_LAUNCH_CHECK();
+      SPC_TRY(radix_sort_u32(dense_a, dense_b, nullptr, nullptr, U, runs.total, hist.as<uint32_t>(), st, &in_b));
+      hipLaunchKernelGGL(k_expand_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, in_b ? dense_b : dense_a, (int)U,
+                         runs, coarse_rows.as<int4>(),
+                         want_rank ? tab_coarse.as<unsigned long long>() : (unsigned long long*)nullptr, lc_fine);
+      SPC_LAUNCH_CHECK();
+    } else {
+      SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, varying, hist.as<uint32_t>(), st,
+                             &in_b));
+      const unsigned long long* sorted = in_b ? ukeys_b.as<unsigned long long>() : ukeys_a.as<unsigned long long>();
+      hipLaunchKernelGGL(k_decode_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
+                         coarse_rows.as<int4>());
+      SPC_LAUNCH_CHECK();
+      if (want_rank) {
+        hipLaunchKernelGGL(k_assign_rank, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
+                           tab_coarse.as<unsigned long long>(), lc_fine);
+        SPC_LAUNCH_CHECK();
+      }
     }
   }
 
   int status = SPCONV_OK;
-  if (!transposed) {
+  if (from_inputs) {
+    km->n_in = N;
+    km->n_out = U;
+    SPC_TRY(alloc_side(km->out_side, U, V, st, true));
+    hipLaunchKernelGGL(k_scatter_down3, dim3(blocks_for(ceil_div(N, 8), 4)), dim3(256), 0, st, rows, (int)N, stride,
+                       tab_coarse.as<unsigned long long>(), lc_fine, km->out_side.map.as<int>(), ctl);
+    SPC_LAUNCH_CHECK();
+    hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks_for(ceil_div(U, 2), 4)), dim3(256), 0, st,
+                       km->out_side.map.as<int>(), (int)U, km->out_side.mask.as<unsigned>(), ctl);
+    SPC_LAUNCH_CHECK();
+  } else if (!transposed) {
     km->n_in = N;
     km->n_out = needs_coarse ? U : N;
     const int4* qrows = needs_coarse ? coarse_rows.as<int4>() : rows;
@@ -680,11 +843,13 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   }
   km->out_side.ready = true;
 
-  if (!needs_coarse) {
+  if (!needs_coarse || from_inputs) {  // (from_inputs: duplicate rows only show up in the scatter)
     SPC_TRY(read_ctl(ctl, &h, st));
-    SPC_TRY(flags_status(h));
-    int64_t pairs = 0;  // the probe ran before this synchronisation: its pair count is final
+    int64_t pairs = 0, entries = 0;  // the probe ran before this synchronisation: its pair count is final
     for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
+    for (int i = 0; i < kPairSlots; ++i) entries += (int64_t)h.entries[i * 16];
+    if (from_inputs && entries != pairs) h.flags |= FLAG_DUP;  // two rows wrote one entry
+    SPC_TRY(flags_status(h));
     km->n_pairs = pairs;
   }
 
@@ -718,7 +883,7 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
   const int V = km->V;
   SPC_TRY(alloc_side(km->in_side, km->n_in, V, st));
   if (km->n_in > 0) {
-    SPC_HIP(hipMemsetAsync(km->in_side.map.p, 0xFF, (size_t)km->in_side.rows_pad * V * sizeof(int), st));
+    SPC_TRY(fill_u32(km->in_side.map.p, km->in_side.rows_pad * V, 0xFFFFFFFFu, st));
     const long long entries = (long long)km->n_out * V;
     if (entries > 0) {
       hipLaunchKernelGGL(k_scatter_in_side, dim3(blocks_for(entries, 256)), dim3(256), 0, st,
@@ -729,10 +894,10 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
     const unsigned blocks = blocks_for(ceil_div(km->n_in, rpw), 4);
     if (V == 27)
       hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
-                         (int)km->n_in, km->in_side.mask.as<unsigned>());
+                         (int)km->n_in, km->in_side.mask.as<unsigned>(), (Ctl*)nullptr);
     else
       hipLaunchKernelGGL((k_mask_from_map<1>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
-                         (int)km->n_in, km->in_side.mask.as<unsigned>());
+                         (int)km->n_in, km->in_side.mask.as<unsigned>(), (Ctl*)nullptr);
     SPC_LAUNCH_CHECK();
   }
   km->in_side.ready = true;
@@ -745,7 +910,7 @@ int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
   if (km->n_out > 0) {
     DevBuf counts;
     SPC_TRY(counts.alloc(32 * sizeof(unsigned long long)));
-    SPC_HIP(hipMemsetAsync(counts.p, 0, 32 * sizeof(unsigned long long), st));
+    SPC_TRY(fill_u32(counts.p, 64, 0u, st));
     const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(km->n_out, 256), 1024);
     hipLaunchKernelGGL(k_count_pairs, dim3(blocks), dim3(256), 0, st, km->out_side.mask.as<unsigned>(),
                        (int)km->n_out, counts.as<unsigned long long>());

@@ -14,7 +14,7 @@ namespace spc {
 namespace {
 
 constexpr int kItemsPerWave = 512;
-constexpr int kMaxBits = 9;
+constexpr int kMaxBits = 10;
 constexpr int kMaxBins = 1 << kMaxBits;
 
 template <typename KeyT>
@@ -194,10 +194,13 @@ int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* va
   int shift = 0;
   for (int p = 0; p < passes; ++p) {
     const int b = (shift + bits <= key_bits) ? bits : key_bits - shift;
-    if (*in_b == 0)
-      SPC_TRY((radix_pass<uint32_t, true>(key_a, key_b, val_a, val_b, n, shift, b, hist, st)));
-    else
-      SPC_TRY((radix_pass<uint32_t, true>(key_b, key_a, val_b, val_a, n, shift, b, hist, st)));
+    const bool fwd = (*in_b == 0);
+    if (val_a)
+      SPC_TRY((radix_pass<uint32_t, true>(fwd ? key_a : key_b, fwd ? key_b : key_a, fwd ? val_a : val_b,
+                                          fwd ? val_b : val_a, n, shift, b, hist, st)));
+    else  // keys only
+      SPC_TRY((radix_pass<uint32_t, false>(fwd ? key_a : key_b, fwd ? key_b : key_a, nullptr, nullptr, n, shift, b,
+                                           hist, st)));
     *in_b ^= 1;
     shift += b;
   }

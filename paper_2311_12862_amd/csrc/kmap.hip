@@ -722,8 +722,10 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kPairSlots), 0, st, ctl);
   SPC_LAUNCH_CHECK();
 
-  // Strided 3x3x3 maps are built from the input side and need no table of the fine points.
-  const bool from_inputs = (K == 3 && stride > 1 && !transposed);
+  // Stride-2 3x3x3 maps are built from the input side and need no table of the fine points.  (Only
+  // stride 2: there every input row meets the output floor(p/2), so every row writes at least one
+  // entry and duplicate rows cannot escape the entry count; at larger strides some rows write none.)
+  const bool from_inputs = (K == 3 && stride == 2 && !transposed);
   // fine table: key(p_j) -> j.  Also the duplicate / range check of the caller's rows.
   const int lc_fine = log2_capacity(N);
   // the caller's rows are kept: they are P_in (and P_out for stride 1), or the fine output set

@@ -88,6 +88,17 @@ def test_errors(sp):
     assert e.value.status == -3
     with pytest.raises(ValueError):
         oc.build_kmap(dup, 3, 1)
+    # duplicates and range errors are reported by every kind of build
+    for stride, transposed in ((2, False), (3, False), (2, True), (1, True)):
+        with pytest.raises(sp.SpconvError) as e:
+            sp.build_kmap(coords_dev(dup), 3, stride, transposed)
+        assert e.value.status == -3, (stride, transposed)
+    r = c.copy()
+    r[7] = [0, 32768, 0, 0]
+    for stride, transposed in ((2, False), (2, True)):
+        with pytest.raises(sp.SpconvError) as e:
+            sp.build_kmap(coords_dev(r), 3, stride, transposed)
+        assert e.value.status == -2, (stride, transposed)
     for bad in ([0, 32768, 0, 0], [0, 0, -32769, 0], [65535, 0, 0, 0], [-1, 0, 0, 0]):
         r = c.copy()
         r[7] = bad

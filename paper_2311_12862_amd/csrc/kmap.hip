@@ -52,9 +52,16 @@ __device__ __forceinline__ unsigned long long pack_key(int b, int x, int y, int 
          ((unsigned long long)(unsigned)(y + 32768) << 16) | (unsigned long long)(unsigned)(z + 32768);
 }
 
+// Home slot of a key.  The two low z bits pick a slot inside a group of four neighbouring slots
+// (one 64-byte line) and only the rest of the key is hashed, so the three z-neighbours that a
+// probe looks up for one (dx, dy) share a line or touch two adjacent ones.  Collisions move on by
+// five slots: to the next group and the next slot within it, so that the probe sequence visits the
+// whole table even when every key has the same low z bits (a planar point set).
 __device__ __forceinline__ unsigned hash_slot(unsigned long long key, int log_cap) {
-  return (unsigned)((key * 0x9E3779B97F4A7C15ull) >> (64 - log_cap));
+  const unsigned group = (unsigned)(((key >> 2) * 0x9E3779B97F4A7C15ull) >> (64 - (log_cap - 2)));
+  return (group << 2) | (unsigned)(key & 3ull);
 }
+constexpr unsigned kProbeStep = 5;
 
 // 0: inserted, 1: key already there, 2: table full (cannot happen at load <= 0.5)
 __device__ __forceinline__ int table_insert(unsigned long long* tab, int log_cap, unsigned long long key,
@@ -72,7 +79,7 @@ __device__ __forceinline__ int table_insert(unsigned long long* tab, int log_cap
       if (slot_out) *slot_out = s;
       return 1;
     }
-    s = (s + 1) & cap_mask;
+    s = (s + kProbeStep) & cap_mask;
   }
   return 2;
 }
@@ -88,7 +95,7 @@ __device__ __forceinline__ int table_find(const unsigned long long* tab, int log
       return (int)(unsigned)e.y;
     }
     if (e.x == kEmpty) return -1;
-    s = (s + 1) & cap_mask;
+    s = (s + kProbeStep) & cap_mask;
   }
   return -1;
 }

@@ -113,6 +113,19 @@ def test_errors(sp):
     _check_kmap(sp, c, 3, 1, False)
 
 
+def test_planar_and_line_sets(sp):
+    """Degenerate sets (constant z, constant y and z) load one slot class of the hash table."""
+    rng = np.random.default_rng(5)
+    xy = rng.permutation(90 * 90)[:5000]
+    plane = np.stack([np.zeros(5000, np.int64), xy // 90, xy % 90, np.full(5000, 8)], axis=1).astype(np.int32)
+    _check_kmap(sp, plane, 3, 1, False)
+    _check_kmap(sp, plane, 3, 2, False)
+    line = np.stack([np.zeros(3000, np.int64), rng.permutation(6000)[:3000] - 3000, np.full(3000, -4),
+                     np.full(3000, 12)], axis=1).astype(np.int32)
+    _check_kmap(sp, line, 3, 1, False)
+    _check_kmap(sp, line, 3, 2, True)
+
+
 def test_build_is_deterministic(sp):
     c = gen.uniform_cloud(5000, 24, seed=9)
     a = sp.build_kmap(coords_dev(c), 3, 2)

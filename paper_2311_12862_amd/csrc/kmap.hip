@@ -52,50 +52,66 @@ __device__ __forceinline__ unsigned long long pack_key(int b, int x, int y, int 
          ((unsigned long long)(unsigned)(y + 32768) << 16) | (unsigned long long)(unsigned)(z + 32768);
 }
 
-// Home slot of a key.  The two low z bits pick a slot inside a group of four neighbouring slots
-// (one 64-byte line) and only the rest of the key is hashed, so the three z-neighbours that a
-// probe looks up for one (dx, dy) share a line or touch two adjacent ones.  Collisions move on by
-// five slots: to the next group and the next slot within it, so that the probe sequence visits the
-// whole table even when every key has the same low z bits (a planar point set).
-__device__ __forceinline__ unsigned hash_slot(unsigned long long key, int log_cap) {
-  const unsigned group = (unsigned)(((key >> 2) * 0x9E3779B97F4A7C15ull) >> (64 - (log_cap - 2)));
-  return (group << 2) | (unsigned)(key & 3ull);
+// The table is an array of buckets of four 16-byte slots (one 64-byte line).  A key hashes to a
+// bucket; insertion takes the first free slot of the bucket, in order, and moves on to the next
+// bucket when all four are taken.  A lookup reads one line per step (four loads in flight) and
+// stops at the first empty slot; at load <= 0.5 a second step is rare.
+__device__ __forceinline__ unsigned hash_bucket(unsigned long long key, int log_cap) {
+  return (unsigned)((key * 0x9E3779B97F4A7C15ull) >> (64 - (log_cap - 2)));
 }
-constexpr unsigned kProbeStep = 5;
 
 // 0: inserted, 1: key already there, 2: table full (cannot happen at load <= 0.5)
 __device__ __forceinline__ int table_insert(unsigned long long* tab, int log_cap, unsigned long long key,
                                             int val, unsigned* slot_out) {
-  const unsigned cap_mask = (1u << log_cap) - 1u;
-  unsigned s = hash_slot(key, log_cap);
-  for (unsigned it = 0; it <= cap_mask; ++it) {
-    unsigned long long old = atomicCAS(&tab[2 * (size_t)s], kEmpty, key);
-    if (old == kEmpty) {
-      tab[2 * (size_t)s + 1] = (unsigned long long)(unsigned)val;
-      if (slot_out) *slot_out = s;
-      return 0;
+  const unsigned bucket_mask = (1u << (log_cap - 2)) - 1u;
+  unsigned b = hash_bucket(key, log_cap);
+  for (unsigned it = 0; it <= bucket_mask; ++it) {
+    for (unsigned i = 0; i < 4; ++i) {
+      const unsigned s = b * 4 + i;
+      const unsigned long long old = atomicCAS(&tab[2 * (size_t)s], kEmpty, key);
+      if (old == kEmpty) {
+        tab[2 * (size_t)s + 1] = (unsigned long long)(unsigned)val;
+        if (slot_out) *slot_out = s;
+        return 0;
+      }
+      if (old == key) {
+        if (slot_out) *slot_out = s;
+        return 1;
+      }
     }
-    if (old == key) {
-      if (slot_out) *slot_out = s;
-      return 1;
-    }
-    s = (s + kProbeStep) & cap_mask;
+    b = (b + 1) & bucket_mask;
   }
   return 2;
 }
 
 __device__ __forceinline__ int table_find(const unsigned long long* tab, int log_cap, unsigned long long key,
                                           unsigned* slot_out) {
-  const unsigned cap_mask = (1u << log_cap) - 1u;
-  unsigned s = hash_slot(key, log_cap);
-  for (unsigned it = 0; it <= cap_mask; ++it) {
-    const ulonglong2 e = *reinterpret_cast<const ulonglong2*>(&tab[2 * (size_t)s]);
-    if (e.x == key) {
-      if (slot_out) *slot_out = s;
-      return (int)(unsigned)e.y;
+  const unsigned bucket_mask = (1u << (log_cap - 2)) - 1u;
+  unsigned b = hash_bucket(key, log_cap);
+  for (unsigned it = 0; it <= bucket_mask; ++it) {
+    const ulonglong2* line = reinterpret_cast<const ulonglong2*>(tab) + (size_t)b * 4;
+    const ulonglong2 e0 = line[0], e1 = line[1], e2 = line[2], e3 = line[3];  // four loads in flight
+    if (e0.x == key) {
+      if (slot_out) *slot_out = b * 4;
+      return (int)(unsigned)e0.y;
     }
-    if (e.x == kEmpty) return -1;
-    s = (s + kProbeStep) & cap_mask;
+    if (e0.x == kEmpty) return -1;
+    if (e1.x == key) {
+      if (slot_out) *slot_out = b * 4 + 1;
+      return (int)(unsigned)e1.y;
+    }
+    if (e1.x == kEmpty) return -1;
+    if (e2.x == key) {
+      if (slot_out) *slot_out = b * 4 + 2;
+      return (int)(unsigned)e2.y;
+    }
+    if (e2.x == kEmpty) return -1;
+    if (e3.x == key) {
+      if (slot_out) *slot_out = b * 4 + 3;
+      return (int)(unsigned)e3.y;
+    }
+    if (e3.x == kEmpty) return -1;
+    b = (b + 1) & bucket_mask;
   }
   return -1;
 }

@@ -19,9 +19,10 @@ int hip_fail(hipError_t e, const char* what, const char* file, int line) {
 }
 
 // ---- device memory: user callbacks, else a small caching pool over hipMalloc.
-// Blocks handed back are reused by later requests of a similar size; reuse is
-// ordered by the stream the library's kernels run on, which is why all work of
-// one kmap has to stay on one stream.
+// Blocks handed back are reused by later requests of a similar size.  Nothing waits for the
+// kernels that used a block: reuse is safe because it is ordered by the stream, so a block is
+// only handed to a request made for the stream it was last used on.  Every entry point names
+// that stream for the duration of the call (StreamScope).
 namespace {
 std::mutex g_mem_mu;
 void* (*g_user_alloc)(size_t, void*) = nullptr;
@@ -31,7 +32,9 @@ void* g_user_ctx = nullptr;
 struct Block {
   void* p;
   size_t bytes;
+  hipStream_t stream;  // the stream whose work last touched the block
 };
+thread_local hipStream_t t_stream = nullptr;
 std::vector<Block> g_free_blocks;
 std::map<void*, size_t> g_live;
 size_t g_pooled_bytes = 0;
@@ -44,6 +47,9 @@ void pool_trim_locked() {
 }
 }  // namespace
 
+StreamScope::StreamScope(hipStream_t st) : saved_(t_stream) { t_stream = st; }
+StreamScope::~StreamScope() { t_stream = saved_; }
+
 void* dev_alloc(size_t bytes) {
   std::lock_guard<std::mutex> lk(g_mem_mu);
   if (g_user_alloc) return g_user_alloc(bytes, g_user_ctx);
@@ -51,6 +57,7 @@ void* dev_alloc(size_t bytes) {
   int best = -1;
   for (int i = 0; i < (int)g_free_blocks.size(); ++i) {
     const size_t b = g_free_blocks[i].bytes;
+    if (g_free_blocks[i].stream != t_stream) continue;
     if (b >= bytes && b <= bytes + bytes / 2 + 4096 && (best < 0 || b < g_free_blocks[best].bytes)) best = i;
   }
   if (best >= 0) {
@@ -88,7 +95,7 @@ void dev_free(void* p) {
     (void)hipFree(p);
     return;
   }
-  g_free_blocks.push_back({p, bytes});
+  g_free_blocks.push_back({p, bytes, t_stream});
   g_pooled_bytes += bytes;
 }
 
@@ -151,6 +158,7 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
                  spconv_dtype dtype, const spconv_config* cfg, void* dst, hipStream_t st) {
   if (!km || !dtype_ok(dtype)) return SPCONV_EINVAL;
   SPC_TRY(check_channels(C_in, C_out, dtype));
+  km->last_stream = st;
   const int64_t rows_dst = op == SPCONV_OP_FWD ? km->n_out : km->n_in;
   if (rows_dst == 0) return SPCONV_OK;
   if (!src || !weights || !dst) return SPCONV_EINVAL;
@@ -197,6 +205,7 @@ extern "C" {
 
 SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int stride, int transposed, void* stream,
                       spconv_kmap** out) {
+  StreamScope scope((hipStream_t)stream);
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
   if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
@@ -208,6 +217,7 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
 
 SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, int stride, int transposed,
                                        void* stream, spconv_kmap** out) {
+  StreamScope scope((hipStream_t)stream);
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
   if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
@@ -218,6 +228,7 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
 }
 
 SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km) return SPCONV_EINVAL;
   return kmap_status(km, (hipStream_t)stream);
 }
@@ -234,6 +245,7 @@ SPCONV_API int spconv_kmap_sizes(const spconv_kmap* km, int64_t* n_in, int64_t* 
 }
 
 SPCONV_API int spconv_kmap_out_coords(const spconv_kmap* km, int32_t* dst, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_out > 0)) return SPCONV_EINVAL;
   if (km->n_out == 0) return SPCONV_OK;
   const DevBuf& b = km->submanifold() ? km->in_coords : km->out_coords;
@@ -242,6 +254,7 @@ SPCONV_API int spconv_kmap_out_coords(const spconv_kmap* km, int32_t* dst, void*
 }
 
 SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_in > 0)) return SPCONV_EINVAL;
   if (km->n_in == 0) return SPCONV_OK;
   const DevBuf& b = (km->transposed && km->stride == 1) ? km->out_coords : km->in_coords;
@@ -250,6 +263,7 @@ SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* 
 }
 
 SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_out > 0)) return SPCONV_EINVAL;
   if (km->n_out == 0) return SPCONV_OK;
   SPC_HIP(hipMemcpyAsync(dst, km->out_side.map.p, (size_t)km->n_out * km->V * sizeof(int32_t),
@@ -258,6 +272,7 @@ SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* str
 }
 
 SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_out > 0)) return SPCONV_EINVAL;
   if (km->n_out == 0) return SPCONV_OK;
   SPC_HIP(hipMemcpyAsync(dst, km->out_side.mask.p, (size_t)km->n_out * sizeof(uint32_t), hipMemcpyDeviceToDevice,
@@ -266,8 +281,10 @@ SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, voi
 }
 
 SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_config* cfg, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || op < SPCONV_OP_FWD || op > SPCONV_OP_WGRAD) return SPCONV_EINVAL;
   hipStream_t st = (hipStream_t)stream;
+  km->last_stream = st;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, SPCONV_F16, &c));
   if (op == SPCONV_OP_WGRAD) {
@@ -283,6 +300,7 @@ SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_c
 
 SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
   if (!km) return SPCONV_EINVAL;
+  StreamScope scope(km->last_stream);
   SPC_HIP(hipDeviceSynchronize());
   km->out_side.plans.clear();
   km->in_side.plans.clear();
@@ -295,6 +313,7 @@ SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
 
 SPCONV_API int spconv_kmap_export_perm(spconv_kmap* km, spconv_op op, const spconv_config* cfg, int split, int32_t* dst,
                             void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || !dst || (op != SPCONV_OP_FWD && op != SPCONV_OP_DGRAD)) return SPCONV_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
@@ -312,6 +331,7 @@ SPCONV_API int spconv_kmap_export_perm(spconv_kmap* km, spconv_op op, const spco
 
 SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv_config* cfg, int64_t* executed,
                           int64_t* effective, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || !executed || !effective || (op != SPCONV_OP_FWD && op != SPCONV_OP_DGRAD)) return SPCONV_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
@@ -326,26 +346,34 @@ SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv
   return SPCONV_OK;
 }
 
-SPCONV_API void spconv_kmap_destroy(spconv_kmap* km) { delete km; }
+SPCONV_API void spconv_kmap_destroy(spconv_kmap* km) {
+  if (!km) return;
+  StreamScope scope(km->last_stream);  // its blocks go back to the pool of the stream that used them last
+  delete km;
+}
 
 SPCONV_API int spconv_fwd(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype,
                const spconv_config* cfg, void* out, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   return run_igemm_op(SPCONV_OP_FWD, feats, weights, km, C_in, C_out, dtype, cfg, out, (hipStream_t)stream);
 }
 
 SPCONV_API int spconv_dgrad(const void* dout, const void* weights, spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype,
                  const spconv_config* cfg, void* din, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   return run_igemm_op(SPCONV_OP_DGRAD, dout, weights, km, C_in, C_out, dtype, cfg, din, (hipStream_t)stream);
 }
 
 SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype,
                  const spconv_config* cfg, float* dweights, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || !dtype_ok(dtype) || !dweights) return SPCONV_EINVAL;
   SPC_TRY(check_channels(C_in, C_out, dtype));
   if ((km->n_out > 0 && km->n_in > 0) && (!feats || !dout)) return SPCONV_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
+  km->last_stream = st;
   if (km->n_pairs < 0 && !km->pending) SPC_TRY(kmap_count_pairs(km, st, nullptr));
   const int64_t target = c.wgrad_pairs > 0 ? c.wgrad_pairs : auto_wgrad_pairs(km, C_in, C_out);
   WgradPlan* wp = nullptr;
@@ -355,6 +383,7 @@ SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km
 
 SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype, spconv_op op, int layers_sharing_kmap,
                 spconv_config* best, float* best_us, void* stream) {
+  StreamScope scope((hipStream_t)stream);
   if (!km || !best || !dtype_ok(dtype) || op < SPCONV_OP_FWD || op > SPCONV_OP_WGRAD || layers_sharing_kmap < 1)
     return SPCONV_EINVAL;
   SPC_TRY(check_channels(C_in, C_out, dtype));

@@ -30,6 +30,17 @@ int hip_fail(hipError_t e, const char* what, const char* file, int line);
 
 void* dev_alloc(size_t bytes);
 void dev_free(void* p);
+// Names the stream that the pool's requests and returns of this thread belong to.
+class StreamScope {
+ public:
+  explicit StreamScope(hipStream_t st);
+  ~StreamScope();
+  StreamScope(const StreamScope&) = delete;
+  StreamScope& operator=(const StreamScope&) = delete;
+
+ private:
+  hipStream_t saved_;
+};
 
 // Owning device buffer (grow-only when used as scratch).
 struct DevBuf {
@@ -103,6 +114,7 @@ struct spconv_kmap {
   int K = 3, V = 27, stride = 1, transposed = 0;
   int64_t n_in = 0, n_out = 0, n_pairs = -1;
   hipStream_t build_stream = nullptr;
+  hipStream_t last_stream = nullptr;  // stream of the most recent call that used this kmap
   spc::DevBuf in_coords, out_coords;
   spc::SideMap out_side;  // M: rows = n_out, entries index input rows
   spc::SideMap in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)

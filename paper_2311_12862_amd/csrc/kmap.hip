@@ -719,6 +719,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   km->stride = stride;
   km->transposed = transposed;
   km->build_stream = st;
+  km->last_stream = st;
   const int V = km->V;
   const bool needs_coarse = stride > 1;
 

@@ -87,9 +87,11 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   typedef IgemmSmem<BM, BN, KC> S;
   typedef typename Mfma<T>::vec vec8;
   constexpr int LDA = S::LDA, LDB = S::LDB;
-  constexpr int WM = BM / 4;    // rows per wave
-  constexpr int MB = WM / 16;   // 16-row MFMA blocks per wave
-  constexpr int NB = BN / 16;   // 16-column MFMA blocks
+  // the four waves tile the workgroup's BM x BN outputs 2 x 2 (fewer fragment reads per MFMA than 4 x 1)
+  constexpr int WM = BM / 2;         // rows per wave
+  constexpr int WN = BN / 2;         // columns per wave
+  constexpr int MB = WM / 16;        // 16-row MFMA blocks per wave
+  constexpr int NB = WN / 16;        // 16-column MFMA blocks per wave
   constexpr int SEG = KC / 8;   // 16-byte segments per staged A row
   constexpr int A_RPP = 256 / SEG;
   constexpr int A_PASSES = BM / A_RPP;
@@ -103,6 +105,7 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   int* permS = reinterpret_cast<int*>(smem + S::a_bytes + S::b_bytes + S::map_bytes);
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wave_m = wave >> 1, wave_n = wave & 1;
   const int part = blockIdx.z;
   const long long tile = blockIdx.x;
   const int n0 = blockIdx.y * BN;
@@ -128,17 +131,21 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   // per-block offset masks: bit c set iff some row of the 16-row block has neighbour c
   unsigned blk_mask[MB];
   {
-    unsigned bits = 0;
-    if (lane < WM) {
-      const int* mr = mapS + (wave * WM + lane) * width;
-      for (int c = 0; c < width; ++c) bits |= (mr[c] >= 0 ? 1u : 0u) << c;
-    }
-    bits |= __shfl_xor(bits, 1);
-    bits |= __shfl_xor(bits, 2);
-    bits |= __shfl_xor(bits, 4);
-    bits |= __shfl_xor(bits, 8);
 #pragma unroll
-    for (int mb = 0; mb < MB; ++mb) blk_mask[mb] = __builtin_amdgcn_readlane(bits, mb * 16);
+    for (int m0 = 0; m0 < WM; m0 += 64) {  // 64 rows per round, one per lane
+      unsigned bits = 0;
+      if (m0 + lane < WM) {
+        const int* mr = mapS + (wave_m * WM + m0 + lane) * width;
+        for (int c = 0; c < width; ++c) bits |= (mr[c] >= 0 ? 1u : 0u) << c;
+      }
+      bits |= __shfl_xor(bits, 1);
+      bits |= __shfl_xor(bits, 2);
+      bits |= __shfl_xor(bits, 4);
+      bits |= __shfl_xor(bits, 8);
+#pragma unroll
+      for (int j = 0; j < 4; ++j)
+        if (m0 / 16 + j < MB) blk_mask[m0 / 16 + j] = __builtin_amdgcn_readlane(bits, j * 16);
+    }
   }
 
   f32x4 acc[MB][NB];
@@ -225,14 +232,14 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
     // last step they are harmless repeats of a valid step)
     load_regs(nxt_c, nxt_chunk);
 
-    const unsigned short* a = As + (wave * WM + fa) * LDA + fg * 8;
+    const unsigned short* a = As + (wave_m * WM + fa) * LDA + fg * 8;
 #pragma unroll
     for (int ks = 0; ks < KC / 32; ++ks) {
       vec8 bf[NB];
       if (!p.dgrad) {
         // 16 lanes fetch a 4 x 16 block of [ci][co] and each receives one column: 4 reduction
         // steps of its output channel; two reads give the lane's 8 steps (ci = 8*fg .. 8*fg+7)
-        const unsigned short* b = Bs + (ks * 32 + 8 * fg + (fa >> 2)) * LDB + 4 * (fa & 3);
+        const unsigned short* b = Bs + (ks * 32 + 8 * fg + (fa >> 2)) * LDB + wave_n * WN + 4 * (fa & 3);
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
           const s16x4 lo4 = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
@@ -244,7 +251,7 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
           bf[nb] = __builtin_bit_cast(vec8, v);
         }
       } else {
-        const unsigned short* b = Bs + fa * LDA + fg * 8;
+        const unsigned short* b = Bs + (wave_n * WN + fa) * LDA + fg * 8;
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDA + ks * 32);
       }
@@ -270,11 +277,11 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   for (int mb = 0; mb < MB; ++mb) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int orow = permS[wave * WM + mb * 16 + (lane >> 4) * 4 + r];
+      const int orow = permS[wave_m * WM + mb * 16 + (lane >> 4) * 4 + r];
       if (orow < 0) continue;
 #pragma unroll
       for (int nb = 0; nb < NB; ++nb) {
-        const int col = n0 + nb * 16 + (lane & 15);
+        const int col = n0 + wave_n * WN + nb * 16 + (lane & 15);
         if (col >= c_out) continue;
         const float v = acc[mb][nb][r];
         if (p.parts > 1)

@@ -76,7 +76,7 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
 /* Dataflow parameters (the design space of Section 4.1).  Zero-initialise for
  * the defaults.
  *   n_split     0: unsorted implicit GEMM, rows in map order, one pass.
- *               s >= 1 (at most 4): the K^3 offsets are cut into s contiguous
+ *               s >= 1 (at most 4 and at most K^3): the K^3 offsets are cut into s contiguous
  *               ranges [floor(i*V/s), floor((i+1)*V/s)); in each range the
  *               rows are visited in ascending order of that range's bitmask
  *               bits (stable), and for s > 1 the fp32 partial sums of the

@@ -164,13 +164,24 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   if (!src || !weights || !dst) return SPCONV_EINVAL;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
+  if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
+    // automatic tile height: 128 rows only when that still leaves several workgroups per CU
+    const int c_cols = op == SPCONV_OP_FWD ? C_out : C_in;
+    c.tile_m = ceil_div(rows_dst, 128) * ceil_div(c_cols, 128) >= 2048 ? 128 : 64;
+  }
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   const int c_red = os.dgrad ? C_out : C_in;
   bool wave = false;
   if (c.kernel != 2) {
-    wave = igemm_wave_pick_bn(km->V, c.n_split, c_red, os.dgrad ? C_in : C_out, c.tile_n, nullptr) > 0;
+    const int c_cols = os.dgrad ? C_in : C_out;
+    const int bn = igemm_wave_pick_bn(km->V, c.n_split, c_red, c_cols, c.tile_n, nullptr);
+    wave = bn > 0;
     if (!wave && c.kernel == 1) return SPCONV_EINVAL;
+    // Automatic choice: the LDS-resident kernel gathers the input once per column tile, so it only
+    // pays while the output is at most two tiles wide (64 -> 64 is 2 x 32); wider layers go to
+    // the tiled kernel, which gathers once per 128 columns.
+    if (wave && c.kernel == 0 && (c_cols + bn - 1) / bn > 2) wave = false;
   }
   if (!wave && c.tile_n == 16) return SPCONV_EINVAL;
   IgemmPlan* plan = nullptr;
@@ -414,7 +425,7 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
   } else {
     const int tiles[3] = {64, 128, 256};
     const int c_red = op == SPCONV_OP_DGRAD ? C_out : C_in, c_dst = op == SPCONV_OP_DGRAD ? C_in : C_out;
-    for (int s = 0; s <= kMaxSplit; ++s) {
+    for (int s = 0; s <= kMaxSplit && s <= km->V; ++s) {  // (a part needs at least one offset)
       for (int t = 0; t < (dtype == SPCONV_F32 ? 1 : 3); ++t) {
         spconv_config c{};
         c.n_split = s;

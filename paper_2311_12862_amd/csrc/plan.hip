@@ -246,6 +246,9 @@ __global__ void __launch_bounds__(1024)
 }  // namespace
 
 int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out) {
+  // every part needs at least one offset (a K = 1 map has a single one): the kernels index the
+  // last column of a part's map
+  if (n_split < 0 || n_split > kMaxSplit || n_split > km->V) return SPCONV_EINVAL;
   auto key = std::make_pair(n_split, tile_m);
   auto it = side.plans.find(key);
   if (it != side.plans.end()) {

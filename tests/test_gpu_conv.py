@@ -5,7 +5,7 @@ import torch
 
 from oracle import sparse_conv as oc
 from workloads import generators as gen
-from _util import TOL, coords_dev, make_layer, norm_err
+from _util import TOL, coords_dev, make_layer, norm_err, to_dev
 
 pytestmark = pytest.mark.gpu
 
@@ -236,3 +236,24 @@ def test_layer_on_a_pending_asynchronous_kmap(sp, cloud):
     assert norm_err(dx, oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
     assert norm_err(dw, oc.wgrad(x32, g32, ref.M)) <= 1e-4
     assert torch.equal(dw, sp.wgrad(x, g, km))
+
+
+def test_kernel_size_one_maps_tune_and_reject_empty_splits(sp):
+    """A K = 1 map has one offset: it cannot be split, and the tuner must not try."""
+    c = gen.uniform_cloud(3000, 20, seed=41)
+    km = sp.build_kmap(coords_dev(c), 1, 1)
+    ref = oc.build_kmap(c, 1, 1)
+    x32, xr = gen.features(len(c), 64, "f16", 42)
+    w32, wr = gen.weights(1, 64, 32, "f16", 43)
+    x, w = to_dev(xr, "f16"), to_dev(wr, "f16")
+    want = oc.forward(x32, w32, ref.M)
+    for op in (sp.OP_FWD, sp.OP_DGRAD, sp.OP_WGRAD):
+        best, us = sp.tune(km, 64, 32, torch.float16, op, 2)
+        assert best.n_split <= 1 and us > 0
+    cfg = sp.tune(km, 64, 32, torch.float16, sp.OP_FWD, 2)[0]
+    assert norm_err(sp.fwd(x, w, km, cfg), want) <= TOL["f16"]
+    bad = sp.Config()
+    bad.n_split = 2
+    with pytest.raises(sp.SpconvError) as e:
+        sp.fwd(x, w, km, bad)
+    assert e.value.status == -1

@@ -90,6 +90,25 @@ class GpuBackend:
         return a, b
 
 
+class TunedBackend(GpuBackend):
+    """The same network with every layer's dataflow chosen by spconv_tune (Section 4.2): one
+    configuration per (kernel map, channel pair, op), the mapping cost spread over `share` uses."""
+
+    def __init__(self, sp, coords, W, share):
+        super().__init__(sp, coords, W)
+        self.cfg, self.share = {}, share
+
+    def _cfg(self, km, ci, co, op):
+        key = (id(km), ci, co, op)
+        if key not in self.cfg:
+            self.cfg[key] = self.sp.tune(km, ci, co, torch.float16, op, self.share)[0]
+        return self.cfg[key]
+
+    def conv(self, x, name, km):
+        w = self.W[name]
+        return self.sp.fwd(x, w, km, self._cfg(km, w.shape[1], w.shape[2], self.sp.OP_FWD))
+
+
 def test_config5_minkunet_inference_and_training_step():
     import paper_2311_12862_amd as sp
     coords = gen.lidar_batch(5000, 4, target_n=PER_SCAN)
@@ -123,6 +142,13 @@ def test_config5_minkunet_inference_and_training_step():
     e_fwd = norm_err(got, want)
     print(f"inference output: max|y|={np.abs(want).max():.3g} err={e_fwd:.2e}")
     assert e_fwd <= 2e-2
+
+    # the same inference with tuned dataflows (sorted / split maps, both kernels, all tile shapes)
+    tb = TunedBackend(sp, coords, Wdev, 8)
+    e_tuned = norm_err(Net(tb).forward(x_dev), want)
+    kinds = sorted({(c.kernel, c.n_split) for c in tb.cfg.values()})
+    print(f"tuned inference: err={e_tuned:.2e}, (kernel, n_split) chosen: {kinds}")
+    assert e_tuned <= 2e-2
 
     # Training step.  ReLU gradients are decisions (y > 0) taken on forward activations; a value
     # that is +1e-4 on one side and 0 on the other flips a whole gradient element, so the two

@@ -380,7 +380,7 @@ size_t slab_bytes_for(int max_width, int bn, int parts) {
 // Largest BN in {64, 32, 16} (or exactly tile_n) for which the weights of the widest part plus
 // the per-wave slabs of at least 8 waves fit in LDS; 0 if none does.
 int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int* waves_out) {
-  if (c_red > 128) return 0;
+  if (c_red > 128 || n_split > V) return 0;  // (every part needs at least one offset)
   const int ks = (c_red + 31) / 32;
   const int parts = std::max(1, n_split);
   int max_width = 0;
@@ -391,12 +391,7 @@ int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int
     if (tile_n == 0 && bn > 16 && bn >= 2 * c_out) continue;  // no point in a tile twice as wide as the layer
     const size_t w = (size_t)max_width * bn * ks * 64;
     const size_t slab = slab_bytes_for(max_width, bn, parts);
-    static const int forced = [] {
-      const char* e = getenv("SPCONV_WAVES");  // developer knob: 8 or 16 waves per workgroup
-      return e ? atoi(e) : 0;
-    }();
     for (int waves : {16, 8}) {
-      if (forced && waves != forced) continue;
       if (w + (size_t)waves * slab <= kLdsBudget) {
         if (waves_out) *waves_out = waves;
         return bn;

@@ -198,16 +198,17 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   // the first block's map rows travel while the weights are being staged
   if (has_work) prefetch_block(block_of(wave));
 
-  // ---- weights of this part -> LDS (once per workgroup), four loads in flight per thread
+  // ---- weights of this part -> LDS (once per workgroup), kFill loads in flight per thread
+  constexpr int kFill = 8;
   {
     const unsigned slice = (unsigned)(p.C_in * p.C_out * 2);
     if (p.dgrad) {
       // B[kk = co][n = ci] = W[k][ci][co]: rows of W are already reduction-contiguous
       const int chunks = width * BN * ROW_CHUNKS;
-      for (int e0 = tid; e0 < chunks; e0 += 4 * blockDim.x) {
-        uint4 v[4];
+      for (int e0 = tid; e0 < chunks; e0 += kFill * blockDim.x) {
+        uint4 v[kFill];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kFill; ++u) {
           const int e = e0 + u * blockDim.x;
           const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
           const int k = lo + c;
@@ -217,7 +218,7 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
           v[u] = buf_load16(w_rsrc, ok ? off : 0xFFFFFFFFu);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kFill; ++u) {
           const int e = e0 + u * blockDim.x;
           const int q = e % ROW_CHUNKS, n = (e / ROW_CHUNKS) % BN, c = e / (ROW_CHUNKS * BN);
           if (e < chunks)
@@ -227,10 +228,10 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
     } else {
       // B[kk = ci][n = co] = W[k][ci][co]: read 8 output channels of one ci, scatter transposed
       const int vecs = width * ROW_HALFS * (BN / 8);
-      for (int e0 = tid; e0 < vecs; e0 += 4 * blockDim.x) {
-        uint4 v[4];
+      for (int e0 = tid; e0 < vecs; e0 += kFill * blockDim.x) {
+        uint4 v[kFill];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kFill; ++u) {
           const int e = e0 + u * blockDim.x;
           const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
           const int k = lo + c;
@@ -240,7 +241,7 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
           v[u] = buf_load16(w_rsrc, ok ? off : 0xFFFFFFFFu);
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < kFill; ++u) {
           const int e = e0 + u * blockDim.x;
           if (e >= vecs) continue;
           const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);

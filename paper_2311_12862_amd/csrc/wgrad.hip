@@ -79,7 +79,7 @@ __device__ __forceinline__ s16x8 read_frag(const unsigned short* tile, int row0,
   return s16x8{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
 }
 
-// TILE x TILE outputs of dW[k] per workgroup (64 or 128); each of the four waves owns a
+// TILE x TILE outputs of dW[k] per workgroup (32, 64 or 128); each of the four waves owns a
 // TILE/2 x TILE/2 quadrant as QB x QB MFMA blocks.  A larger tile gathers every pair's rows
 // fewer times when the layer has more than 64 channels.
 template <typename T, int TILE>
@@ -317,7 +317,8 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
       hipLaunchKernelGGL(k_wgrad_f32, grid, dim3(256), 0, st, p);
     } else {
       // 128 x 128 tiles as soon as a 64 x 64 tile would gather every pair's rows more than once
-      const int tile = (C_in > 64 || C_out > 64) ? 128 : 64;
+      // (and 32 x 32 tiles for layers of at most 32 channels, whose rows would otherwise be half padding)
+      const int tile = (C_in > 64 || C_out > 64) ? 128 : ((C_in > 32 || C_out > 32) ? 64 : 32);
       const unsigned tiles = (unsigned)(ceil_div(C_in, tile) * ceil_div(C_out, tile));
       const unsigned gx = (unsigned)std::min<int64_t>(wp.max_items, std::max<unsigned>(64u, 512u / tiles));
       dim3 grid(gx, (unsigned)ceil_div(C_in, tile), (unsigned)ceil_div(C_out, tile));
@@ -331,10 +332,12 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
         attr_set = true;
       }
       if (dtype == SPCONV_F16) {
-        if (tile == 64) hipLaunchKernelGGL((k_wgrad<_Float16, 64>), grid, dim3(256), smem, st, p);
+        if (tile == 32) hipLaunchKernelGGL((k_wgrad<_Float16, 32>), grid, dim3(256), smem, st, p);
+        else if (tile == 64) hipLaunchKernelGGL((k_wgrad<_Float16, 64>), grid, dim3(256), smem, st, p);
         else hipLaunchKernelGGL((k_wgrad<_Float16, 128>), grid, dim3(256), smem, st, p);
       } else {
-        if (tile == 64) hipLaunchKernelGGL((k_wgrad<__bf16, 64>), grid, dim3(256), smem, st, p);
+        if (tile == 32) hipLaunchKernelGGL((k_wgrad<__bf16, 32>), grid, dim3(256), smem, st, p);
+        else if (tile == 64) hipLaunchKernelGGL((k_wgrad<__bf16, 64>), grid, dim3(256), smem, st, p);
         else hipLaunchKernelGGL((k_wgrad<__bf16, 128>), grid, dim3(256), smem, st, p);
       }
     }

@@ -188,6 +188,9 @@ def main():
                       "fwd_kernel_e2e_cfg": round(t_fwd_e2e_cfg, 4),
                       "dgrad_kernel": round(t_dgrad, 4), "wgrad_kernels": round(t_wgrad, 4),
                       "fwd_mapping_first_call": round(map_f, 4), "wgrad_mapping_first_call": round(map_w, 4)},
+        # forward with its mapping (sort, reorder, tile masks) spread over L layers that share the kmap
+        "fwd_ms_with_mapping": {"sorted_cfg_L1": round(t_fwd + map_f, 4), "sorted_cfg_L4": round(t_fwd + map_f / 4, 4),
+                                "unsorted_cfg": round(t_fwd_e2e_cfg, 4)},
         "fwd_effective_tflops": round(fwd_tflops, 2),
         "dgrad_effective_tflops": round(flops_one / (t_dgrad * 1e-3) / 1e12, 2),
         "wgrad_effective_tflops": round(flops_one / (t_wgrad * 1e-3) / 1e12, 2),

@@ -122,10 +122,23 @@ __global__ void __launch_bounds__(256)
   const long long begin = w * ipw;
   const long long end = begin + ipw < n ? begin + ipw : n;
   const unsigned long long lt = (1ull << lane) - 1ull;
-  for (long long base = begin; base < end; base += 64) {
-    const long long i = base + lane;
+  // all of the wave's keys (and values) are fetched up front: the ranking steps below depend on
+  // each other through the running offsets, and a load inside them would expose its latency
+  // once per step
+  constexpr int STEPS = kItemsPerWave / 64;
+  KeyT kreg[STEPS];
+  int vreg[STEPS];
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const long long i = begin + s * 64 + lane;
+    kreg[s] = i < end ? kin[i] : (KeyT)0;
+    if (HAS_VAL) vreg[s] = i < end ? vin[i] : 0;
+  }
+#pragma unroll
+  for (int s = 0; s < STEPS; ++s) {
+    const long long i = begin + s * 64 + lane;
     const bool valid = i < end;
-    const KeyT key = valid ? kin[i] : (KeyT)0;
+    const KeyT key = kreg[s];
     const unsigned d = (unsigned)(key >> shift) & (unsigned)(bins - 1);
     unsigned long long peers = __ballot(valid);
     for (int b = 0; b < bits; ++b) {
@@ -141,7 +154,7 @@ __global__ void __launch_bounds__(256)
     __builtin_amdgcn_wave_barrier();
     if (valid) {
       kout[pos + rank] = key;
-      if (HAS_VAL) vout[pos + rank] = vin[i];
+      if (HAS_VAL) vout[pos + rank] = vreg[s];
     }
   }
 }

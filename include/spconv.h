@@ -208,6 +208,29 @@ SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km
 SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype, spconv_op op,
                 int layers_sharing_kmap, spconv_config* best, float* best_us, void* stream);
 
+/* One layer of a group: the layers of a network that use the same kmap (Section 4.2). */
+typedef struct spconv_layer_shape {
+  int32_t c_in, c_out;
+} spconv_layer_shape;
+
+/* Group-based tuning (Section 4.2).  All n_layers layers run on `km`, so they share one map
+ * structure: the tuner tries every split count of the design space (0 = unsorted, 1..min(4, K^3)
+ * sorted splits), gives each layer the fastest kernel and tile shape for that split count, adds
+ * the time to build every plan those choices need - paid once per group, not once per layer - and
+ * keeps the split count with the lowest measured total.
+ *   training = 0: forward only; fwd[n_layers] receives the configurations (dgrad, wgrad unused).
+ *   training = 1: dgrad[n_layers] and wgrad[n_layers] are filled as well.  bind_fwd_dgrad = 1
+ *     gives forward and dgrad the same split count (the paper's workload-pattern oriented binding:
+ *     the two kernels have the same shape); 0 tunes them apart.  wgrad is always tuned apart, and
+ *     with one value for the whole group: it walks weight-stationary pair lists whose only
+ *     parameter is the number of pairs per work item (in this library the maps that dgrad and
+ *     wgrad could share under the paper's sparse-mapping oriented binding are different objects).
+ * group_us (may be NULL): the winning total in microseconds, every layer once, mapping included.
+ * Blocking; allocates scratch tensors; leaves the winning plans to be rebuilt on first use. */
+SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* layers, int n_layers,
+                                 spconv_dtype dtype, int training, int bind_fwd_dgrad, spconv_config* fwd,
+                                 spconv_config* dgrad, spconv_config* wgrad, float* group_us, void* stream);
+
 /* Element-wise glue between layers of a network (not part of the paper's method: activation,
  * residual add and their gradients), so that a whole network can run on this library's kernels.
  *   op 0: out = max(a, 0)            (b ignored, may be NULL)

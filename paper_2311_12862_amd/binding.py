@@ -33,6 +33,11 @@ class Config(C.Structure):
                 f"wgrad_pairs={self.wgrad_pairs}, kernel={self.kernel})")
 
 
+class LayerShape(C.Structure):
+    """Mirror of spconv_layer_shape."""
+    _fields_ = [("c_in", C.c_int32), ("c_out", C.c_int32)]
+
+
 _LIB = None
 
 
@@ -70,6 +75,8 @@ def load_library():
         "spconv_dgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_wgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_tune": (i32, [vp, i32, i32, i32, i32, i32, cfgp, C.POINTER(C.c_float), vp]),
+        "spconv_tune_group": (i32, [vp, C.POINTER(LayerShape), i32, i32, i32, i32, cfgp, cfgp, cfgp,
+                                    C.POINTER(C.c_float), vp]),
         "spconv_ew": (i32, [i32, vp, vp, vp, i64, i32, vp]),
         "spconv_copy_cols": (i32, [vp, i32, i32, vp, i32, i32, i32, i64, i32, vp]),
         "spconv_set_allocator": (i32, [vp, vp, vp]),
@@ -259,6 +266,22 @@ def tune(kmap: KMap, c_in: int, c_out: int, dtype, op: int, layers_sharing_kmap:
     _check(load_library().spconv_tune(kmap.handle, c_in, c_out, _DTYPES[dtype], op, layers_sharing_kmap,
                                       C.byref(best), C.byref(us), _stream(stream)), "spconv_tune")
     return best, us.value
+
+
+def tune_group(kmap: KMap, layers, dtype, training: bool = False, bind_fwd_dgrad: bool = True, stream=None):
+    """spconv_tune_group: layers is a sequence of (c_in, c_out) of the layers that run on kmap.
+    Returns (fwd, dgrad, wgrad, microseconds): lists of Config, one per layer (dgrad and wgrad are
+    None for training=False)."""
+    n = len(layers)
+    shapes = (LayerShape * n)(*[LayerShape(int(ci), int(co)) for ci, co in layers])
+    fwd = (Config * n)()
+    dg = (Config * n)() if training else None
+    wg = (Config * n)() if training else None
+    us = C.c_float()
+    _check(load_library().spconv_tune_group(kmap.handle, shapes, n, _DTYPES[dtype], int(training), int(bind_fwd_dgrad),
+                                            fwd, dg, wg, C.byref(us), _stream(stream)), "spconv_tune_group")
+    copy = lambda arr: None if arr is None else [Config.from_buffer_copy(c) for c in arr]
+    return copy(fwd), copy(dg), copy(wg), us.value
 
 
 EW_RELU, EW_ADD, EW_ADD_RELU, EW_RELU_BWD = 0, 1, 2, 3

@@ -499,6 +499,226 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
   return status;
 }
 
+// ---- group tuner (Section 4.2): the layers that share a kmap take one map structure --------
+namespace {
+
+struct GroupTimer {
+  spconv_kmap* km;
+  spconv_dtype dtype;
+  hipStream_t st;
+  DevBuf x, y, w, dw;
+  hipEvent_t e0 = nullptr, e1 = nullptr;
+  ~GroupTimer() {
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+  }
+  float elapsed_ms() {
+    float ms = 0.f;
+    (void)hipEventRecord(e1, st);
+    (void)hipEventSynchronize(e1);
+    (void)hipEventElapsedTime(&ms, e0, e1);
+    return ms;
+  }
+  int run(spconv_op op, int ci, int co, const spconv_config& c) {
+    switch (op) {
+      case SPCONV_OP_FWD: return spconv_fwd(x.p, w.p, km, ci, co, dtype, &c, y.p, st);
+      case SPCONV_OP_DGRAD: return spconv_dgrad(y.p, w.p, km, ci, co, dtype, &c, x.p, st);
+      default: return spconv_wgrad(x.p, y.p, km, ci, co, dtype, &c, dw.as<float>(), st);
+    }
+  }
+  // warm kernel time in microseconds: best of two groups of four launches
+  int kernel_us(spconv_op op, int ci, int co, const spconv_config& c, float* us) {
+    SPC_TRY(run(op, ci, co, c));
+    float best = 1e30f;
+    for (int grp = 0; grp < 2; ++grp) {
+      (void)hipEventRecord(e0, st);
+      for (int r = 0; r < 4; ++r) SPC_TRY(run(op, ci, co, c));
+      best = std::min(best, elapsed_ms() / 4.f);
+    }
+    *us = best * 1000.f;
+    return SPCONV_OK;
+  }
+  // time to build the plan of c from scratch, in microseconds (best of two)
+  int mapping_us(spconv_op op, const spconv_config& c, float* us) {
+    float best = 1e30f;
+    for (int rep = 0; rep < 2; ++rep) {
+      SPC_TRY(spconv_kmap_drop_plans(km));
+      (void)hipEventRecord(e0, st);
+      if (op == SPCONV_OP_WGRAD) {
+        WgradPlan* wp = nullptr;
+        SPC_TRY(wplan_get(km, c.wgrad_pairs, st, &wp));
+      } else {
+        SPC_TRY(spconv_kmap_prepare(km, op, &c, st));
+      }
+      best = std::min(best, elapsed_ms());
+    }
+    *us = best * 1000.f;
+    return SPCONV_OK;
+  }
+};
+
+struct SplitChoice {                    // one op, one split count, every layer of the group
+  std::vector<spconv_config> cfg;       // fastest kernel / tile per distinct layer shape
+  float us = 1e30f;                     // sum over the layers + mapping of the plans they use
+};
+
+}  // namespace
+
+SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* layers, int n_layers, spconv_dtype dtype,
+                                 int training, int bind_fwd_dgrad, spconv_config* fwd, spconv_config* dgrad,
+                                 spconv_config* wgrad, float* group_us, void* stream) {
+  StreamScope scope((hipStream_t)stream);
+  if (!km || !layers || n_layers < 1 || !fwd || !dtype_ok(dtype)) return SPCONV_EINVAL;
+  if (training && (!dgrad || !wgrad)) return SPCONV_EINVAL;
+  int max_ci = 0, max_co = 0;
+  std::vector<std::pair<int, int>> shapes;  // distinct shapes
+  std::vector<int> shape_of(n_layers), count;
+  for (int i = 0; i < n_layers; ++i) {
+    SPC_TRY(check_channels(layers[i].c_in, layers[i].c_out, dtype));
+    max_ci = std::max(max_ci, layers[i].c_in);
+    max_co = std::max(max_co, layers[i].c_out);
+    const auto sh = std::make_pair(layers[i].c_in, layers[i].c_out);
+    size_t j = 0;
+    while (j < shapes.size() && shapes[j] != sh) ++j;
+    if (j == shapes.size()) {
+      shapes.push_back(sh);
+      count.push_back(0);
+    }
+    shape_of[i] = (int)j;
+    ++count[j];
+  }
+  GroupTimer t;
+  t.km = km;
+  t.dtype = dtype;
+  t.st = (hipStream_t)stream;
+  const size_t e = dtype == SPCONV_F32 ? 4 : 2;
+  SPC_TRY(t.x.alloc((size_t)std::max<int64_t>(km->n_in, 1) * max_ci * e));
+  SPC_TRY(t.y.alloc((size_t)std::max<int64_t>(km->n_out, 1) * max_co * e));
+  SPC_TRY(t.w.alloc((size_t)km->V * max_ci * max_co * e));
+  SPC_TRY(t.dw.alloc((size_t)km->V * max_ci * max_co * 4));
+  SPC_HIP(hipMemsetAsync(t.x.p, 0, t.x.bytes, t.st));  // zeros are valid numbers in every dtype
+  SPC_HIP(hipMemsetAsync(t.y.p, 0, t.y.bytes, t.st));
+  SPC_HIP(hipMemsetAsync(t.w.p, 0, t.w.bytes, t.st));
+  SPC_HIP(hipEventCreate(&t.e0));
+  SPC_HIP(hipEventCreate(&t.e1));
+  km->last_stream = t.st;
+
+  const int max_split = std::min(kMaxSplit, km->V);
+  // fwd / dgrad: for every split count, the fastest kernel and tile of each layer shape, plus the
+  // mapping time of every plan (split count, tile height) those choices need, paid once per group
+  auto tune_op = [&](spconv_op op, std::vector<SplitChoice>* out) -> int {
+    out->assign(max_split + 1, SplitChoice{});
+    for (int s = 0; s <= max_split; ++s) {
+      SplitChoice& ch = (*out)[s];
+      ch.cfg.resize(shapes.size());
+      float total = 0.f;
+      std::vector<int> plan_keys;  // tile heights whose plans are used (16 = kernel 1)
+      for (size_t j = 0; j < shapes.size(); ++j) {
+        const int ci = shapes[j].first, co = shapes[j].second;
+        const int c_red = op == SPCONV_OP_DGRAD ? co : ci, c_dst = op == SPCONV_OP_DGRAD ? ci : co;
+        std::vector<spconv_config> cands;
+        for (int tm : {64, 128, 256}) {
+          if (dtype == SPCONV_F32 && tm != 64) continue;
+          spconv_config c{};
+          c.n_split = s;
+          c.tile_m = tm;
+          c.kernel = 2;
+          cands.push_back(c);
+        }
+        if (dtype != SPCONV_F32)
+          for (int tn : {64, 32, 16}) {
+            if (tn >= 2 * c_dst && tn > 16) continue;
+            if (igemm_wave_pick_bn(km->V, s, c_red, c_dst, tn, nullptr) == 0) continue;
+            spconv_config c{};
+            c.n_split = s;
+            c.kernel = 1;
+            c.tile_n = tn;
+            cands.push_back(c);
+          }
+        float best = 1e30f;
+        for (const auto& c : cands) {
+          float us = 0.f;
+          SPC_TRY(t.kernel_us(op, ci, co, c, &us));
+          if (us < best) {
+            best = us;
+            ch.cfg[j] = c;
+          }
+        }
+        total += best * (float)count[j];
+        const int key = ch.cfg[j].kernel == 1 ? 16 : ch.cfg[j].tile_m;
+        if (std::find(plan_keys.begin(), plan_keys.end(), key) == plan_keys.end()) plan_keys.push_back(key);
+      }
+      for (int key : plan_keys) {
+        spconv_config c{};
+        c.n_split = s;
+        c.kernel = key == 16 ? 1 : 2;
+        c.tile_m = key == 16 ? 0 : key;
+        float us = 0.f;
+        SPC_TRY(t.mapping_us(op, c, &us));
+        total += us;
+      }
+      ch.us = total;
+    }
+    return SPCONV_OK;
+  };
+
+  std::vector<SplitChoice> f, d;
+  SPC_TRY(tune_op(SPCONV_OP_FWD, &f));
+  int sf = 0, sd = 0;
+  float total = 0.f;
+  if (!training) {
+    for (int s = 1; s <= max_split; ++s)
+      if (f[s].us < f[sf].us) sf = s;
+    total = f[sf].us;
+  } else {
+    SPC_TRY(tune_op(SPCONV_OP_DGRAD, &d));
+    if (bind_fwd_dgrad) {
+      for (int s = 1; s <= max_split; ++s)
+        if (f[s].us + d[s].us < f[sf].us + d[sf].us) sf = s;
+      sd = sf;
+    } else {
+      for (int s = 1; s <= max_split; ++s) {
+        if (f[s].us < f[sf].us) sf = s;
+        if (d[s].us < d[sd].us) sd = s;
+      }
+    }
+    total = f[sf].us + d[sd].us;
+  }
+  for (int i = 0; i < n_layers; ++i) {
+    fwd[i] = f[sf].cfg[shape_of[i]];
+    if (training) dgrad[i] = d[sd].cfg[shape_of[i]];
+  }
+  if (training) {
+    // wgrad walks the weight-stationary pair lists, whose only parameter is the pairs per work
+    // item: one value for the group, so that the lists are built once
+    if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, t.st, nullptr));
+    float best = 1e30f;
+    int32_t best_pairs = 0;
+    for (int32_t pairs : {768, 1536, 3072, 6144}) {
+      spconv_config c{};
+      c.wgrad_pairs = pairs;
+      float sum = 0.f, us = 0.f;
+      SPC_TRY(t.mapping_us(SPCONV_OP_WGRAD, c, &us));
+      sum += us;
+      for (size_t j = 0; j < shapes.size(); ++j) {
+        SPC_TRY(t.kernel_us(SPCONV_OP_WGRAD, shapes[j].first, shapes[j].second, c, &us));
+        sum += us * (float)count[j];
+      }
+      if (sum < best) {
+        best = sum;
+        best_pairs = pairs;
+      }
+    }
+    for (int i = 0; i < n_layers; ++i) {
+      wgrad[i] = spconv_config{};
+      wgrad[i].wgrad_pairs = best_pairs;
+    }
+    total += best;
+  }
+  if (group_us) *group_us = total;
+  return SPCONV_OK;
+}
+
 SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t, void*), void (*free_)(void*, void*), void* user) {
   if ((alloc == nullptr) != (free_ == nullptr)) return SPCONV_EINVAL;
   std::lock_guard<std::mutex> lk(g_mem_mu);

@@ -91,22 +91,52 @@ class GpuBackend:
 
 
 class TunedBackend(GpuBackend):
-    """The same network with every layer's dataflow chosen by spconv_tune (Section 4.2): one
-    configuration per (kernel map, channel pair, op), the mapping cost spread over `share` uses."""
+    """The same network under the group-based tuner of Section 4.2: the layers that run on one
+    kernel map form a group, and spconv_tune_group gives the group one map structure (split count)
+    and each of its layers the fastest kernel and tile shape for it."""
 
-    def __init__(self, sp, coords, W, share):
-        super().__init__(sp, coords, W)
-        self.cfg, self.share = {}, share
+    def __init__(self, base, training):
+        sp, W = base.sp, base.W
+        self.sp, self.W = sp, W
+        self.sub, self.one, self.down, self.up = base.sub, base.one, base.down, base.up  # the same kmaps
+        groups = {}                                   # id(kmap) -> (kmap, [layer names])
+        for name, km in self._layer_maps():
+            groups.setdefault(id(km), (km, []))[1].append(name)
+        self.fwd_cfg, self.dgrad_cfg, self.wgrad_cfg, self.group_us = {}, {}, {}, 0.0
+        for km, names in groups.values():
+            shapes = [(W[nm].shape[1], W[nm].shape[2]) for nm in names]
+            f, d, w, us = sp.tune_group(km, shapes, torch.float16, training=training)
+            self.group_us += us
+            for i, nm in enumerate(names):
+                self.fwd_cfg[nm] = f[i]
+                if training:
+                    self.dgrad_cfg[nm], self.wgrad_cfg[(id(km), shapes[i])] = d[i], w[i]
+        self.n_groups = len(groups)
 
-    def _cfg(self, km, ci, co, op):
-        key = (id(km), ci, co, op)
-        if key not in self.cfg:
-            self.cfg[key] = self.sp.tune(km, ci, co, torch.float16, op, self.share)[0]
-        return self.cfg[key]
+    def _layer_maps(self):
+        """(layer name, kmap) of every convolution, as Net.forward uses them."""
+        yield "stem", self.sub[0]
+        for i in range(1, 5):
+            yield f"down{i}", self.down[i - 1]
+            for blk in ("b1", "b2"):
+                for c in ("c1", "c2"):
+                    yield f"e{i}{blk}.{c}", self.sub[i]
+        for i in range(1, 5):
+            lvl = 4 - i
+            yield f"up{i}", self.up[lvl]
+            yield f"d{i}b1.proj", self.one[lvl]
+            for blk in ("b1", "b2"):
+                for c in ("c1", "c2"):
+                    yield f"d{i}{blk}.{c}", self.sub[lvl]
 
     def conv(self, x, name, km):
-        w = self.W[name]
-        return self.sp.fwd(x, w, km, self._cfg(km, w.shape[1], w.shape[2], self.sp.OP_FWD))
+        return self.sp.fwd(x, self.W[name], km, self.fwd_cfg[name])
+
+    def dgrad(self, dy, name, km):
+        return self.sp.dgrad(dy, self.W[name], km, self.dgrad_cfg[name])
+
+    def wgrad(self, x, dy, km):
+        return self.sp.wgrad(x, dy, km, self.wgrad_cfg[(id(km), (x.shape[1], dy.shape[1]))])
 
 
 def test_config5_minkunet_inference_and_training_step():
@@ -143,11 +173,13 @@ def test_config5_minkunet_inference_and_training_step():
     print(f"inference output: max|y|={np.abs(want).max():.3g} err={e_fwd:.2e}")
     assert e_fwd <= 2e-2
 
-    # the same inference with tuned dataflows (sorted / split maps, both kernels, all tile shapes)
-    tb = TunedBackend(sp, coords, Wdev, 8)
-    e_tuned = norm_err(Net(tb).forward(x_dev), want)
-    kinds = sorted({(c.kernel, c.n_split) for c in tb.cfg.values()})
-    print(f"tuned inference: err={e_tuned:.2e}, (kernel, n_split) chosen: {kinds}")
+    # the same inference under the group tuner (sorted / split maps, both kernels, all tile shapes)
+    tb = TunedBackend(gb, training=True)
+    assert set(tb.fwd_cfg) == set(shapes) and tb.n_groups == 17
+    tnet = Net(tb)
+    e_tuned = norm_err(tnet.forward(x_dev), want)
+    kinds = sorted({(c.kernel, c.n_split) for c in tb.fwd_cfg.values()})
+    print(f"group-tuned inference: err={e_tuned:.2e}, {tb.n_groups} groups, (kernel, n_split) chosen: {kinds}")
     assert e_tuned <= 2e-2
 
     # Training step.  ReLU gradients are decisions (y > 0) taken on forward activations; a value
@@ -181,3 +213,12 @@ def test_config5_minkunet_inference_and_training_step():
     for name, e in errs.items():
         assert e <= 2e-2, (name, e)
     assert e_dx <= 2e-2
+
+    # the training step under the group tuner's dgrad / wgrad configurations, on the same forward
+    # activations (same ReLU decisions): other dataflows, so equal up to summation order
+    tnet.tape, tnet.n_enc = gnet.tape, gnet.n_enc
+    dW_t, dx_t = tnet.backward(torch.from_numpy(gr).cuda())
+    e_t = max(norm_err(dW_t[name], dW_got[name].double().cpu().numpy()) for name in shapes)
+    e_tx = norm_err(dx_t, dx_got.double().cpu().numpy())
+    print(f"group-tuned training step vs default configurations: worst dW {e_t:.2e}, dx {e_tx:.2e}")
+    assert e_t <= 2e-2 and e_tx <= 2e-2

@@ -257,3 +257,29 @@ def test_kernel_size_one_maps_tune_and_reject_empty_splits(sp):
     with pytest.raises(sp.SpconvError) as e:
         sp.fwd(x, w, km, bad)
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("stride,bind", [(1, True), (2, False)])
+def test_group_tuner(sp, stride, bind):
+    """spconv_tune_group: one split count per group (fwd and dgrad bound or not), a configuration per
+    layer, one wgrad item size for the group; every returned configuration computes the layer."""
+    c = gen.lidar_scene(77, target_n=6000)
+    km = sp.build_kmap(coords_dev(c), 3, stride)
+    ref = oc.build_kmap(c, 3, stride)
+    layers = [(16, 16), (16, 32), (16, 16), (32, 16)]
+    f, d, w, us = sp.tune_group(km, layers, torch.float16, training=True, bind_fwd_dgrad=bind)
+    assert len(f) == len(d) == len(w) == 4 and us > 0
+    assert len({x.n_split for x in f}) == 1 and len({x.n_split for x in d}) == 1
+    assert len({x.wgrad_pairs for x in w}) == 1 and w[0].wgrad_pairs > 0
+    if bind:
+        assert f[0].n_split == d[0].n_split
+    assert f[0].n_split == f[2].n_split and repr(f[0]) == repr(f[2])      # equal shapes, equal choice
+    fi, _, _, us_inf = sp.tune_group(km, layers, torch.float16)
+    assert len(fi) == 4 and 0 < us_inf
+    for i, (ci, co) in enumerate(layers):
+        (x32, x), (w32, wt), (g32, g) = make_layer(ref.n_in, ref.n_out, ci, co, 27, "f16", 900 + i)
+        assert norm_err(sp.fwd(x, wt, km, f[i]), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+        assert norm_err(sp.dgrad(g, wt, km, d[i]), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+        assert norm_err(sp.wgrad(x, g, km, w[i]), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    with pytest.raises(sp.SpconvError):
+        sp.tune_group(km, [(16, 12)], torch.float16)   # channel counts must be multiples of 8

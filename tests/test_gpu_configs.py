@@ -104,3 +104,33 @@ def test_config4_room_300k_bf16(sp, room, width):
     assert norm_err(sp.fwd(x, w, km, _cfg(sp, n_split=2)), oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
     assert norm_err(sp.dgrad(g, w, km), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["bf16"]
     assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+
+
+def test_detection_style_stack(sp):
+    """A second workload shape (anisotropic 0.1 x 0.1 x 0.15 m voxels, a regular stack of
+    submanifold and stride-2 convolutions with 16..64 channels, as 3-D detectors use): maps
+    bit-exact at every level, every layer of the stack against the oracle under the group tuner."""
+    lvl = gen.detection_scene(6000)
+    assert 60_000 <= len(lvl) <= 100_000
+    widths = (16, 32, 64)
+    seed = 6100
+    for i, c in enumerate(widths):
+        ref = oc.build_kmap(lvl, 3, 1)
+        km = sp.build_kmap(coords_dev(lvl), 3, 1)
+        np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+        f, _, _, us = sp.tune_group(km, [(c, c), (c, c)], torch.float16)
+        (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, c, c, 27, "f16", seed + 10 * i)
+        assert norm_err(sp.fwd(x, w, km, f[0]), oc.forward(x32, w32, ref.M)) <= TOL["f16"], repr(f[0])
+        nu = (ref.M >= 0).sum() / ref.n_out
+        print(f"level {i}: {ref.n_out} voxels, nu={nu:.1f}, C={c}: group of two layers {us:.0f} us, "
+              f"n_split={f[0].n_split}, kernel={f[0].kernel}")
+        if i + 1 < len(widths):
+            dref = oc.build_kmap(lvl, 3, 2)
+            dkm = sp.build_kmap(coords_dev(lvl), 3, 2)
+            np.testing.assert_array_equal(dkm.export().cpu().numpy(), dref.M)
+            np.testing.assert_array_equal(dkm.out_coords().cpu().numpy(), dref.out_coords)
+            co = widths[i + 1]
+            (x32, x), (w32, w), _ = make_layer(dref.n_in, dref.n_out, c, co, 27, "f16", seed + 10 * i + 5)
+            fd, _, _, _ = sp.tune_group(dkm, [(c, co)], torch.float16)
+            assert norm_err(sp.fwd(x, w, dkm, fd[0]), oc.forward(x32, w32, dref.M)) <= TOL["f16"], repr(fd[0])
+            lvl = dref.out_coords

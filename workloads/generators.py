@@ -93,8 +93,8 @@ def _lidar_points(rng, n_ground: int, n_object: int) -> np.ndarray:
     return p
 
 
-def _quantize_unique(points_xyz: np.ndarray, voxel: float) -> np.ndarray:
-    """floor(p / v) then Unique (Section 2); rows come back in sorted order."""
+def _quantize_unique(points_xyz: np.ndarray, voxel) -> np.ndarray:
+    """floor(p / v) then Unique (Section 2); v a scalar or one size per axis; rows come back in sorted order."""
     q = np.floor(points_xyz / voxel).astype(np.int64)
     lo = q.min(axis=0)
     span = q.max(axis=0) - lo + 1
@@ -127,6 +127,14 @@ def lidar_scene(seed: int, batch: int = 0, target_n: int = 100_000) -> np.ndarra
         else:
             hi = mid
     return _finish(_quantize_unique(p[:hi], 0.05), batch, rng)
+
+
+def detection_scene(seed: int, batch: int = 0) -> np.ndarray:
+    """The same scan model voxelised the way 3-D detectors do (Section 2: anisotropic voxels of
+    0.1 x 0.1 x 0.15 m), every raw point used: coarser cells, denser neighbourhoods."""
+    rng = np.random.default_rng(seed)
+    p = _lidar_points(rng, LIDAR_RAW_GROUND, LIDAR_RAW_OBJECT)
+    return _finish(_quantize_unique(p, np.array([0.1, 0.1, 0.15])), batch, rng)
 
 
 def lidar_batch(seed: int, batches: int, target_n: int = 100_000) -> np.ndarray:

@@ -43,14 +43,18 @@ import numpy as np
 
 
 def offsets(K: int) -> list[tuple[int, int, int]]:
-    """Delta^3(K) (Section 2.1) as a list; position in the list is k."""
-    if K < 1 or K % 2 == 0:
-        raise ValueError("K must be odd and positive")
-    r = (K - 1) // 2
+    """Delta^3(K) (Section 2.1) as a list; position in the list is k.
+
+    The paper defines the neighbourhood for odd K only ({-r..r}^3, r = (K-1)/2).  Reading for
+    even K: {0..K-1}^3, so that K = s = 2 tiles space without overlap (every input belongs to
+    exactly one output), which is what the 2x2x2 / stride-2 layers of U-Nets compute."""
+    if K < 1:
+        raise ValueError("K must be positive")
+    lo, hi = (-((K - 1) // 2), (K - 1) // 2) if K % 2 else (0, K - 1)
     out = []
-    for dx in range(-r, r + 1):
-        for dy in range(-r, r + 1):
-            for dz in range(-r, r + 1):
+    for dx in range(lo, hi + 1):
+        for dy in range(lo, hi + 1):
+            for dz in range(lo, hi + 1):
                 out.append((dx, dy, dz))
     return out
 

@@ -22,22 +22,24 @@ def test_offsets_order_and_centre():
     for k, (dx, dy, dz) in enumerate(offs):
         assert k == 9 * (dx + 1) + 3 * (dy + 1) + (dz + 1)
     assert oc.offsets(1) == [(0, 0, 0)]
+    # even K (the paper defines odd K only): {0..K-1}^3 in the same order
+    assert oc.offsets(2) == [(0, 0, 0), (0, 0, 1), (0, 1, 0), (0, 1, 1), (1, 0, 0), (1, 0, 1), (1, 1, 0), (1, 1, 1)]
     with pytest.raises(ValueError):
-        oc.offsets(2)
+        oc.offsets(0)
 
 
 # ------------------------------------------------------ kmap vs brute force
 def _brute_kmap(in_pts, out_pts, K, stride):
     """O(N_out * N_in * K^3): test every (output, input) pair against Eq. 1."""
-    r = (K - 1) // 2
+    lo, hi = (-((K - 1) // 2), (K - 1) // 2) if K % 2 else (0, K - 1)
     M = -np.ones((len(out_pts), K ** 3), dtype=np.int64)
     for n, q in enumerate(out_pts):
         for j, p in enumerate(in_pts):
             if p[0] != q[0]:
                 continue
             d = [int(p[a]) - stride * int(q[a]) for a in (1, 2, 3)]
-            if all(-r <= v <= r for v in d):
-                k = ((d[0] + r) * K + (d[1] + r)) * K + (d[2] + r)
+            if all(lo <= v <= hi for v in d):
+                k = ((d[0] - lo) * K + (d[1] - lo)) * K + (d[2] - lo)
                 assert M[n, k] == -1
                 M[n, k] = j
     return M
@@ -170,6 +172,37 @@ def test_strided_forward_full_even_grid_is_strided_conv3d():
     ref = torch.nn.functional.conv3d(_dense_from_sparse(c, X, B, G), _torch_weight(W, 3), stride=2, padding=1)
     for (b, x, y, z), row in zip(km.out_coords, Y):
         np.testing.assert_allclose(row, ref[b, :, x, y, z].numpy(), rtol=1e-12, atol=1e-12)
+
+
+def test_even_kernel_stride2_is_conv3d_kernel2_and_partitions_the_inputs():
+    """K = s = 2: out[q] reads in[2q + delta], delta in {0,1}^3 = conv3d(kernel 2, stride 2, no
+    padding); on any cloud every input row appears in exactly one map entry."""
+    rng = np.random.default_rng(12)
+    G, B = 6, 2
+    c = gen.full_grid(G, B, seed=5)
+    X = rng.standard_normal((len(c), 3))
+    W = rng.standard_normal((8, 3, 4))
+    km = oc.build_kmap(c, 2, 2)
+    assert km.M.shape == (B * (G // 2) ** 3, 8)
+    Y = oc.forward(X, W, km.M)
+    ref = torch.nn.functional.conv3d(_dense_from_sparse(c, X, B, G), _torch_weight(W, 2), stride=2)
+    for (b, x, y, z), row in zip(km.out_coords, Y):
+        np.testing.assert_allclose(row, ref[b, :, x, y, z].numpy(), rtol=1e-12, atol=1e-12)
+    cloud = gen.uniform_cloud(500, 12, seed=8, lo=-5)
+    ks = oc.build_kmap(cloud, 2, 2)
+    hit = np.sort(ks.M[ks.M >= 0])
+    np.testing.assert_array_equal(hit, np.arange(len(cloud)))
+    np.testing.assert_array_equal(ks.M, _brute_kmap(cloud, ks.out_coords, 2, 2))
+    # transposed: the adjoint structure = conv_transpose3d(kernel 2, stride 2)
+    fine = gen.full_grid(G, 1, seed=6)
+    kt = oc.build_kmap(fine, 2, 2, transposed=True)
+    Xq = rng.standard_normal((kt.n_in, 2))
+    Wt = rng.standard_normal((8, 2, 3))
+    Yt = oc.forward(Xq, Wt, kt.M)
+    wt = torch.from_numpy(Wt).reshape(2, 2, 2, 2, 3).permute(3, 4, 0, 1, 2).contiguous()
+    reft = torch.nn.functional.conv_transpose3d(_dense_from_sparse(kt.in_coords, Xq, 1, G // 2), wt, stride=2)
+    for (b, x, y, z), row in zip(fine, Yt):
+        np.testing.assert_allclose(row, reft[b, :, x, y, z].numpy(), rtol=1e-12, atol=1e-12)
 
 
 def test_transposed_forward_full_grid_is_conv_transpose3d():

@@ -20,7 +20,9 @@
  *   - a coordinate row is (b, x, y, z), int32; b is the batch index, never
  *     offset or strided; x, y, z in [-32768, 32767], b in [0, 65534];
  *   - offset index k = ((dx+r)*K + (dy+r))*K + (dz+r), r = (K-1)/2, i.e. x
- *     slowest, z fastest; K is 1 or 3; bit k of a neighbour bitmask is 1u<<k;
+ *     slowest, z fastest; K is 1 or 3, or 2 with offsets {0, 1}^3 (r = 0: the
+ *     paper defines odd K only; with stride 2 this is the non-overlapping
+ *     2x2x2 layer); bit k of a neighbour bitmask is 1u<<k;
  *   - output q reads the input at s*q + delta with W[delta] (no kernel flip);
  *   - stride 1: P_out = P_in in input order; stride s > 1: P_out = unique
  *     floor(p / s), sorted ascending lexicographically in (b, x, y, z);
@@ -106,7 +108,7 @@ typedef struct spconv_config {
 /* Kernel-map construction ("mapping operations", Sections 3.1, 4.2, 6.2).
  *   coords      device, int32 [N][4] = (b, x, y, z), unique rows.
  *   N           number of rows, >= 0 (N = 0 gives an empty kmap).
- *   K           kernel size, 1 or 3.
+ *   K           kernel size: 1, 3, or 2 (K = 2 only together with stride 2).
  *   stride      >= 1 (stride 1 with transposed = 0 is the submanifold case).
  *   transposed  0: coords are P_in.  1: coords are the fine output set.
  *   out         receives a new kmap; release with spconv_kmap_destroy.

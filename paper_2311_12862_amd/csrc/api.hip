@@ -220,7 +220,8 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
   if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
-  if (K != 1 && K != 3) return SPCONV_EINVAL;
+  if (K != 1 && K != 2 && K != 3) return SPCONV_EINVAL;
+  if (K == 2 && stride != 2) return SPCONV_EINVAL;  // the even kernel is the non-overlapping 2x2x2 / stride-2 layer
   if (stride < 1 || stride > 64) return SPCONV_EINVAL;
   if (transposed != 0 && transposed != 1) return SPCONV_EINVAL;
   return kmap_build(coords, N, K, stride, transposed, false, (hipStream_t)stream, out);
@@ -232,7 +233,8 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
   if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
-  if (K != 1 && K != 3) return SPCONV_EINVAL;
+  if (K != 1 && K != 2 && K != 3) return SPCONV_EINVAL;
+  if (K == 2 && stride != 2) return SPCONV_EINVAL;  // the even kernel is the non-overlapping 2x2x2 / stride-2 layer
   if (stride < 1 || stride > 64) return SPCONV_EINVAL;
   if (transposed != 0 && transposed != 1) return SPCONV_EINVAL;
   return kmap_build(coords, N, K, stride, transposed, true, (hipStream_t)stream, out);

@@ -850,10 +850,12 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     km->n_out = needs_coarse ? U : N;
     const int4* qrows = needs_coarse ? coarse_rows.as<int4>() : rows;
     SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
-    status = (K == 3) ? launch_probe<3>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
-                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), ctl, st)
-                      : launch_probe<1>(false, qrows, km->n_out, stride, tab_fine.as<unsigned long long>(), lc_fine,
-                                        km->out_side.map.as<int>(), km->out_side.mask.as<unsigned>(), ctl, st);
+    int* mp = km->out_side.map.as<int>();
+    unsigned* mk = km->out_side.mask.as<unsigned>();
+    const unsigned long long* tf = tab_fine.as<unsigned long long>();
+    status = K == 3   ? launch_probe<3>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st)
+             : K == 2 ? launch_probe<2>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st)
+                      : launch_probe<1>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st);
     SPC_TRY(status);
   } else {
     km->n_in = needs_coarse ? U : N;
@@ -861,10 +863,11 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     const unsigned long long* tab = needs_coarse ? tab_coarse.as<unsigned long long>()
                                                  : tab_fine.as<unsigned long long>();
     SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
-    status = (K == 3) ? launch_probe<3>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
-                                        km->out_side.mask.as<unsigned>(), ctl, st)
-                      : launch_probe<1>(true, rows, N, stride, tab, lc_fine, km->out_side.map.as<int>(),
-                                        km->out_side.mask.as<unsigned>(), ctl, st);
+    int* mp = km->out_side.map.as<int>();
+    unsigned* mk = km->out_side.mask.as<unsigned>();
+    status = K == 3   ? launch_probe<3>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st)
+             : K == 2 ? launch_probe<2>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st)
+                      : launch_probe<1>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st);
     SPC_TRY(status);
   }
   km->out_side.ready = true;
@@ -918,12 +921,14 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
     }
     const int64_t rpw = 64 / V;
     const unsigned blocks = blocks_for(ceil_div(km->n_in, rpw), 4);
+    const int* tm = km->in_side.map.as<int>();
+    unsigned* tk = km->in_side.mask.as<unsigned>();
     if (V == 27)
-      hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
-                         (int)km->n_in, km->in_side.mask.as<unsigned>(), (Ctl*)nullptr);
+      hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks), dim3(256), 0, st, tm, (int)km->n_in, tk, (Ctl*)nullptr);
+    else if (V == 8)
+      hipLaunchKernelGGL((k_mask_from_map<8>), dim3(blocks), dim3(256), 0, st, tm, (int)km->n_in, tk, (Ctl*)nullptr);
     else
-      hipLaunchKernelGGL((k_mask_from_map<1>), dim3(blocks), dim3(256), 0, st, km->in_side.map.as<int>(),
-                         (int)km->n_in, km->in_side.mask.as<unsigned>(), (Ctl*)nullptr);
+      hipLaunchKernelGGL((k_mask_from_map<1>), dim3(blocks), dim3(256), 0, st, tm, (int)km->n_in, tk, (Ctl*)nullptr);
     SPC_LAUNCH_CHECK();
   }
   km->in_side.ready = true;

@@ -396,14 +396,17 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
                        p->item_seg.as<int>());
     SPC_LAUNCH_CHECK();
   }
+  const int* mp = side.map.as<int>();
+  const unsigned* mk = side.mask.as<unsigned>();
   if (V == 27)
-    hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
-                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, wave_rows, counts.as<unsigned>(),
-                       p->pairs.as<int2>());
+    hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
+  else if (V == 8)
+    hipLaunchKernelGGL((k_pair_fill<8>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
   else
-    hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, side.map.as<int>(),
-                       side.mask.as<unsigned>(), (long long)km->n_out, n_waves, wave_rows, counts.as<unsigned>(),
-                       p->pairs.as<int2>());
+    hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
   SPC_LAUNCH_CHECK();
   *out = p.get();
   km->wplans[target_pairs] = std::move(p);

@@ -283,3 +283,29 @@ def test_group_tuner(sp, stride, bind):
         assert norm_err(sp.wgrad(x, g, km, w[i]), oc.wgrad(x32, g32, ref.M)) <= 1e-4
     with pytest.raises(sp.SpconvError):
         sp.tune_group(km, [(16, 12)], torch.float16)   # channel counts must be multiples of 8
+
+
+@pytest.mark.parametrize("transposed", [False, True])
+def test_even_kernel_layers(sp, transposed):
+    """fwd / dgrad / wgrad on K = s = 2 maps (8 offsets), automatic and explicit configurations."""
+    c = gen.lidar_scene(91, target_n=9000)
+    km = sp.build_kmap(coords_dev(c), 2, 2, transposed)
+    ref = oc.build_kmap(c, 2, 2, transposed)
+    ci, co = (32, 64) if not transposed else (64, 32)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, ci, co, 8, "f16", 92)
+    want_f, want_d = oc.forward(x32, w32, ref.M), oc.dgrad(g32, w32, ref.M, ref.n_in)
+    cfgs = [None]
+    for kw in (dict(kernel=1, tile_n=32), dict(kernel=1, n_split=2, tile_n=32), dict(kernel=2, tile_m=64),
+               dict(kernel=2, n_split=4, tile_m=128)):
+        cfg = sp.Config()
+        for k, v in kw.items():
+            setattr(cfg, k, v)
+        cfgs.append(cfg)
+    for cfg in cfgs:
+        assert norm_err(sp.fwd(x, w, km, cfg), want_f) <= TOL["f16"], repr(cfg)
+        assert norm_err(sp.dgrad(g, w, km, cfg), want_d) <= TOL["f16"], repr(cfg)
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    f, d, wg, us = sp.tune_group(km, [(ci, co)], torch.float16, training=True)
+    assert norm_err(sp.fwd(x, w, km, f[0]), want_f) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, d[0]), want_d) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, km, wg[0]), oc.wgrad(x32, g32, ref.M)) <= 1e-4

@@ -46,6 +46,20 @@ def test_strided(sp, stride, lo):
     assert ref.n_out < 4000
 
 
+@pytest.mark.parametrize("transposed", [False, True])
+def test_even_kernel_stride2(sp, transposed):
+    """K = s = 2: the non-overlapping 2x2x2 layer and its transposed counterpart (8 offsets)."""
+    c = gen.uniform_cloud(4000, 20, seed=29, lo=-6)
+    c[:1300, 0] = 1
+    ref = _check_kmap(sp, c, 2, 2, transposed)
+    assert ref.M.shape[1] == 8
+    _check_kmap(sp, gen.lidar_scene(31, target_n=30_000), 2, 2, transposed)
+    _check_kmap(sp, np.array([[0, -1, 0, 3]], dtype=np.int32), 2, 2, transposed)
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(c), 2, 1, transposed)   # the even kernel exists for stride 2 only
+    assert e.value.status == -1
+
+
 @pytest.mark.parametrize("stride", [1, 2])
 def test_transposed(sp, stride):
     c = gen.uniform_cloud(3500, 18, seed=23, lo=-5)

@@ -83,16 +83,26 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *               rows are visited in ascending order of that range's bitmask
  *               bits (stable), and for s > 1 the fp32 partial sums of the
  *               ranges are added by a reduction kernel.
- *   kernel      which fwd / dgrad kernel runs (F16 / BF16 only):
+ *   kernel      which fwd / dgrad kernel runs (F16 / BF16 only; F32 always runs
+ *               its one kernel and refuses kernel = 3):
  *               1: weights of a split resident in LDS, one wave per 16-row
  *                  block (needs reduced channels <= 128 and the split's
  *                  weight slices for tile_n channels to fit in LDS, else
  *                  SPCONV_EINVAL); tile_m is ignored;
  *               2: workgroup tiles of tile_m rows, weights streamed per offset;
- *               0: 1 if it fits, else 2.
- *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 128).
+ *               3: the fetch-on-demand dataflow of Section 2.2.2 instead of
+ *                  implicit GEMM: the weight-stationary pair lists of the map
+ *                  (the ones wgrad walks) in tiles of tile_m pairs of one
+ *                  offset, products added to an fp32 accumulator with atomic
+ *                  adds, rounded once to the output type.  No multiply is
+ *                  spent on absent neighbours; results are the same up to
+ *                  the order of the fp32 additions (which varies from call to
+ *                  call).  Needs n_split = 0, else SPCONV_EINVAL;
+ *               0: never 3; 1 where it fits and the layer is narrow, else 2.
+ *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 128);
+ *               pairs per workgroup of kernel 3: 64 or 128 (0 = 64).
  *   tile_n      output channels per workgroup: 16, 32, 64 (kernel 1) or 32, 64,
- *               128 (kernel 2); 0 = chosen from the channel counts.
+ *               128 (kernels 2 and 3); 0 = chosen from the channel counts.
  *   wgrad_pairs target number of (output,input) pairs per wgrad workgroup
  *               (0 = chosen from the pair count); ignored by fwd / dgrad.
  */
@@ -200,8 +210,9 @@ SPCONV_API int spconv_dgrad(const void* dout, const void* weights, spconv_kmap* 
 SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km, int C_in, int C_out,
                  spconv_dtype dtype, const spconv_config* cfg_or_null, float* dweights, void* stream);
 
-/* Picks the configuration of the design space of Section 4.1 (number of
- * splits, sorted or not, tile sizes) with the lowest measured time for op on
+/* Picks the configuration of the design space of Section 4.1 (dataflow: implicit
+ * GEMM or fetch-on-demand; number of splits, sorted or not; tile sizes) with the
+ * lowest measured time for op on
  * this kmap and these channel counts, where time = kernel time + mapping time
  * / layers_sharing_kmap (layers that use the same maps form a group and share
  * the mapping cost, Section 4.2).  Blocking: allocates scratch tensors, runs
@@ -216,13 +227,14 @@ typedef struct spconv_layer_shape {
 } spconv_layer_shape;
 
 /* Group-based tuning (Section 4.2).  All n_layers layers run on `km`, so they share one map
- * structure: the tuner tries every split count of the design space (0 = unsorted, 1..min(4, K^3)
- * sorted splits), gives each layer the fastest kernel and tile shape for that split count, adds
- * the time to build every plan those choices need - paid once per group, not once per layer - and
- * keeps the split count with the lowest measured total.
+ * structure and one dataflow: the tuner tries every structure of the design space (implicit GEMM
+ * on the unsorted map or on 1..min(4, K^3) sorted splits; fetch-on-demand on the pair lists),
+ * gives each layer the fastest kernel and tile shape for that structure, adds the time to build
+ * every plan those choices need - paid once per group, not once per layer - and keeps the
+ * structure with the lowest measured total.
  *   training = 0: forward only; fwd[n_layers] receives the configurations (dgrad, wgrad unused).
  *   training = 1: dgrad[n_layers] and wgrad[n_layers] are filled as well.  bind_fwd_dgrad = 1
- *     gives forward and dgrad the same split count (the paper's workload-pattern oriented binding:
+ *     gives forward and dgrad the same structure (the paper's workload-pattern oriented binding:
  *     the two kernels have the same shape); 0 tunes them apart.  wgrad is always tuned apart, and
  *     with one value for the whole group: it walks weight-stationary pair lists whose only
  *     parameter is the number of pairs per work item (in this library the maps that dgrad and

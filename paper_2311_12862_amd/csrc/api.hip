@@ -117,7 +117,11 @@ int resolve_config(const spconv_config* cfg, spconv_dtype dtype, spconv_config* 
   if (c.tile_m == 0) c.tile_m = 128;
   if (c.tile_m != 64 && c.tile_m != 128 && c.tile_m != 256) return SPCONV_EINVAL;
   if (c.tile_n != 0 && c.tile_n != 16 && c.tile_n != 32 && c.tile_n != 64 && c.tile_n != 128) return SPCONV_EINVAL;
-  if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 2) return SPCONV_EINVAL;
+  if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 3) return SPCONV_EINVAL;
+  if (c.kernel == 3) {  // fetch-on-demand: unsorted pair lists, tiles of 64 or 128 pairs, 16-bit types
+    if (cfg->tile_m == 0) c.tile_m = 64;
+    if (dtype == SPCONV_F32 || c.n_split != 0 || c.tile_m == 256 || c.tile_n == 16) return SPCONV_EINVAL;
+  }
   if (dtype == SPCONV_F32) {  // the fp32 kernel has one tile shape
     c.tile_m = 64;
     c.kernel = 2;
@@ -164,6 +168,21 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   if (!src || !weights || !dst) return SPCONV_EINVAL;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
+  if (c.kernel == 3) {  // fetch-on-demand dataflow over the weight-stationary pair lists
+    const int dgrad = op == SPCONV_OP_DGRAD;
+    if (!fod_supported(km, dgrad, C_in, C_out, dtype)) return SPCONV_EINVAL;
+    WgradPlan* wp = nullptr;
+    SPC_TRY(wplan_get(km, c.tile_m, st, &wp));
+    IgemmArgs a{};
+    a.feats = src;
+    a.weights = weights;
+    a.C_in = C_in;
+    a.C_out = C_out;
+    a.dgrad = dgrad;
+    a.dtype = dtype;
+    a.tile_n = c.tile_n;
+    return fod_run(km, *wp, a, c.tile_m, dst, st);
+  }
   if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
     // automatic tile height: 128 rows only when that still leaves several workgroups per CU
     const int c_cols = op == SPCONV_OP_FWD ? C_out : C_in;
@@ -305,6 +324,10 @@ SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_c
     WgradPlan* wp = nullptr;
     return wplan_get(km, c.wgrad_pairs, st, &wp);
   }
+  if (c.kernel == 3) {
+    WgradPlan* wp = nullptr;
+    return wplan_get(km, c.tile_m, st, &wp);
+  }
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
@@ -427,6 +450,13 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
   } else {
     const int tiles[3] = {64, 128, 256};
     const int c_red = op == SPCONV_OP_DGRAD ? C_out : C_in, c_dst = op == SPCONV_OP_DGRAD ? C_in : C_out;
+    if (fod_supported(km, op == SPCONV_OP_DGRAD, C_in, C_out, dtype))
+      for (int tm : {64, 128}) {  // the fetch-on-demand dataflow (its mapping: the pair lists)
+        spconv_config c{};
+        c.kernel = 3;
+        c.tile_m = tm;
+        cands.push_back(c);
+      }
     for (int s = 0; s <= kMaxSplit && s <= km->V; ++s) {  // (a part needs at least one offset)
       for (int t = 0; t < (dtype == SPCONV_F32 ? 1 : 3); ++t) {
         spconv_config c{};
@@ -606,11 +636,20 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
   km->last_stream = t.st;
 
   const int max_split = std::min(kMaxSplit, km->V);
-  // fwd / dgrad: for every split count, the fastest kernel and tile of each layer shape, plus the
-  // mapping time of every plan (split count, tile height) those choices need, paid once per group
+  // The map structures a group can take: implicit GEMM on an unsorted map or on 1..max_split sorted
+  // splits (choices 0..max_split), or the fetch-on-demand dataflow on the pair lists (the last choice).
+  const int n_choices = max_split + 2, fod_choice = max_split + 1;
+  // fwd / dgrad: for every map structure, the fastest kernel and tile of each layer shape, plus the
+  // mapping time of every plan (structure, tile height) those choices need, paid once per group
   auto tune_op = [&](spconv_op op, std::vector<SplitChoice>* out) -> int {
-    out->assign(max_split + 1, SplitChoice{});
-    for (int s = 0; s <= max_split; ++s) {
+    out->assign(n_choices, SplitChoice{});
+    for (int s = 0; s < n_choices; ++s) {
+      const bool fod = s == fod_choice;
+      if (fod) {
+        bool ok = true;
+        for (const auto& sh : shapes) ok = ok && fod_supported(km, op == SPCONV_OP_DGRAD, sh.first, sh.second, dtype);
+        if (!ok) continue;  // stays at its initial, never-chosen time
+      }
       SplitChoice& ch = (*out)[s];
       ch.cfg.resize(shapes.size());
       float total = 0.f;
@@ -620,14 +659,14 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
         const int c_red = op == SPCONV_OP_DGRAD ? co : ci, c_dst = op == SPCONV_OP_DGRAD ? ci : co;
         std::vector<spconv_config> cands;
         for (int tm : {64, 128, 256}) {
-          if (dtype == SPCONV_F32 && tm != 64) continue;
+          if (fod ? tm == 256 : (dtype == SPCONV_F32 && tm != 64)) continue;
           spconv_config c{};
-          c.n_split = s;
+          c.n_split = fod ? 0 : s;
           c.tile_m = tm;
-          c.kernel = 2;
+          c.kernel = fod ? 3 : 2;
           cands.push_back(c);
         }
-        if (dtype != SPCONV_F32)
+        if (dtype != SPCONV_F32 && !fod)
           for (int tn : {64, 32, 16}) {
             if (tn >= 2 * c_dst && tn > 16) continue;
             if (igemm_wave_pick_bn(km->V, s, c_red, c_dst, tn, nullptr) == 0) continue;
@@ -652,8 +691,8 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
       }
       for (int key : plan_keys) {
         spconv_config c{};
-        c.n_split = s;
-        c.kernel = key == 16 ? 1 : 2;
+        c.n_split = fod ? 0 : s;
+        c.kernel = fod ? 3 : (key == 16 ? 1 : 2);
         c.tile_m = key == 16 ? 0 : key;
         float us = 0.f;
         SPC_TRY(t.mapping_us(op, c, &us));
@@ -669,17 +708,17 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
   int sf = 0, sd = 0;
   float total = 0.f;
   if (!training) {
-    for (int s = 1; s <= max_split; ++s)
+    for (int s = 1; s < n_choices; ++s)
       if (f[s].us < f[sf].us) sf = s;
     total = f[sf].us;
   } else {
     SPC_TRY(tune_op(SPCONV_OP_DGRAD, &d));
     if (bind_fwd_dgrad) {
-      for (int s = 1; s <= max_split; ++s)
+      for (int s = 1; s < n_choices; ++s)
         if (f[s].us + d[s].us < f[sf].us + d[sf].us) sf = s;
       sd = sf;
     } else {
-      for (int s = 1; s <= max_split; ++s) {
+      for (int s = 1; s < n_choices; ++s) {
         if (f[s].us < f[sf].us) sf = s;
         if (d[s].us < d[sd].us) sd = s;
       }

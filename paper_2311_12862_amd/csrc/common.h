@@ -180,6 +180,10 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
 int split_reduce(const float* partial, int parts, int64_t rows, int c, spconv_dtype dtype, void* out,
                  hipStream_t st);
 
+// ---- fod.hip (fetch-on-demand dataflow; wp must have been cut into items of tile_m pairs)
+bool fod_supported(const spconv_kmap* km, int dgrad, int C_in, int C_out, spconv_dtype dtype);
+int fod_run(spconv_kmap* km, const WgradPlan& wp, const IgemmArgs& a, int tile_m, void* dst, hipStream_t st);
+
 // ---- wgrad.hip
 int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const void* dout, int C_in,
               int C_out, spconv_dtype dtype, float* dweights, hipStream_t st);

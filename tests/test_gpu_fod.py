@@ -1,0 +1,139 @@
+"""The fetch-on-demand dataflow (Section 2.2.2; `kernel = 3`) against the fp64 oracle.
+
+It computes the same forward and input gradient as the implicit-GEMM kernels, from the
+weight-stationary pair lists with atomic scatter, so every case compares with the plain definition.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import sparse_conv as oc
+from workloads import generators as gen
+from _util import TOL, coords_dev, make_layer, norm_err
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def sp():
+    import paper_2311_12862_amd as sp
+    return sp
+
+
+def _cfg(sp, tile_m=0, tile_n=0, n_split=0):
+    c = sp.Config()
+    c.kernel, c.tile_m, c.tile_n, c.n_split = 3, tile_m, tile_n, n_split
+    return c
+
+
+@pytest.fixture(scope="module")
+def cloud():
+    c = gen.lidar_scene(79, target_n=2900)
+    return c, oc.build_kmap(c, 3, 1)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("c_in,c_out", [(64, 64), (32, 96), (96, 32), (8, 16), (128, 256), (256, 128), (24, 40)])
+def test_forward_and_dgrad_channels(sp, cloud, dtype, c_in, c_out):
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 5)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    want_y, want_dx = oc.forward(x32, w32, ref.M), oc.dgrad(g32, w32, ref.M, ref.n_in)
+    for tile_m in (0, 64, 128):
+        cfg = _cfg(sp, tile_m)
+        assert norm_err(sp.fwd(x, w, km, cfg), want_y) <= TOL[dtype], tile_m
+        assert norm_err(sp.dgrad(g, w, km, cfg), want_dx) <= TOL[dtype], tile_m
+
+
+@pytest.mark.parametrize("tile_m", [64, 128])
+@pytest.mark.parametrize("tile_n", [32, 64, 128])
+def test_tile_shapes(sp, cloud, tile_m, tile_n):
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 72, 104, 27, "f16", 6)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    cfg = _cfg(sp, tile_m, tile_n)
+    assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    # a second call on the same accumulator starts from zero again
+    assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+
+
+@pytest.mark.parametrize("K,stride,transposed", [(3, 2, False), (3, 2, True), (2, 2, False), (2, 2, True),
+                                                 (1, 1, False), (3, 3, False)])
+def test_all_map_kinds(sp, K, stride, transposed):
+    c = gen.lidar_scene(80, target_n=2500)
+    ref = oc.build_kmap(c, K, stride, transposed)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, K ** 3, "f16", 11)
+    km = sp.build_kmap(coords_dev(c), K, stride, transposed)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    cfg = _cfg(sp)
+    assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    # the pair lists serve the weight gradient as well, whichever dataflow built them first
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+
+
+def test_after_asynchronous_build(sp):
+    """The pair count is not on the host yet: buffers and grid come from the bound rows x 27."""
+    c = gen.lidar_scene(81, target_n=2000)
+    ref = oc.build_kmap(c, 3, 1)
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 12)
+    km = sp.build_kmap(coords_dev(c), 3, 1, asynchronous=True)
+    got = sp.fwd(x, w, km, _cfg(sp))
+    km.status()
+    assert norm_err(got, oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+
+
+def test_dense_cube_and_isolated_points(sp):
+    cube = gen.full_grid(9, 2, seed=4)
+    ref = oc.build_kmap(cube, 3, 1)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 32, 27, "bf16", 32)
+    km = sp.build_kmap(coords_dev(cube), 3, 1)
+    assert norm_err(sp.fwd(x, w, km, _cfg(sp)), oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
+    iso = gen.uniform_cloud(300, 10, seed=2) * np.array([1, 3, 3, 3], dtype=np.int32)
+    ref = oc.build_kmap(iso, 3, 1)
+    (x32, x), (w32, w), (g32, g) = make_layer(300, 300, 32, 32, 27, "f16", 31)
+    km = sp.build_kmap(coords_dev(iso), 3, 1)
+    assert norm_err(sp.fwd(x, w, km, _cfg(sp, 128)), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, _cfg(sp, 128)), oc.dgrad(g32, w32, ref.M, 300)) <= TOL["f16"]
+
+
+def test_empty_and_single_point(sp):
+    km = sp.build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
+    x = torch.zeros((0, 32), dtype=torch.float16, device="cuda")
+    w = torch.zeros((27, 32, 32), dtype=torch.float16, device="cuda")
+    assert sp.fwd(x, w, km, _cfg(sp)).shape == (0, 32)
+    one = np.array([[0, 5, 6, 7]], dtype=np.int32)
+    ref = oc.build_kmap(one, 3, 1)
+    (x32, x), (w32, w), _ = make_layer(1, 1, 16, 16, 27, "f16", 41)
+    km = sp.build_kmap(coords_dev(one), 3, 1)
+    assert norm_err(sp.fwd(x, w, km, _cfg(sp)), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+
+
+def test_rejected_configurations(sp, cloud):
+    c, ref = cloud
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    (x32, x), (w32, w), _ = make_layer(ref.n_in, ref.n_out, 16, 16, 27, "f16", 7)
+    for bad in (_cfg(sp, 256), _cfg(sp, 64, 16), _cfg(sp, 64, 0, n_split=1)):
+        with pytest.raises(sp.SpconvError) as e:
+            sp.fwd(x, w, km, bad)
+        assert e.value.status == -1
+    (x32, xf), (w32, wf), _ = make_layer(ref.n_in, ref.n_out, 16, 16, 27, "f32", 7)
+    with pytest.raises(sp.SpconvError) as e:   # 16-bit types only: the call must refuse, not fall back
+        sp.fwd(xf, wf, km, _cfg(sp))
+    assert e.value.status == -1
+
+
+def test_tuners_consider_it(sp):
+    """On a small, wide layer the design space includes the second dataflow; whatever wins is correct."""
+    c = gen.lidar_scene(82, target_n=1200)
+    ref = oc.build_kmap(c, 3, 1)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 128, 128, 27, "f16", 51)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    best, us = sp.tune(km, 128, 128, torch.float16, sp.OP_FWD, 4)
+    assert best.kernel in (1, 2, 3) and us > 0
+    assert norm_err(sp.fwd(x, w, km, best), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    fwd, dgr, wgr, us = sp.tune_group(km, [(128, 128)] * 3, torch.float16, training=True)
+    assert fwd[0].kernel == dgr[0].kernel or 3 not in (fwd[0].kernel, dgr[0].kernel)  # bound: one dataflow
+    assert norm_err(sp.fwd(x, w, km, fwd[0]), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, dgr[0]), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]

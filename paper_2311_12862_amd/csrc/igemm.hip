@@ -39,6 +39,7 @@ struct IgemmParams {
   int c_red, c_out;  // reduced / produced channel counts
   int C_in, C_out;   // of the layer
   int dgrad, mirror;
+  int heavy_first;   // sorted maps: tiles late in the sort order hold the most offsets; start them first
   unsigned feats_bytes;  // size of the gathered tensor (16-bit kernels address it through a buffer descriptor)
 };
 
@@ -107,7 +108,7 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wave_m = wave >> 1, wave_n = wave & 1;
   const int part = blockIdx.z;
-  const long long tile = blockIdx.x;
+  const long long tile = p.heavy_first ? (long long)gridDim.x - 1 - blockIdx.x : blockIdx.x;
   const int n0 = blockIdx.y * BN;
   const int width = p.width[part], lo = p.lo[part];
   const long long row0 = tile * BM;
@@ -117,13 +118,26 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 2));
   const unsigned row_bytes = (unsigned)c_red * 2u, slice_bytes = (unsigned)(p.C_in * p.C_out) * 2u;
 
-  {  // map slab and output rows of this tile
-    const int* mp = p.map[part] + row0 * width;
-    for (int e = tid; e < BM * width; e += 256) mapS[e] = mp[e];
+  {  // map slab and output rows of this tile: every load is issued before the first one is awaited
+    // (the slab is BM * width consecutive ints; tiles start on 256-byte boundaries)
+    constexpr int SLAB_IT = (BM * 27 / 4 + 255) / 256;
+    const int4* mp4 = reinterpret_cast<const int4*>(p.map[part] + row0 * width);
+    const int n4 = BM * width / 4;
+    int4 slab[SLAB_IT];
+#pragma unroll
+    for (int i = 0; i < SLAB_IT; ++i) {
+      const int e = tid + 256 * i;
+      if (e < n4) slab[i] = mp4[e];
+    }
     const int* pm = p.perm[part];
     for (int r = tid; r < BM; r += 256) {
       const long long g = row0 + r;
       permS[r] = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+    }
+#pragma unroll
+    for (int i = 0; i < SLAB_IT; ++i) {
+      const int e = tid + 256 * i;
+      if (e < n4) reinterpret_cast<int4*>(mapS)[e] = slab[i];
     }
   }
   __syncthreads();
@@ -135,8 +149,12 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
     for (int m0 = 0; m0 < WM; m0 += 64) {  // 64 rows per round, one per lane
       unsigned bits = 0;
       if (m0 + lane < WM) {
+        // all 27 reads are issued at once; entries past `width` belong to the next row or to the
+        // unused end of the slab's LDS and are masked off
         const int* mr = mapS + (wave_m * WM + m0 + lane) * width;
-        for (int c = 0; c < width; ++c) bits |= (mr[c] >= 0 ? 1u : 0u) << c;
+#pragma unroll
+        for (int c = 0; c < 27; ++c) bits |= (mr[c] >= 0 ? 1u : 0u) << c;
+        bits &= (1u << width) - 1u;
       }
       bits |= __shfl_xor(bits, 1);
       bits |= __shfl_xor(bits, 2);
@@ -157,10 +175,10 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
   const int n_chunks = (c_red + KC - 1) / KC;
   const int total = __popc(tmask) * n_chunks;
 
-  uint4 ra[A_PASSES], rb[B_PASSES];
+  uint4 ra0[A_PASSES], rb0[B_PASSES];  // operands of the step that is on its way
   const int a_seg = tid % SEG, a_row = tid / SEG;
 
-  auto load_regs = [&](int c, int chunk) {
+  auto load_regs = [&](uint4* ra, uint4* rb, int c, int chunk) {
     const unsigned col = (unsigned)(chunk * KC + a_seg * 8);
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps) {
@@ -190,7 +208,7 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
     }
   };
 
-  auto store_lds = [&]() {
+  auto store_lds = [&](const uint4* ra, const uint4* rb) {
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps)
       *reinterpret_cast<uint4*>(As + (a_row + ps * A_RPP) * LDA + a_seg * 8) = ra[ps];
@@ -210,28 +228,9 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
     }
   };
 
-  unsigned m_rem = tmask;
-  int cur_c = 0, cur_chunk = 0;
-  if (total > 0) {
-    cur_c = __ffs((int)m_rem) - 1;
-    m_rem &= m_rem - 1;
-    load_regs(cur_c, 0);
-    store_lds();
-  }
-  __syncthreads();
-
   const int fa = lane & 15, fg = lane >> 4;
-  for (int it = 0; it < total; ++it) {
-    int nxt_c = cur_c, nxt_chunk = cur_chunk + 1;
-    if (nxt_chunk == n_chunks) {
-      nxt_chunk = 0;
-      nxt_c = m_rem ? __ffs((int)m_rem) - 1 : 0;
-      m_rem &= m_rem - 1;
-    }
-    // the loads of the next step travel while this one is on the matrix cores (past the
-    // last step they are harmless repeats of a valid step)
-    load_regs(nxt_c, nxt_chunk);
-
+  // one step (offset c, one chunk of the reduction) out of the LDS tiles
+  auto compute = [&](int c) {
     const unsigned short* a = As + (wave_m * WM + fa) * LDA + fg * 8;
 #pragma unroll
     for (int ks = 0; ks < KC / 32; ++ks) {
@@ -257,18 +256,51 @@ __global__ void __launch_bounds__(256) k_igemm(const IgemmParams p) {
       }
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
-        if ((blk_mask[mb] >> cur_c) & 1u) {
+        if ((blk_mask[mb] >> c) & 1u) {
           const vec8 af = *reinterpret_cast<const vec8*>(a + mb * 16 * LDA + ks * 32);
 #pragma unroll
           for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = Mfma<T>::run(af, bf[nb], acc[mb][nb]);
         }
       }
     }
+  };
+
+  // The steps in order: set bits of the tile mask, ascending, each with its chunks.  The loads of
+  // a step are issued one step ahead of the matrix cores and wait in registers; one step lives in
+  // LDS.  (A second register set, two steps ahead, was measured and changed nothing.)
+  unsigned m_rem = tmask;
+  int iss_c = 0, iss_chunk = 0, issued = 0;  // the next step to issue
+  if (total > 0) {
+    iss_c = __ffs((int)m_rem) - 1;
+    m_rem &= m_rem - 1;
+  }
+  int c_lds = 0, c_regs = 0;  // offsets of the step in LDS and of the step held in registers
+  auto issue = [&]() {
+    if (issued < total) {
+      load_regs(ra0, rb0, iss_c, iss_chunk);
+      c_regs = iss_c;
+      if (++iss_chunk == n_chunks) {
+        iss_chunk = 0;
+        iss_c = m_rem ? __ffs((int)m_rem) - 1 : 0;
+        m_rem &= m_rem - 1;
+      }
+    }
+    ++issued;
+  };
+  if (total > 0) {
+    issue();
+    store_lds(ra0, rb0);
+    c_lds = c_regs;
+  }
+  __syncthreads();
+  for (int it = 0; it < total; ++it) {
+    issue();  // the next step travels while this one is on the matrix cores
+    compute(c_lds);
+    if (it + 1 >= total) break;
     __syncthreads();  // everyone is done reading this step's tiles
-    store_lds();
+    store_lds(ra0, rb0);
+    c_lds = c_regs;
     __syncthreads();
-    cur_c = nxt_c;
-    cur_chunk = nxt_chunk;
   }
 
   // D layout of the 16x16 MFMA: lane holds rows 4*(lane/16)+r, column lane%16
@@ -500,6 +532,9 @@ int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan,
   if (bn == 0) bn = p.c_out <= 32 ? 32 : (p.c_out <= 64 ? 64 : 128);
   const int kc = (p.c_red % 64 == 0) ? 64 : 32;
   dim3 grid((unsigned)plan.n_tiles, (unsigned)ceil_div(p.c_out, bn), (unsigned)plan.parts);
+  // tiles late in a bitmask-sorted order hold the most offsets: they start first, so that the
+  // grid does not end on its longest workgroups
+  p.heavy_first = plan.n_split > 0 ? 1 : 0;
   if (a.dtype == SPCONV_F16) return launch_bm<_Float16>(p, plan.tile_m, bn, kc, grid, st);
   return launch_bm<__bf16>(p, plan.tile_m, bn, kc, grid, st);
 }

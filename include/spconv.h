@@ -260,8 +260,11 @@ SPCONV_API int spconv_copy_cols(const void* src, int src_ld, int src_off, void* 
                                 int64_t rows, spconv_dtype dtype, void* stream);
 
 /* Device allocations made by the library go through these callbacks when set
- * (so that a framework's caching allocator can back them); NULL restores
- * hipMalloc / hipFree. */
+ * (so that a framework's caching allocator can back them); NULL, NULL restores
+ * the library's own pool over hipMalloc.  alloc returns a device pointer aligned
+ * to 256 bytes, or NULL when out of memory; both run on the calling host thread,
+ * inside library calls.  Switch allocators only while no kmap is alive: a block
+ * goes back to whatever is installed when it is released. */
 SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* user), void (*free_)(void* ptr, void* user),
                          void* user);
 

@@ -92,6 +92,29 @@ def load_library():
     return lib
 
 
+_ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
+_FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+_allocator_refs = None   # keeps the ctypes thunks of the installed callbacks alive
+
+
+def set_allocator(alloc=None, free=None):
+    """spconv_set_allocator: alloc(bytes) -> device address (int, 0 = out of memory) and free(address)
+    serve every device allocation the library makes from now on; (None, None) restores its own pool.
+    Switch only while no kmap is alive."""
+    global _allocator_refs
+    if (alloc is None) != (free is None):
+        raise ValueError("give both callbacks or neither")
+    lib = load_library()
+    if alloc is None:
+        _check(lib.spconv_set_allocator(None, None, None), "spconv_set_allocator")
+        _allocator_refs = None
+        return
+    a = _ALLOC_FN(lambda n, _user: int(alloc(int(n))) or None)
+    f = _FREE_FN(lambda ptr, _user: free(int(ptr or 0)))
+    _check(lib.spconv_set_allocator(C.cast(a, C.c_void_p), C.cast(f, C.c_void_p), None), "spconv_set_allocator")
+    _allocator_refs = (a, f)
+
+
 def _check(status: int, where: str):
     if status != 0:
         raise SpconvError(status, where)

@@ -173,3 +173,42 @@ def test_asynchronous_build(sp):
     # map kinds without an asynchronous path are built synchronously by the same call
     km = sp.build_kmap(coords_dev(c), 3, 2, asynchronous=True)
     np.testing.assert_array_equal(km.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)
+
+
+def test_caller_allocator_backs_every_device_allocation(sp):
+    """spconv_set_allocator: with PyTorch's caching allocator installed, builds, plans and
+    kernels run out of its blocks, results do not change, and every block comes back."""
+    import torch
+    from _util import TOL, make_layer, norm_err
+    c = gen.lidar_scene(91, target_n=3000)
+    ref = oc.build_kmap(c, 3, 2)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, 27, "f16", 92)
+    live, calls = {}, [0, 0]
+
+    def alloc(n):
+        t = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
+        live[t.data_ptr()] = t
+        calls[0] += 1
+        return t.data_ptr()
+
+    def free(ptr):
+        calls[1] += 1
+        live.pop(ptr)
+
+    sp.set_allocator(alloc, free)
+    try:
+        km = sp.build_kmap(coords_dev(c), 3, 2)
+        np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+        cfg = sp.Config()
+        cfg.n_split, cfg.kernel = 2, 2                     # sorted plan and split partial sums
+        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+        assert norm_err(sp.dgrad(g, w, km), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+        assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+        assert calls[0] > 5 and live
+        torch.cuda.synchronize()
+        km.destroy()
+        assert not live and calls[0] == calls[1]
+    finally:
+        sp.set_allocator(None, None)
+    km = sp.build_kmap(coords_dev(c), 3, 2)                # the library's own pool serves again
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)

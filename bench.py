@@ -136,6 +136,10 @@ def main():
     t_fwd_e2e_cfg = _events(lambda: sp.fwd(x, w, km, cfg_f, out=y), R, torch)
     t_dgrad = _events(lambda: sp.dgrad(g, w, km, cfg_d, out=dx), R, torch)
     t_wgrad = _events(lambda: sp.wgrad(x, g, km, cfg_w, out=dw), R, torch)
+    # the second dataflow of the design space on the same layer (pair lists, atomic scatter)
+    cfg_fod = sp.Config()
+    cfg_fod.kernel, cfg_fod.tile_m = 3, 64
+    t_fod = _events(lambda: sp.fwd(x, w, km, cfg_fod, out=y), R, torch)
 
     def mapping_ms(op, cfg):
         torch.cuda.synchronize()
@@ -191,6 +195,9 @@ def main():
         # forward with its mapping (sort, reorder, tile masks) spread over L layers that share the kmap
         "fwd_ms_with_mapping": {"sorted_cfg_L1": round(t_fwd + map_f, 4), "sorted_cfg_L4": round(t_fwd + map_f / 4, 4),
                                 "unsorted_cfg": round(t_fwd_e2e_cfg, 4)},
+        # forward kernels only, per dataflow (Section 2.2): implicit GEMM in the step's configuration
+        # against fetch-on-demand (zero-fill + pair-list kernel with atomic adds + rounding pass)
+        "fwd_ms_by_dataflow": {"implicit_gemm": round(t_fwd_e2e_cfg, 4), "fetch_on_demand": round(t_fod, 4)},
         "fwd_effective_tflops": round(fwd_tflops, 2),
         "dgrad_effective_tflops": round(flops_one / (t_dgrad * 1e-3) / 1e12, 2),
         "wgrad_effective_tflops": round(flops_one / (t_wgrad * 1e-3) / 1e12, 2),

@@ -138,6 +138,16 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
 SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, int stride, int transposed,
                                        void* stream, spconv_kmap** out);
 
+/* The kmap of the transposed convolution that pairs with km: the same (input, output) pairs with
+ * the two roles exchanged, i.e. exactly what spconv_build_kmap returns for the same rows with
+ * `transposed` flipped, without building a table or probing again (one scatter pass over km's
+ * map plus copies).  An encoder-decoder network derives each up-convolution's kmap from its
+ * down-convolution this way.  *out is independent of km (own buffers; destroy both).  `stream`
+ * must be ordered after the work that built km; an unresolved asynchronous build is resolved
+ * first (one synchronisation) and its error, if any, is returned.  Errors: EINVAL, ENOMEM,
+ * EHIP, ERANGE / EDUP of a pending build; on error *out is NULL. */
+SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out);
+
 /* Resolves an asynchronous build: synchronises `stream`, returns SPCONV_OK, SPCONV_ERANGE or
  * SPCONV_EDUP, and makes the pair count available.  SPCONV_OK at once for other kmaps. */
 SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream);

@@ -61,6 +61,7 @@ def load_library():
         "spconv_build_kmap": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
         "spconv_build_kmap_async": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
         "spconv_kmap_status": (i32, [vp, vp]),
+        "spconv_kmap_transpose": (i32, [vp, vp, C.POINTER(vp)]),
         "spconv_kmap_sizes": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]),
         "spconv_kmap_out_coords": (i32, [vp, vp, vp]),
         "spconv_kmap_in_coords": (i32, [vp, vp, vp]),
@@ -163,6 +164,12 @@ class KMap:
     def status(self, stream=None):
         """spconv_kmap_status: raises on a range / duplicate error of an asynchronous build."""
         _check(load_library().spconv_kmap_status(self.handle, _stream(stream)), "spconv_kmap_status")
+
+    def transpose(self, stream=None) -> "KMap":
+        """spconv_kmap_transpose: the kmap of the paired transposed convolution, derived from this one."""
+        h = C.c_void_p()
+        _check(load_library().spconv_kmap_transpose(self.handle, _stream(stream), C.byref(h)), "spconv_kmap_transpose")
+        return KMap(h, self.K)
 
     def n_pairs(self) -> int:
         v = C.c_int64()

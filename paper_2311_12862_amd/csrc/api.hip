@@ -259,6 +259,15 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
   return kmap_build(coords, N, K, stride, transposed, true, (hipStream_t)stream, out);
 }
 
+SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out) {
+  StreamScope scope((hipStream_t)stream);
+  if (!out) return SPCONV_EINVAL;
+  *out = nullptr;
+  if (!km) return SPCONV_EINVAL;
+  km->last_stream = (hipStream_t)stream;
+  return kmap_transpose(km, (hipStream_t)stream, out);
+}
+
 SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream) {
   StreamScope scope((hipStream_t)stream);
   if (!km) return SPCONV_EINVAL;

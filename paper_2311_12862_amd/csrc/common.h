@@ -137,6 +137,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
 int kmap_status(spconv_kmap* km, hipStream_t st);  // resolves a pending asynchronous build (synchronises)
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);
+int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out);
 
 // ---- sort.hip
 // Stable LSD radix sort of n (key, value) pairs on key bits [0, key_bits).

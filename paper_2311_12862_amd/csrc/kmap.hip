@@ -935,6 +935,58 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
   return SPCONV_OK;
 }
 
+// The kmap of the transposed convolution that pairs with src: the same pairs with inputs and
+// outputs exchanged.  Its output-stationary table is src's input-side table and the other way
+// round, so no table is built and nothing is probed: one scatter pass (unless src has its input
+// side already) and device-to-device copies.
+int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out) {
+  if (src->pending) SPC_TRY(kmap_status(src, st));  // a failed build has no transpose
+  SPC_TRY(kmap_build_in_side(src, st));
+  std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
+  if (!km) return SPCONV_ENOMEM;
+  km->K = src->K;
+  km->V = src->V;
+  km->stride = src->stride;
+  km->transposed = src->transposed ? 0 : 1;
+  km->n_in = src->n_out;
+  km->n_out = src->n_in;
+  km->n_pairs = src->n_pairs;
+  km->build_stream = st;
+  km->last_stream = st;
+  const int V = km->V;
+  auto copy_side = [&](SideMap& dst, const SideMap& from) -> int {
+    dst.rows = from.rows;
+    dst.rows_pad = from.rows_pad;
+    const size_t map_bytes = (size_t)from.rows_pad * V * sizeof(int), mask_bytes = (size_t)from.rows_pad * sizeof(unsigned);
+    SPC_TRY(dst.map.alloc(map_bytes));
+    SPC_TRY(dst.mask.alloc(mask_bytes));
+    SPC_HIP(hipMemcpyAsync(dst.map.p, from.map.p, map_bytes, hipMemcpyDeviceToDevice, st));
+    SPC_HIP(hipMemcpyAsync(dst.mask.p, from.mask.p, mask_bytes, hipMemcpyDeviceToDevice, st));
+    dst.ready = true;
+    return SPCONV_OK;
+  };
+  SPC_TRY(copy_side(km->out_side, src->in_side));
+  SPC_TRY(copy_side(km->in_side, src->out_side));
+  auto copy_rows = [&](DevBuf& dst, const DevBuf& from, int64_t rows) -> int {
+    if (rows == 0 || !from.p) return dst.alloc(16);
+    SPC_TRY(dst.alloc((size_t)rows * 16));
+    SPC_HIP(hipMemcpyAsync(dst.p, from.p, (size_t)rows * 16, hipMemcpyDeviceToDevice, st));
+    return SPCONV_OK;
+  };
+  // A kmap keeps the caller's rows and, for stride > 1, the coarse set; with stride 1 the two
+  // sets are one and only the caller's rows are kept (in_coords of a forward kmap, out_coords
+  // of a transposed one).
+  if (!src->transposed) {
+    SPC_TRY(copy_rows(km->out_coords, src->in_coords, src->n_in));
+    if (src->stride > 1) SPC_TRY(copy_rows(km->in_coords, src->out_coords, src->n_out));
+  } else {
+    SPC_TRY(copy_rows(km->in_coords, src->out_coords, src->n_out));
+    if (src->stride > 1) SPC_TRY(copy_rows(km->out_coords, src->in_coords, src->n_in));
+  }
+  *out = km.release();
+  return SPCONV_OK;
+}
+
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
   if (km->pending && !per_k) return kmap_status(km, st) == SPCONV_EHIP ? SPCONV_EHIP : SPCONV_OK;
   unsigned long long h[32] = {0};

@@ -212,3 +212,51 @@ def test_caller_allocator_backs_every_device_allocation(sp):
         sp.set_allocator(None, None)
     km = sp.build_kmap(coords_dev(c), 3, 2)                # the library's own pool serves again
     np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+
+
+@pytest.mark.parametrize("K,stride", [(3, 2), (2, 2), (3, 1), (3, 3), (1, 1)])
+def test_transpose_equals_transposed_build(sp, K, stride):
+    """spconv_kmap_transpose: the paired transposed convolution's kmap, derived without a rebuild,
+    is bit for bit what a build with `transposed` flipped returns (and what the oracle defines)."""
+    from _util import TOL, make_layer, norm_err
+    c = gen.lidar_scene(93, target_n=2600)
+    ref = oc.build_kmap(c, K, stride, False)
+    ref_t = oc.build_kmap(c, K, stride, True)
+    km = sp.build_kmap(coords_dev(c), K, stride)
+    kt = km.transpose()
+    assert (kt.n_in, kt.n_out) == (ref_t.n_in, ref_t.n_out) == (km.n_out, km.n_in)
+    assert kt.n_pairs() == km.n_pairs() == int((ref.M >= 0).sum())
+    np.testing.assert_array_equal(kt.export().cpu().numpy(), ref_t.M)
+    direct = sp.build_kmap(coords_dev(c), K, stride, transposed=True)
+    np.testing.assert_array_equal(kt.export_mask().cpu().numpy(), direct.export_mask().cpu().numpy())
+    np.testing.assert_array_equal(kt.out_coords().cpu().numpy(), direct.out_coords().cpu().numpy())
+    np.testing.assert_array_equal(kt.in_coords().cpu().numpy(), direct.in_coords().cpu().numpy())
+    # the derived kmap runs every operator, under sorted plans as well
+    (x32, x), (w32, w), (g32, g) = make_layer(ref_t.n_in, ref_t.n_out, 32, 16, K ** 3, "f16", 94)
+    cfg = sp.Config()
+    cfg.n_split = 1
+    assert norm_err(sp.fwd(x, w, kt, cfg), oc.forward(x32, w32, ref_t.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, kt, cfg), oc.dgrad(g32, w32, ref_t.M, ref_t.n_in)) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, kt), oc.wgrad(x32, g32, ref_t.M)) <= 1e-4
+    # and transposing twice gives the original structure back (also from a transposed build)
+    np.testing.assert_array_equal(kt.transpose().export().cpu().numpy(), ref.M)
+    back = direct.transpose()
+    np.testing.assert_array_equal(back.export().cpu().numpy(), ref.M)
+    np.testing.assert_array_equal(back.out_coords().cpu().numpy(), km.out_coords().cpu().numpy())
+    np.testing.assert_array_equal(back.in_coords().cpu().numpy(), km.in_coords().cpu().numpy())
+
+
+def test_transpose_of_empty_and_pending_builds(sp):
+    import torch
+    empty = sp.build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 2)
+    t = empty.transpose()
+    assert (t.n_in, t.n_out) == (0, 0)
+    c = gen.lidar_scene(95, target_n=1500)
+    ref_t = oc.build_kmap(c, 3, 1, True)
+    km = sp.build_kmap(coords_dev(c), 3, 1, asynchronous=True)
+    np.testing.assert_array_equal(km.transpose().export().cpu().numpy(), ref_t.M)   # resolves the build first
+    dup = np.vstack([c, c[:1]])
+    bad = sp.build_kmap(coords_dev(dup), 3, 1, asynchronous=True)
+    with pytest.raises(sp.SpconvError) as e:
+        bad.transpose()
+    assert e.value.status == -3          # SPCONV_EDUP

@@ -52,7 +52,7 @@ class GpuBackend:
             if l < 4:
                 self.one.append(sp.build_kmap(lvl, 1, 1))
                 self.down.append(sp.build_kmap(lvl, 3, 2))
-                self.up.append(sp.build_kmap(lvl, 3, 2, transposed=True))
+                self.up.append(self.down[-1].transpose())   # the up-convolution pairs with this down-convolution
                 lvl = self.down[-1].out_coords()
 
     def conv(self, x, name, km):

@@ -381,14 +381,17 @@ SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, SPCONV_F16, &c));
+  if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));
+  *effective = km->n_pairs;
+  if (c.kernel == 3) {  // fetch-on-demand walks the pair lists: nothing but valid pairs is multiplied
+    *executed = km->n_pairs;
+    return SPCONV_OK;
+  }
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
   SPC_TRY(plan_get(km, *os.side, c.n_split, c.tile_m, st, &plan));
-  SPC_TRY(plan_mac_units(km, *os.side, plan, 16, st, executed));
-  if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));
-  *effective = km->n_pairs;
-  return SPCONV_OK;
+  return plan_mac_units(km, *os.side, plan, 16, st, executed);
 }
 
 SPCONV_API void spconv_kmap_destroy(spconv_kmap* km) {
@@ -443,9 +446,16 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
   SPC_HIP(hipMemsetAsync(x.p, 0, x.bytes, st));  // zeros are valid numbers in every dtype
   SPC_HIP(hipMemsetAsync(y.p, 0, y.bytes, st));
   SPC_HIP(hipMemsetAsync(w.p, 0, w.bytes, st));
-  hipEvent_t e0, e1;
-  SPC_HIP(hipEventCreate(&e0));
-  SPC_HIP(hipEventCreate(&e1));
+  struct Events {  // destroyed on every way out
+    hipEvent_t a = nullptr, b = nullptr;
+    ~Events() {
+      if (a) (void)hipEventDestroy(a);
+      if (b) (void)hipEventDestroy(b);
+    }
+  } ev;
+  SPC_HIP(hipEventCreate(&ev.a));
+  SPC_HIP(hipEventCreate(&ev.b));
+  const hipEvent_t e0 = ev.a, e1 = ev.b;
 
   std::vector<spconv_config> cands;
   if (op == SPCONV_OP_WGRAD) {
@@ -534,8 +544,6 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
       *best = c;
     }
   }
-  (void)hipEventDestroy(e0);
-  (void)hipEventDestroy(e1);
   if (status == SPCONV_OK && best_us) *best_us = best_t * 1000.f;
   return status;
 }

@@ -110,6 +110,14 @@ def test_empty_and_single_point(sp):
     assert norm_err(sp.fwd(x, w, km, _cfg(sp)), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
 
 
+def test_executes_only_valid_pairs(sp, cloud):
+    """Zero redundant computation (Section 2.2.2): executed MAC units == valid pairs."""
+    c, ref = cloud
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    ex, eff = km.mac_units(sp.OP_FWD, _cfg(sp))
+    assert ex == eff == int((ref.M >= 0).sum())
+
+
 def test_rejected_configurations(sp, cloud):
     c, ref = cloud
     km = sp.build_kmap(coords_dev(c), 3, 1)

@@ -309,3 +309,36 @@ def test_even_kernel_layers(sp, transposed):
     assert norm_err(sp.fwd(x, w, km, f[0]), want_f) <= TOL["f16"]
     assert norm_err(sp.dgrad(g, w, km, d[0]), want_d) <= TOL["f16"]
     assert norm_err(sp.wgrad(x, g, km, wg[0]), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+
+
+def test_layer_replays_in_a_hip_graph(sp, cloud):
+    """Once plans and scratch exist, fwd / dgrad / wgrad only launch kernels (buffers are cleared by
+    fill kernels, never by memset nodes), so a layer can be captured and replayed; every replay,
+    with eager work in between, must equal the eager result on the inputs of that moment."""
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 91)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    fod = _cfg(sp, kernel=3)
+    cfgs = [_cfg(sp, 0), _cfg(sp, 2, 64, kernel=2), fod]
+    outs = [sp.fwd(x, w, km, cf) for cf in cfgs]          # warm-up: plans, scratch, kernel attributes
+    dx, dw = sp.dgrad(g, w, km), sp.wgrad(x, g, km)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for cf, o in zip(cfgs, outs):
+            sp.fwd(x, w, km, cf, out=o)
+        sp.dgrad(g, w, km, out=dx)
+        sp.wgrad(x, g, km, out=dw)
+    for rep in range(3):
+        x.copy_((torch.randn_like(x, dtype=torch.float32) * 0.5).half())      # eager work between replays
+        g.copy_((torch.randn_like(g, dtype=torch.float32) * 0.5).half())
+        for o in outs + [dx, dw]:
+            o.fill_(7.0)
+        graph.replay()
+        torch.cuda.synchronize()
+        want = sp.fwd(x, w, km, cfgs[0])
+        assert torch.equal(outs[0], want), rep
+        assert torch.equal(outs[1], sp.fwd(x, w, km, cfgs[1])), rep
+        assert norm_err(outs[2], want.double().cpu().numpy()) <= TOL["f16"], rep   # atomics: order varies
+        assert torch.equal(dx, sp.dgrad(g, w, km)), rep
+        assert torch.equal(dw, sp.wgrad(x, g, km)), rep

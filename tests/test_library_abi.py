@@ -30,7 +30,7 @@ def test_library_exports_every_declared_symbol():
 
 def test_python_binding_mirrors_the_c_names():
     import paper_2311_12862_amd as sp
-    for name in ("build_kmap", "fwd", "dgrad", "wgrad", "tune"):
+    for name in ("build_kmap", "fwd", "dgrad", "wgrad", "tune", "tune_group", "set_allocator", "ew", "copy_cols"):
         assert callable(getattr(sp, name))
 
 
@@ -43,3 +43,21 @@ def test_argument_errors_need_no_gpu():
     assert lib.spconv_build_kmap(None, 0, 2, 1, 0, None, ctypes.byref(out)) == -1
     assert lib.spconv_kmap_sizes(None, None, None, None) == -1
     assert lib.spconv_fwd(None, None, None, 64, 64, 1, None, None, None) == -1
+    for K, stride, transposed in ((4, 1, 0), (5, 1, 0), (3, 0, 0), (3, 65, 0), (3, 1, 2), (2, 1, 0), (2, 3, 0)):
+        assert lib.spconv_build_kmap(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1, (K, stride)
+        assert lib.spconv_build_kmap_async(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1
+    assert lib.spconv_build_kmap(None, 0, 3, 1, 0, None, None) == -1
+    assert lib.spconv_kmap_transpose(None, None, ctypes.byref(out)) == -1 and out.value is None
+    assert lib.spconv_kmap_transpose(None, None, None) == -1
+    assert lib.spconv_kmap_status(None, None) == -1
+    assert lib.spconv_dgrad(None, None, None, 64, 64, 1, None, None, None) == -1
+    assert lib.spconv_wgrad(None, None, None, 64, 64, 1, None, None, None) == -1
+    assert lib.spconv_tune(None, 64, 64, 1, 0, 1, None, None, None) == -1
+    assert lib.spconv_tune_group(None, None, 0, 1, 0, 1, None, None, None, None, None) == -1
+    assert lib.spconv_ew(9, None, None, None, 4, 1, None) == -1
+    assert lib.spconv_ew(0, None, None, None, 0, 1, None) == 0          # nothing to do
+    assert lib.spconv_copy_cols(None, 8, 4, None, 8, 0, 8, 4, 1, None) == -1   # columns past the row
+    alloc = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)(lambda n, u: None)
+    assert lib.spconv_set_allocator(ctypes.cast(alloc, ctypes.c_void_p), None, None) == -1   # both or neither
+    assert lib.spconv_set_allocator(None, None, None) == 0
+    lib.spconv_kmap_destroy(None)                                        # a no-op

@@ -48,6 +48,71 @@ def _events(fn, reps, torch):
     return e0.elapsed_time(e1) / reps
 
 
+# Other single-layer workloads (parity-test configurations; not the headline line):
+# name -> (generator, dtype, C_in, C_out, stride, transposed)
+LAYER_WORKLOADS = {
+    "stride2_64x128": ("lidar_batch2", "f16", 64, 128, 2, False),
+    "transposed2_128x64": ("lidar_batch2", "f16", 128, 64, 2, True),
+    "room_c32": ("room", "bf16", 32, 32, 1, False),
+    "room_c96": ("room", "bf16", 96, 96, 1, False),
+    "room_c256": ("room", "bf16", 256, 256, 1, False),
+    "detection_c64": ("detection", "f16", 64, 64, 1, False),
+}
+
+
+def layer_report(name, reps):
+    """One JSON line for one of LAYER_WORKLOADS: kmap build and the three kernels under the tuner's
+    kernel-only choice (mapping amortised over many layers), plus forward in the other dataflow."""
+    import numpy as np
+    import torch
+    import paper_2311_12862_amd as sp
+    from workloads import generators as gen
+
+    source, dt, c_in, c_out, stride, transposed = LAYER_WORKLOADS[name]
+    coords_h = {"lidar_batch2": lambda: gen.lidar_batch(3000, 2), "room": lambda: gen.room_scene(4000),
+                "detection": lambda: gen.detection_scene(6000)}[source]()
+    tdt = {"f16": torch.float16, "bf16": torch.bfloat16}[dt]
+
+    def dev(raw):
+        t = torch.from_numpy(raw.view(np.int16).copy() if dt == "bf16" else raw).cuda()
+        return t.view(torch.bfloat16) if dt == "bf16" else t
+
+    coords = torch.from_numpy(coords_h).cuda()
+    built = []
+
+    def build_only():
+        built.append(sp.build_kmap(coords, 3, stride, transposed))
+        if len(built) > 2:
+            built.pop(0).destroy()
+    torch.cuda.synchronize()
+    build_only()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(10):
+        build_only()
+    torch.cuda.synchronize()
+    build_ms = (time.perf_counter() - t0) * 1e3 / 10
+    km = built[-1]
+    pairs = km.n_pairs()
+    x = dev(gen.features(km.n_in, c_in, dt, 1)[1])
+    w = dev(gen.weights(27, c_in, c_out, dt, 2)[1])
+    g = dev(gen.features(km.n_out, c_out, dt, 3)[1])
+    flops = 2.0 * pairs * c_in * c_out
+    out = {"workload": name, "dtype": dt, "n_in": int(km.n_in), "n_out": int(km.n_out), "pairs": int(pairs),
+           "c_in": c_in, "c_out": c_out, "stride": stride, "transposed": bool(transposed),
+           "kmap_build_ms": round(build_ms, 4)}
+    for op, label, run in ((sp.OP_FWD, "fwd", lambda c: sp.fwd(x, w, km, c)),
+                           (sp.OP_DGRAD, "dgrad", lambda c: sp.dgrad(g, w, km, c)),
+                           (sp.OP_WGRAD, "wgrad", lambda c: sp.wgrad(x, g, km, c))):
+        cfg, _ = sp.tune(km, c_in, c_out, tdt, op, 1000)
+        ms = _events(lambda: run(cfg), reps, torch)
+        out[label] = {"ms": round(ms, 4), "effective_tflops": round(flops / (ms * 1e-3) / 1e12, 1), "cfg": repr(cfg)}
+    fod = sp.Config()
+    fod.kernel, fod.tile_m = 3, 64
+    out["fwd_fetch_on_demand_ms"] = round(_events(lambda: sp.fwd(x, w, km, fod), reps, torch), 4)
+    print(json.dumps(out))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -57,9 +122,17 @@ def main():
     ap.add_argument("--kernel-reps", type=int, default=50)
     ap.add_argument("--calibration-copy", action="store_true",
                     help="end with three 256 MiB device-to-device copies (known traffic for counter calibration)")
+    ap.add_argument("--workload", default="lidar100k", choices=["lidar100k"] + sorted(LAYER_WORKLOADS),
+                    help="lidar100k (default): the headline step; the others print a per-layer report instead")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU; --gpus must be 1 (no multi-GPU path exists)")
+    if args.workload != "lidar100k":
+        import torch
+        if not torch.cuda.is_available():
+            sys.exit("bench.py needs a GPU")
+        torch.cuda.set_device(0)
+        return layer_report(args.workload, args.kernel_reps)
 
     import numpy as np
     import torch

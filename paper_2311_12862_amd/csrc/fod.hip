@@ -70,7 +70,8 @@ __device__ __forceinline__ int2 buf_load8(__amdgpu_buffer_rsrc_t r, unsigned byt
 }
 
 template <int BM, int BN, int KC> struct FodSmem {
-  static constexpr int LDA = KC + 8;   // gathered rows and input-gradient weight rows: reduction index contiguous
+  static constexpr int LDA = KC + 16;  // rows with the reduction index contiguous; a pitch of 32 B mod 64 B keeps the
+                                       // 16-byte fragment reads of 8 rows x 2 column groups (one LDS pass) on distinct banks
   static constexpr int LDB = BN + 16;  // forward weight rows: output channel contiguous; pitch = 8 words mod 32
   static constexpr size_t a_bytes = (size_t)BM * LDA * 2;
   static constexpr size_t b_fwd = (size_t)KC * LDB * 2, b_dgrad = (size_t)BN * LDA * 2;

@@ -72,22 +72,34 @@ __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned b
 
 // LDS plan of the tiled kernel.  One stage of operands (the next stage waits in registers):
 // more workgroups fit on a CU, and they hide each other's load latency.
-template <int BM, int BN, int KC> struct IgemmSmem {
-  static constexpr int LDA = KC + 8;   // A rows and dgrad weight rows: reduction index contiguous, +16 B pad
+// Pitches (in 2-byte elements) of the rows whose reduction index is contiguous (gathered rows, and
+// the weight rows of the input gradient).  Measured on gfx950: one pass of a 16-byte LDS read
+// serves 8 rows x 2 column groups, so a pitch of 32 B mod 64 B (KC + 16 elements) is free of bank
+// conflicts (19 clk per wave instruction with four waves reading) while KC + 8 costs two passes
+// (32 clk).  The wider pitch is used unless it would cost a resident workgroup per CU.
+template <int BM, int BN, int KC, bool DGRAD> struct IgemmSmem {
   static constexpr int LDB = BN + 16;  // forward weight rows: output channel contiguous; pitch = 8 words mod 32
-  static constexpr size_t a_bytes = (size_t)BM * LDA * 2;
-  static constexpr size_t b_fwd = (size_t)KC * LDB * 2, b_dgrad = (size_t)BN * LDA * 2;
-  static constexpr size_t b_bytes = b_fwd > b_dgrad ? b_fwd : b_dgrad;
   static constexpr size_t map_bytes = (size_t)BM * 27 * 4;
   static constexpr size_t perm_bytes = (size_t)BM * 4;
+  static constexpr size_t kLdsPerCu = 160 * 1024;
+  static constexpr size_t total_with(int lda, int ldbd) {
+    return (size_t)BM * lda * 2 + (DGRAD ? (size_t)BN * ldbd * 2 : (size_t)KC * LDB * 2) + map_bytes + perm_bytes;
+  }
+  static constexpr size_t fit(int lda, int ldbd) { return kLdsPerCu / total_with(lda, ldbd); }
+  static constexpr int LDA = fit(KC + 16, KC + 8) == fit(KC + 8, KC + 8) ? KC + 16 : KC + 8;
+  static constexpr int LDBD = fit(LDA, KC + 16) == fit(LDA, KC + 8) ? KC + 16 : KC + 8;
+  static constexpr size_t a_bytes = (size_t)BM * LDA * 2;
+  static constexpr size_t b_bytes = DGRAD ? (size_t)BN * LDBD * 2 : (size_t)KC * LDB * 2;
   static constexpr size_t total = a_bytes + b_bytes + map_bytes + perm_bytes;
 };
 
-template <typename T, int BM, int BN, int KC, int NW>
+// DGRAD is a template parameter: as a run-time flag the compiler issued the LDS reads of both
+// operand layouts and awaited the unused ones.
+template <typename T, int BM, int BN, int KC, int NW, bool DGRAD>
 __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
-  typedef IgemmSmem<BM, BN, KC> S;
+  typedef IgemmSmem<BM, BN, KC, DGRAD> S;
   typedef typename Mfma<T>::vec vec8;
-  constexpr int LDA = S::LDA, LDB = S::LDB;
+  constexpr int LDA = S::LDA, LDB = S::LDB, LDBD = S::LDBD;
   // the NW (4 or 8) waves tile the workgroup's BM x BN outputs (NW/2) x 2
   constexpr int NT = NW * 64;        // threads
   constexpr int WM = BM / (NW / 2);  // rows per wave
@@ -189,7 +201,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
     }
     const int k = lo + c;
     const unsigned wk = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice_bytes;
-    if (!p.dgrad) {  // rows of W[k]: reduction channel ci, 8 output channels per load
+    if constexpr (!DGRAD) {  // rows of W[k]: reduction channel ci, 8 output channels per load
       const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
@@ -213,7 +225,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps)
       *reinterpret_cast<uint4*>(As + (a_row + ps * A_RPP) * LDA + a_seg * 8) = ra[ps];
-    if (!p.dgrad) {  // forward: stored as loaded, [ci][co]; the transposing LDS read does the rest
+    if constexpr (!DGRAD) {  // forward: stored as loaded, [ci][co]; the transposing LDS read does the rest
       const int nseg = tid % (BN / 8), kk0 = tid / (BN / 8);
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
@@ -224,7 +236,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 #pragma unroll
       for (int ps = 0; ps < B_PASSES; ++ps) {
         const int n = a_row + ps * A_RPP;
-        if (n < BN) *reinterpret_cast<uint4*>(Bs + n * LDA + a_seg * 8) = rb[ps];
+        if (n < BN) *reinterpret_cast<uint4*>(Bs + n * LDBD + a_seg * 8) = rb[ps];
       }
     }
   };
@@ -236,7 +248,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 #pragma unroll
     for (int ks = 0; ks < KC / 32; ++ks) {
       vec8 bf[NB];
-      if (!p.dgrad) {
+      if constexpr (!DGRAD) {
         // 16 lanes fetch a 4 x 16 block of [ci][co] and each receives one column: 4 reduction
         // steps of its output channel; two reads give the lane's 8 steps (ci = 8*fg .. 8*fg+7)
         const unsigned short* b = Bs + (ks * 32 + 8 * fg + (fa >> 2)) * LDB + wave_n * WN + 4 * (fa & 3);
@@ -251,16 +263,21 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
           bf[nb] = __builtin_bit_cast(vec8, v);
         }
       } else {
-        const unsigned short* b = Bs + (wave_n * WN + fa) * LDA + fg * 8;
+        const unsigned short* b = Bs + (wave_n * WN + fa) * LDBD + fg * 8;
 #pragma unroll
-        for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDA + ks * 32);
+        for (int nb = 0; nb < NB; ++nb) bf[nb] = *reinterpret_cast<const vec8*>(b + nb * 16 * LDBD + ks * 32);
       }
+      // every fragment read of the step is issued before the first MFMA waits for one (a read
+      // inside the per-block branch would be awaited right where it is issued); only the
+      // MFMAs of a block without this offset are skipped
+      vec8 af[MB];
+#pragma unroll
+      for (int mb = 0; mb < MB; ++mb) af[mb] = *reinterpret_cast<const vec8*>(a + mb * 16 * LDA + ks * 32);
 #pragma unroll
       for (int mb = 0; mb < MB; ++mb) {
         if ((blk_mask[mb] >> c) & 1u) {
-          const vec8 af = *reinterpret_cast<const vec8*>(a + mb * 16 * LDA + ks * 32);
 #pragma unroll
-          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = Mfma<T>::run(af, bf[nb], acc[mb][nb]);
+          for (int nb = 0; nb < NB; ++nb) acc[mb][nb] = Mfma<T>::run(af[mb], bf[nb], acc[mb][nb]);
         }
       }
     }
@@ -447,16 +464,23 @@ __global__ void __launch_bounds__(256) k_split_reduce(const float* __restrict__ 
 
 template <typename T, int BM, int BN, int KC, int NW>
 int launch_igemm(const IgemmParams& p, dim3 grid, hipStream_t st) {
-  typedef IgemmSmem<BM, BN, KC> S;
+  typedef IgemmSmem<BM, BN, KC, false> SF;
+  typedef IgemmSmem<BM, BN, KC, true> SD;
   static_assert(BM * (KC / 8) >= NW * 64, "every thread stages at least one segment of the gathered rows");
   static bool attr_set = false;
-  auto fn = k_igemm<T, BM, BN, KC, NW>;
+  auto fwd = k_igemm<T, BM, BN, KC, NW, false>;
+  auto dgr = k_igemm<T, BM, BN, KC, NW, true>;
   if (!attr_set) {
-    SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)S::total));
+    SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fwd), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)SF::total));
+    SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(dgr), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                (int)SD::total));
     attr_set = true;
   }
-  hipLaunchKernelGGL(fn, grid, dim3(NW * 64), S::total, st, p);
+  if (p.dgrad)
+    hipLaunchKernelGGL(dgr, grid, dim3(NW * 64), SD::total, st, p);
+  else
+    hipLaunchKernelGGL(fwd, grid, dim3(NW * 64), SF::total, st, p);
   SPC_LAUNCH_CHECK();
   return SPCONV_OK;
 }

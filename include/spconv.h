@@ -148,8 +148,11 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
  * EHIP, ERANGE / EDUP of a pending build; on error *out is NULL. */
 SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out);
 
-/* Resolves an asynchronous build: synchronises `stream`, returns SPCONV_OK, SPCONV_ERANGE or
- * SPCONV_EDUP, and makes the pair count available.  SPCONV_OK at once for other kmaps. */
+/* Resolves an asynchronous build: waits until the build's last kernel has published its result
+ * (a word in pinned host memory that the host reads: nothing is recorded on the stream, and no
+ * wait at all once that kernel has finished), returns SPCONV_OK, SPCONV_ERANGE or SPCONV_EDUP, and
+ * makes the pair count available.  SPCONV_OK at once for other kmaps.  `stream` is unused for
+ * kmaps built asynchronously (the build's own stream is waited for if the result is late). */
 SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream);
 
 /* Row counts of the two sides of the map and the number of present pairs

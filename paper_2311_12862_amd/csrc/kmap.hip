@@ -10,6 +10,9 @@
 // bitmask assembled from a wave ballot.
 #include "common.h"
 
+#include <chrono>
+#include <thread>
+
 #include <algorithm>
 #include <mutex>
 #include <new>
@@ -37,9 +40,12 @@ struct Ctl {
 
 // What a submanifold build hands to the host: written by the probe straight into pinned host
 // memory, so that no copy has to be enqueued behind the build.
+// What an asynchronous build leaves in pinned host memory, in one 8-byte word so that one store
+// publishes it: bit 63 = written, bits 48..55 = error flags, bits 0..47 = pair count.
 struct HostResult {
-  unsigned long long flags, pairs;
+  unsigned long long word;
 };
+constexpr unsigned long long kHostReady = 1ull << 63;
 
 __device__ __forceinline__ bool coord_ok(int b, int x, int y, int z) {
   return (unsigned)b <= 65534u && (unsigned)(x + 32768) <= 65535u && (unsigned)(y + 32768) <= 65535u &&
@@ -411,10 +417,8 @@ __global__ void __launch_bounds__(256)
   if (is_last && threadIdx.x < 64) {
     unsigned long long v = atomicAdd(&ctl->pairs[threadIdx.x * 16], 0ull);  // kPairSlots == 64 lanes
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
-    if (threadIdx.x == 0) {
-      host->pairs = v;
-      host->flags = ctl->flags;
-    }
+    if (threadIdx.x == 0)
+      host->word = kHostReady | ((unsigned long long)(ctl->flags & 0xFFu) << 48) | (v & 0xFFFFFFFFFFFFull);
   }
 }
 
@@ -556,10 +560,11 @@ int alloc_side(SideMap& side, int64_t rows, int V, hipStream_t st, bool preset_a
   return SPCONV_OK;
 }
 
-// Pool of pinned control blocks, each with the event that marks the end of its copy.
+// Pool of pinned control blocks.  The probe's last workgroup stores the result word; the host finds
+// out by reading the word, so nothing is recorded on the stream behind the probe (an event there
+// delayed the next kernel by 5.6 us).
 struct HostCtl {
   HostResult res;
-  hipEvent_t done;  // recorded behind the probe, whose last workgroup writes res
   HostResult* dev;  // device-side address of res
 };
 
@@ -588,12 +593,18 @@ HostCtl* host_ctl_acquire() {
     return nullptr;
   }
   h->dev = &static_cast<HostCtl*>(dp)->res;
-  if (hipEventCreateWithFlags(&h->done, hipEventDisableTiming) != hipSuccess) {
-    (void)hipGetLastError();
-    (void)hipHostFree(p);
-    return nullptr;
-  }
   return h;
+}
+
+// Waits (briefly, yielding) for the result word of a block to be written.
+bool host_ctl_ready(const HostCtl* h, double max_seconds) {
+  const volatile unsigned long long* w = &h->res.word;
+  const auto t0 = std::chrono::steady_clock::now();
+  while (!(*w & kHostReady)) {
+    if (std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count() > max_seconds) return false;
+    std::this_thread::yield();
+  }
+  return true;
 }
 
 void host_ctl_release(HostCtl* h) {
@@ -634,7 +645,7 @@ int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream);
 namespace {
 
 // Submanifold 3x3x3 build: init, insert, symmetric probe (whose last workgroup publishes the result
-// to pinned host memory); an event marks the end.
+// to pinned host memory).
 int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async, hipStream_t st) {
   const int V = 27;
   DevBuf ctl_buf, tab, own_rows;
@@ -658,9 +669,10 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async,
   SPC_LAUNCH_CHECK();
   HostCtl* hc = host_ctl_acquire();
   if (!hc) return SPCONV_ENOMEM;
+  hc->res.word = 0;  // (pinned memory: visible to the kernel launched below)
   hipLaunchKernelGGL(k_probe_sym3, dim3(blocks_for(ceil_div(N, 4), 4)), dim3(256), 0, st, rows, (int)N,
                      tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl, hc->dev);
-  const bool ok = hipGetLastError() == hipSuccess && hipEventRecord(hc->done, st) == hipSuccess;
+  const bool ok = hipGetLastError() == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();
     (void)hipStreamSynchronize(st);
@@ -682,26 +694,37 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async,
 }  // namespace
 
 struct HostCtlHandle {
+  // the probe must have written the block before it is handed to another build
   static void finish(void* p) {
     HostCtl* hc = static_cast<HostCtl*>(p);
-    (void)hipEventSynchronize(hc->done);
+    if (!host_ctl_ready(hc, 0.05)) (void)hipDeviceSynchronize();
     host_ctl_release(hc);
   }
 };
 
-// wait_stream: wait for the whole stream (the synchronous build: everything on it is the build,
-// and a stream wait returns sooner than an event wait); otherwise only for the probe's event.
+// wait_stream: wait for the whole stream (the synchronous build: everything on it is the build);
+// otherwise only for the probe's result word.
 int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
   if (!km->pending) return SPCONV_OK;
   HostCtl* hc = static_cast<HostCtl*>(km->pending_host);
-  if (wait_stream)
+  if (wait_stream) {
     SPC_HIP(hipStreamSynchronize(st));
-  else
-    SPC_HIP(hipEventSynchronize(hc->done));
+  } else if (!host_ctl_ready(hc, 0.002)) {
+    // not there yet: wait for the stream the build runs on instead of spinning
+    SPC_HIP(hipStreamSynchronize(km->build_stream));
+  }
+  if (!host_ctl_ready(hc, 1.0)) {  // the probe never ran to its end
+    (void)hipDeviceSynchronize();
+    km->pending = false;
+    km->pending_host = nullptr;
+    host_ctl_release(hc);
+    return SPCONV_EHIP;
+  }
+  const unsigned long long word = hc->res.word;
   Ctl h{};
-  h.flags = hc->res.flags;
+  h.flags = (unsigned)((word >> 48) & 0xFFu);
   const int status = flags_status(h);
-  km->n_pairs = (int64_t)hc->res.pairs;
+  km->n_pairs = (int64_t)(word & 0xFFFFFFFFFFFFull);
   km->pending = false;
   km->pending_host = nullptr;
   host_ctl_release(hc);

@@ -138,11 +138,21 @@ __global__ void k_ctl_init(Ctl* ctl) {
   ctl->key_and[threadIdx.x * 16] = ~0ull;
 }
 
-// Insert key(p_j) -> j for every input row; flags range and duplicate errors.
+// Insert key(p_j) -> j for every input row; flags range and duplicate errors.  The kernel is a
+// chain of two memory round trips per thread on a grid that leaves most of the chip idle, so it also
+// presets the map and masks (map4 may be null): those stores ride along for free, and only the
+// probe, which runs next, needs them.
 __global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ coords, int n,
                                                      unsigned long long* tab, int log_cap, Ctl* ctl,
-                                                     int4* __restrict__ keep) {
+                                                     int4* __restrict__ keep, int4* __restrict__ map4,
+                                                     long long map_vec4, unsigned* __restrict__ mask,
+                                                     long long mask_n) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (map4) {
+    const long long stride = (long long)gridDim.x * blockDim.x;
+    for (long long i = j; i < map_vec4; i += stride) map4[i] = make_int4(-1, -1, -1, -1);
+    for (long long i = j; i < mask_n; i += stride) mask[i] = 0u;
+  }
   if (j >= n) return;
   const int4 c = coords[j];
   keep[j] = c;  // the kmap's own copy of the caller's rows
@@ -660,12 +670,13 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async,
   SPC_TRY(side.map.alloc((size_t)side.rows_pad * V * sizeof(int)));
   SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
   const long long slots = 1ll << lc, map_vec4 = side.rows_pad * V / 4;
-  const unsigned init_blocks = (unsigned)std::min<int64_t>(ceil_div(std::max<long long>(slots, map_vec4), 256), 4096);
+  const unsigned init_blocks = (unsigned)std::min<int64_t>(ceil_div(slots, 256), 4096);
   hipLaunchKernelGGL(k_build_init, dim3(init_blocks), dim3(256), 0, st, tab.as<ulonglong2>(), slots,
-                     side.map.as<int4>(), map_vec4, side.mask.as<unsigned>(), (long long)side.rows_pad, ctl);
+                     (int4*)nullptr, 0ll, (unsigned*)nullptr, 0ll, ctl);
   SPC_LAUNCH_CHECK();
   hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                     tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>());
+                     tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>(), side.map.as<int4>(), map_vec4,
+                     side.mask.as<unsigned>(), (long long)side.rows_pad);
   SPC_LAUNCH_CHECK();
   HostCtl* hc = host_ctl_acquire();
   if (!hc) return SPCONV_ENOMEM;
@@ -782,7 +793,8 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
     SPC_TRY(fill_u32(tab_fine.p, (int64_t)4 << lc_fine, 0xFFFFFFFFu, st));
     hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                       tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>());
+                       tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>(), (int4*)nullptr, 0ll,
+                       (unsigned*)nullptr, 0ll);
     SPC_LAUNCH_CHECK();
   }
 

@@ -14,7 +14,10 @@
  * of the offset on the matrix cores, accumulating in fp32 registers.  Output
  * rows can be visited in bitmask-sorted order and the loop over offsets can be
  * cut into several separately sorted splits whose partial sums are added by a
- * reduction kernel (Sections 2.2.3 and 4.1).
+ * reduction kernel (Sections 2.2.3 and 4.1).  Forward and input gradient can
+ * also run in the fetch-on-demand dataflow (Section 2.2.2: the weight-stationary
+ * pair lists of the map, atomic scatter; spconv_config.kernel = 3), and the
+ * tuners choose between the two.
  *
  * Conventions (the paper gives only the set Delta^3(K); these are fixed here):
  *   - a coordinate row is (b, x, y, z), int32; b is the batch index, never

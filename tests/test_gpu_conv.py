@@ -355,3 +355,38 @@ def test_layer_replays_in_a_hip_graph(sp, cloud):
         assert norm_err(outs[2], want.double().cpu().numpy()) <= TOL["f16"], rep   # atomics: order varies
         assert torch.equal(dx, sp.dgrad(g, w, km)), rep
         assert torch.equal(dw, sp.wgrad(x, g, km)), rep
+
+
+def test_two_kmaps_on_two_streams(sp):
+    """Different kmaps may be driven from different streams at the same time (each kmap keeps to
+    one stream); the library's block pool hands a freed block only to the stream that used it."""
+    clouds = [gen.lidar_scene(101 + i, target_n=2500 + 300 * i) for i in range(2)]
+    refs = [oc.build_kmap(c, 3, 1) for c in clouds]
+    layers = [make_layer(r.n_in, r.n_out, 32, 64, 27, "f16", 120 + i) for i, r in enumerate(refs)]
+    streams = [torch.cuda.Stream(), torch.cuda.Stream()]
+    cfg = _cfg(sp, 2, 64, kernel=2)                     # sorted plan, split partial sums: allocations inside
+    torch.cuda.synchronize()
+    outs = [None, None]
+    for rep in range(3):                                # interleave the two streams' calls
+        kms = []
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                kms.append(sp.build_kmap(coords_dev(clouds[i]), 3, 1, asynchronous=True))
+        for i, st in enumerate(streams):
+            (x32, x), (w32, w), (g32, g) = layers[i]
+            with torch.cuda.stream(st):
+                y = sp.fwd(x, w, kms[i], cfg)
+                dx = sp.dgrad(g, w, kms[i])
+                dw = sp.wgrad(x, g, kms[i])
+                outs[i] = (y, dx, dw)
+        for i, st in enumerate(streams):
+            with torch.cuda.stream(st):
+                kms[i].status()
+                kms[i].destroy()
+    torch.cuda.synchronize()
+    for i, r in enumerate(refs):
+        (x32, x), (w32, w), (g32, g) = layers[i]
+        y, dx, dw = outs[i]
+        assert norm_err(y, oc.forward(x32, w32, r.M)) <= TOL["f16"]
+        assert norm_err(dx, oc.dgrad(g32, w32, r.M, r.n_in)) <= TOL["f16"]
+        assert norm_err(dw, oc.wgrad(x32, g32, r.M)) <= 1e-4

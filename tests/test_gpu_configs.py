@@ -48,7 +48,7 @@ def test_config2_lidar_100k_fp16_64(sp):
     # and fixed points of the design space, both kernels
     for cfg in (_cfg(sp, n_split=0, kernel=1, tile_n=32), _cfg(sp, n_split=1, kernel=1, tile_n=32),
                 _cfg(sp, n_split=2, kernel=1, tile_n=64), _cfg(sp, n_split=0, kernel=2, tile_m=128),
-                _cfg(sp, n_split=3, kernel=2, tile_m=64)):
+                _cfg(sp, n_split=3, kernel=2, tile_m=64), _cfg(sp, kernel=3)):
         assert norm_err(sp.fwd(x, w, km, cfg), want_f) <= TOL["f16"], repr(cfg)
         assert norm_err(sp.dgrad(g, w, km, cfg), want_d) <= TOL["f16"], repr(cfg)
 
@@ -102,7 +102,9 @@ def test_config4_room_300k_bf16(sp, room, width):
     (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, width, width, 27, "bf16", 4000 + width)
     assert norm_err(sp.fwd(x, w, km), oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
     assert norm_err(sp.fwd(x, w, km, _cfg(sp, n_split=2)), oc.forward(x32, w32, ref.M)) <= TOL["bf16"]
+    assert norm_err(sp.fwd(x, w, km, _cfg(sp, kernel=3)), oc.forward(x32, w32, ref.M)) <= TOL["bf16"]   # fetch-on-demand
     assert norm_err(sp.dgrad(g, w, km), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["bf16"]
+    assert norm_err(sp.dgrad(g, w, km, _cfg(sp, kernel=3, tile_m=128)), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["bf16"]
     assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
 
 

@@ -226,31 +226,46 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
         }
       }
     } else {
-      // B[kk = ci][n = co] = W[k][ci][co]: read 8 output channels of one ci, scatter transposed
-      const int vecs = width * ROW_HALFS * (BN / 8);
-      for (int e0 = tid; e0 < vecs; e0 += kFill * blockDim.x) {
-        uint4 v[kFill];
+      // B[kk = ci][n = co] = W[k][ci][co].  A thread takes four consecutive ci of one group of 8
+      // output channels (four 16-byte loads), transposes the 4 x 8 block in registers and writes
+      // each output channel's four reduction steps with one 8-byte store (2-byte stores made this
+      // fill 1.7 us slower than the input gradient's, whose rows are copied as they are).
+      constexpr int kQuad = kFill / 4;  // 4-row groups in flight per thread
+      const int groups = width * (ROW_HALFS / 4) * (BN / 8);
+      for (int e0 = tid; e0 < groups; e0 += kQuad * blockDim.x) {
+        uint4 v[kQuad][4];
 #pragma unroll
-        for (int u = 0; u < kFill; ++u) {
+        for (int u = 0; u < kQuad; ++u) {
           const int e = e0 + u * blockDim.x;
-          const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
+          const int ng = e % (BN / 8), k4 = (e / (BN / 8)) % (ROW_HALFS / 4), c = e / ((BN / 8) * (ROW_HALFS / 4));
           const int k = lo + c;
-          const int ci = kk, co = n0 + ng * 8;
-          const bool ok = e < vecs && ci < p.C_in && co < p.C_out;
-          const unsigned off = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice + (unsigned)(ci * p.C_out + co) * 2u;
-          v[u] = buf_load16(w_rsrc, ok ? off : 0xFFFFFFFFu);
+          const int co = n0 + ng * 8;
+          const unsigned base = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice;
+#pragma unroll
+          for (int r = 0; r < 4; ++r) {
+            const int ci = k4 * 4 + r;
+            const bool ok = e < groups && ci < p.C_in && co < p.C_out;
+            v[u][r] = buf_load16(w_rsrc, ok ? base + (unsigned)(ci * p.C_out + co) * 2u : 0xFFFFFFFFu);
+          }
         }
 #pragma unroll
-        for (int u = 0; u < kFill; ++u) {
+        for (int u = 0; u < kQuad; ++u) {
           const int e = e0 + u * blockDim.x;
-          if (e >= vecs) continue;
-          const int ng = e % (BN / 8), kk = (e / (BN / 8)) % ROW_HALFS, c = e / ((BN / 8) * ROW_HALFS);
-          const unsigned w[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+          if (e >= groups) continue;
+          const int ng = e % (BN / 8), k4 = (e / (BN / 8)) % (ROW_HALFS / 4), c = e / ((BN / 8) * (ROW_HALFS / 4));
+          const int kk = k4 * 4;
+          const unsigned w[4][4] = {{v[u][0].x, v[u][0].y, v[u][0].z, v[u][0].w},
+                                    {v[u][1].x, v[u][1].y, v[u][1].z, v[u][1].w},
+                                    {v[u][2].x, v[u][2].y, v[u][2].z, v[u][2].w},
+                                    {v[u][3].x, v[u][3].y, v[u][3].z, v[u][3].w}};
 #pragma unroll
           for (int i = 0; i < 8; ++i) {
             const int n = ng * 8 + i;
-            const unsigned short h = (unsigned short)((i & 1) ? (w[i >> 1] >> 16) : (w[i >> 1] & 0xFFFFu));
-            Ws[((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(kk >> 3, n)) * 8 + (kk & 7)] = h;
+            const int sh = (i & 1) * 16;
+            const unsigned h0 = (w[0][i >> 1] >> sh) & 0xFFFFu, h1 = (w[1][i >> 1] >> sh) & 0xFFFFu;
+            const unsigned h2 = (w[2][i >> 1] >> sh) & 0xFFFFu, h3 = (w[3][i >> 1] >> sh) & 0xFFFFu;
+            *reinterpret_cast<uint2*>(Ws + ((size_t)(c * BN + n) * ROW_CHUNKS + swz<KS>(kk >> 3, n)) * 8 + (kk & 7)) =
+                make_uint2(h0 | (h1 << 16), h2 | (h3 << 16));
           }
         }
       }

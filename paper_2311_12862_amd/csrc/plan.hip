@@ -82,43 +82,67 @@ __global__ void __launch_bounds__(256)
   if ((threadIdx.x & 63) == 0 && mine) atomicAdd(executed, mine);
 }
 
-// Per-offset pair counts of each wave's wave_rows rows (a multiple of 64): counts[k][w].  A ballot per offset turns the
-// 64 masks held by the lanes into that offset's count; lane k keeps the running count of offset k.
-__global__ void __launch_bounds__(256)
-    k_pair_count(const unsigned* __restrict__ mask, long long rows, int V, int n_waves, int wave_rows,
-                 unsigned* __restrict__ counts) {
-  const int lane = threadIdx.x & 63;
-  const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  if (w >= n_waves) return;
+// Per-offset pair counts of chunks of wave_rows rows (a multiple of 256): counts[k][chunk].  A
+// workgroup takes one chunk, each of its four waves a quarter of it (more waves in flight than one
+// wave per chunk, same number of counters to scan).  A ballot per offset turns the 64 masks held by
+// the lanes into that offset's count; lane k keeps the running count of offset k.
+__device__ __forceinline__ unsigned count_offsets(const unsigned* __restrict__ mask, long long rows, long long first,
+                                                  int steps, int V, int lane) {
   unsigned mine = 0;
-  for (int it = 0; it < wave_rows / 64; ++it) {
-    const long long r = (long long)w * wave_rows + it * 64 + lane;
+  for (int it = 0; it < steps; ++it) {
+    const long long r = first + it * 64 + lane;
     const unsigned m = r < rows ? mask[r] : 0u;
     for (int k = 0; k < V; ++k) {
       const unsigned long long bal = __ballot((m >> k) & 1u);
       if (lane == k) mine += (unsigned)__popcll(bal);
     }
   }
-  if (lane < V) counts[(long long)lane * n_waves + w] = mine;
-  if (w == 0 && lane == 63) counts[(long long)V * n_waves] = 0;  // the slot that will receive the total
+  return mine;
 }
 
-// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.  The 64
-// map rows of a step are first copied to LDS with coalesced loads that are all in flight
-// together; the per-offset ballots then rank the present entries.
+__global__ void __launch_bounds__(256)
+    k_pair_count(const unsigned* __restrict__ mask, long long rows, int V, int n_chunks, int wave_rows,
+                 unsigned* __restrict__ counts) {
+  __shared__ unsigned part[4][32];
+  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+  const long long w = blockIdx.x;
+  if (w >= n_chunks) return;
+  const int sub = wave_rows / 4;
+  const unsigned mine = count_offsets(mask, rows, w * wave_rows + (long long)wib * sub, sub / 64, V, lane);
+  if (lane < 32) part[wib][lane] = lane < V ? mine : 0u;
+  __syncthreads();
+  if (wib == 0 && lane < V) counts[(long long)lane * n_chunks + w] = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+  if (w == 0 && threadIdx.x == 63) counts[(long long)V * n_chunks] = 0;  // the slot that will receive the total
+}
+
+// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.  A workgroup
+// takes one chunk: each wave recounts its quarter, so that it knows where its rows start inside
+// the chunk's range of every offset.  The 64 map rows of a step are first copied to LDS with
+// coalesced loads that are all in flight together; the per-offset ballots then rank the present
+// entries.  No pair is written past pairs_cap.
 template <int V>
 __global__ void __launch_bounds__(256)
-    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_waves,
-                int wave_rows, const unsigned* __restrict__ offs, int2* __restrict__ pairs) {
+    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_chunks,
+                int wave_rows, const unsigned* __restrict__ offs, int2* __restrict__ pairs, long long pairs_cap) {
   __shared__ int slab[4][64 * V];
+  __shared__ unsigned part[4][32];
   const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-  const long long w = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  if (w >= n_waves) return;
-  unsigned base = lane < V ? offs[(long long)lane * n_waves + w] : 0u;  // lane k: next slot of offset k
+  const long long w = blockIdx.x;
+  if (w >= n_chunks) return;
+  const int sub = wave_rows / 4;
+  const long long first = w * wave_rows + (long long)wib * sub;
+  const unsigned mine = count_offsets(mask, rows, first, sub / 64, V, lane);
+  if (lane < 32) part[wib][lane] = lane < V ? mine : 0u;
+  __syncthreads();
+  unsigned base = 0;  // lane k: next slot of offset k
+  if (lane < V) {
+    base = offs[(long long)lane * n_chunks + w];
+    for (int i = 0; i < wib; ++i) base += part[i][lane];
+  }
   const unsigned long long lt = (1ull << lane) - 1ull;
   int* ms = slab[wib];
-  for (int it = 0; it < wave_rows / 64; ++it) {
-    const long long r0 = (long long)w * wave_rows + it * 64;
+  for (int it = 0; it < sub / 64; ++it) {
+    const long long r0 = first + it * 64;
     if (r0 >= rows) break;
     const long long r = r0 + lane;
     const unsigned m = r < rows ? mask[r] : 0u;
@@ -133,8 +157,8 @@ __global__ void __launch_bounds__(256)
     for (int k = 0; k < V; ++k) {
       const bool bit = (m >> k) & 1u;
       const unsigned long long bal = __ballot(bit);
-      const unsigned start = __shfl(base, k);
-      if (bit) pairs[start + (unsigned)__popcll(bal & lt)] = make_int2((int)r, ms[lane * V + k]);
+      const unsigned slot = __shfl(base, k) + (unsigned)__popcll(bal & lt);
+      if (bit && (long long)slot < pairs_cap) pairs[slot] = make_int2((int)r, ms[lane * V + k]);
       if (lane == k) base += (unsigned)__popcll(bal);
     }
     __builtin_amdgcn_wave_barrier();
@@ -361,11 +385,13 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   p->target_pairs = target_pairs;
   p->pairs_cap = km->n_pairs >= 0 ? km->n_pairs : km->n_out * V;
   p->max_items = (int)std::min<int64_t>(V + ceil_div(p->pairs_cap, target_pairs), 1 << 20);
-  // rows per wave: 256, or up to 512 when that lets the counters fit the fused scan-and-items launch
+  // rows per chunk (one workgroup, a quarter per wave): 256, or 512 when that lets the counters fit
+  // the fused scan-and-items launch
   int wave_rows = 256;
-  while (wave_rows < 512 && (size_t)V * ceil_div(km->n_out, wave_rows) + 1 > (size_t)kFusedMax) wave_rows += 64;
-  if ((size_t)V * ceil_div(km->n_out, wave_rows) + 1 > (size_t)kFusedMax) wave_rows = 256;
-  const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, wave_rows));
+  if ((size_t)V * ceil_div(km->n_out, 256) + 1 > (size_t)kFusedMax &&
+      (size_t)V * ceil_div(km->n_out, 512) + 1 <= (size_t)kFusedMax)
+    wave_rows = 512;
+  const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, wave_rows));  // chunks
   const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
   const size_t n_sums = scan_sums_elems((int64_t)n_counts);
   DevBuf counts;
@@ -374,7 +400,7 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   SPC_TRY(p->seg.alloc((size_t)(V + 1) * sizeof(int)));
   SPC_TRY(p->items.alloc((size_t)p->max_items * sizeof(WgradItem)));
   SPC_TRY(p->item_seg.alloc((size_t)(V + 2) * sizeof(int)));
-  const unsigned blocks = blocks_for(n_waves, 4);
+  const unsigned blocks = (unsigned)n_waves;  // one workgroup per chunk
   hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
                      n_waves, wave_rows, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
@@ -398,15 +424,16 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   }
   const int* mp = side.map.as<int>();
   const unsigned* mk = side.mask.as<unsigned>();
+  const long long cap = (long long)std::max<int64_t>(1, p->pairs_cap);  // elements the pair buffer holds
   if (V == 27)
     hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
   else if (V == 8)
     hipLaunchKernelGGL((k_pair_fill<8>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
   else
     hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>());
+                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
   SPC_LAUNCH_CHECK();
   *out = p.get();
   km->wplans[target_pairs] = std::move(p);

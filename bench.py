@@ -48,6 +48,28 @@ def _events(fn, reps, torch):
     return e0.elapsed_time(e1) / reps
 
 
+def _single_launches(fn, reps, torch, flush=None):
+    """Average duration in ms of one fn() at a time, each bracketed by its own pair of events; with
+    `flush`, a buffer larger than the last-level cache is overwritten first, so that fn() finds its
+    operands in HBM only (cold).  The bracket itself costs a few microseconds: compare the cold
+    figure with the warm one measured the same way, not with the looped figure."""
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    fn()
+    total = 0.0
+    for _ in range(reps):
+        if flush is not None:
+            flush.zero_()
+        e0.record()
+        fn()
+        e1.record()
+        e1.synchronize()
+        total += e0.elapsed_time(e1)
+    return total / reps
+
+
+FLUSH_BYTES = 512 << 20     # twice the 256 MB last-level cache
+
+
 # Other single-layer workloads (parity-test configurations; not the headline line):
 # name -> (generator, dtype, C_in, C_out, stride, transposed)
 LAYER_WORKLOADS = {
@@ -98,6 +120,14 @@ def layer_report(name, reps):
     w = dev(gen.weights(27, c_in, c_out, dt, 2)[1])
     g = dev(gen.features(km.n_out, c_out, dt, 3)[1])
     flops = 2.0 * pairs * c_in * c_out
+    # compulsory HBM bytes per op: tensors read and written once, weights, and the map (fwd, dgrad:
+    # the 27-column table of the side that is walked; wgrad: the pair lists)
+    e = 2
+    io = km.n_in * c_in * e + km.n_out * c_out * e
+    bytes_of = {"fwd": io + 27 * c_in * c_out * e + km.n_out * 27 * 4,
+                "dgrad": io + 27 * c_in * c_out * e + km.n_in * 27 * 4,
+                "wgrad": io + 27 * c_in * c_out * 4 + pairs * 8}
+    flush = torch.empty(FLUSH_BYTES, dtype=torch.uint8, device="cuda")
     out = {"workload": name, "dtype": dt, "n_in": int(km.n_in), "n_out": int(km.n_out), "pairs": int(pairs),
            "c_in": c_in, "c_out": c_out, "stride": stride, "transposed": bool(transposed),
            "kmap_build_ms": round(build_ms, 4)}
@@ -106,7 +136,12 @@ def layer_report(name, reps):
                            (sp.OP_WGRAD, "wgrad", lambda c: sp.wgrad(x, g, km, c))):
         cfg, _ = sp.tune(km, c_in, c_out, tdt, op, 1000)
         ms = _events(lambda: run(cfg), reps, torch)
-        out[label] = {"ms": round(ms, 4), "effective_tflops": round(flops / (ms * 1e-3) / 1e12, 1), "cfg": repr(cfg)}
+        out[label] = {"ms": round(ms, 4), "effective_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
+                      "frac_of_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
+                      "frac_of_hbm_peak_compulsory_bytes": round(bytes_of[label] / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                      "single_launch_ms": {"warm": round(_single_launches(lambda: run(cfg), 10, torch), 4),
+                                           "cold": round(_single_launches(lambda: run(cfg), 10, torch, flush), 4)},
+                      "cfg": repr(cfg)}
     fod = sp.Config()
     fod.kernel, fod.tile_m = 3, 64
     out["fwd_fetch_on_demand_ms"] = round(_events(lambda: sp.fwd(x, w, km, fod), reps, torch), 4)
@@ -210,6 +245,7 @@ def main():
     t_build = _events(build_only, R, torch)
     for k in built:
         k.destroy()
+    built.clear()
     km = sp.build_kmap(coords, 3, 1)
     t_fwd = _events(lambda: sp.fwd(x, w, km, cfg_k, out=y), R, torch)
     t_fwd_e2e_cfg = _events(lambda: sp.fwd(x, w, km, cfg_f, out=y), R, torch)
@@ -219,6 +255,20 @@ def main():
     cfg_fod = sp.Config()
     cfg_fod.kernel, cfg_fod.tile_m = 3, 64
     t_fod = _events(lambda: sp.fwd(x, w, km, cfg_fod, out=y), R, torch)
+
+    # one launch at a time, warm (operands left in the caches by the previous launch) and cold
+    # (a 512 MB fill in between, so every operand comes from HBM)
+    flush = torch.empty(FLUSH_BYTES, dtype=torch.uint8, device="cuda")
+    single = {}
+    for label, fn in (("kmap_build", build_only), ("fwd_kernel", lambda: sp.fwd(x, w, km, cfg_k, out=y)),
+                      ("dgrad_kernel", lambda: sp.dgrad(g, w, km, cfg_d, out=dx)),
+                      ("wgrad_kernels", lambda: sp.wgrad(x, g, km, cfg_w, out=dw))):
+        single[label] = {"warm": round(_single_launches(fn, 10, torch), 4),
+                         "cold": round(_single_launches(fn, 10, torch, flush), 4)}
+    for k in built:
+        k.destroy()
+    built.clear()
+    del flush
 
     def mapping_ms(op, cfg):
         torch.cuda.synchronize()
@@ -272,6 +322,8 @@ def main():
                       "dgrad_kernel": round(t_dgrad, 4), "wgrad_kernels": round(t_wgrad, 4),
                       "fwd_mapping_first_call": round(map_f, 4), "wgrad_mapping_first_call": round(map_w, 4)},
         # forward with its mapping (sort, reorder, tile masks) spread over L layers that share the kmap
+        # the same phases one launch at a time between two events, warm and with the caches flushed
+        "phases_single_launch_ms": single,
         "fwd_ms_with_mapping": {"sorted_cfg_L1": round(t_fwd + map_f, 4), "sorted_cfg_L4": round(t_fwd + map_f / 4, 4),
                                 "unsorted_cfg": round(t_fwd_e2e_cfg, 4)},
         # forward kernels only, per dataflow (Section 2.2): implicit GEMM in the step's configuration

@@ -115,56 +115,6 @@ __global__ void __launch_bounds__(256)
   if (w == 0 && threadIdx.x == 63) counts[(long long)V * n_chunks] = 0;  // the slot that will receive the total
 }
 
-// Writes the pairs (n, M[n][k]) of every offset in row order at the scanned offsets.  A workgroup
-// takes one chunk: each wave recounts its quarter, so that it knows where its rows start inside
-// the chunk's range of every offset.  The 64 map rows of a step are first copied to LDS with
-// coalesced loads that are all in flight together; the per-offset ballots then rank the present
-// entries.  No pair is written past pairs_cap.
-template <int V>
-__global__ void __launch_bounds__(256)
-    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_chunks,
-                int wave_rows, const unsigned* __restrict__ offs, int2* __restrict__ pairs, long long pairs_cap) {
-  __shared__ int slab[4][64 * V];
-  __shared__ unsigned part[4][32];
-  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
-  const long long w = blockIdx.x;
-  if (w >= n_chunks) return;
-  const int sub = wave_rows / 4;
-  const long long first = w * wave_rows + (long long)wib * sub;
-  const unsigned mine = count_offsets(mask, rows, first, sub / 64, V, lane);
-  if (lane < 32) part[wib][lane] = lane < V ? mine : 0u;
-  __syncthreads();
-  unsigned base = 0;  // lane k: next slot of offset k
-  if (lane < V) {
-    base = offs[(long long)lane * n_chunks + w];
-    for (int i = 0; i < wib; ++i) base += part[i][lane];
-  }
-  const unsigned long long lt = (1ull << lane) - 1ull;
-  int* ms = slab[wib];
-  for (int it = 0; it < sub / 64; ++it) {
-    const long long r0 = first + it * 64;
-    if (r0 >= rows) break;
-    const long long r = r0 + lane;
-    const unsigned m = r < rows ? mask[r] : 0u;
-    // rows r0 .. r0+63 are contiguous in the padded map (rows_pad is a multiple of 256)
-    const int* src = map + r0 * V;
-    int tmp[V];
-#pragma unroll
-    for (int i = 0; i < V; ++i) tmp[i] = src[lane + 64 * i];
-#pragma unroll
-    for (int i = 0; i < V; ++i) ms[lane + 64 * i] = tmp[i];
-    __builtin_amdgcn_wave_barrier();
-    for (int k = 0; k < V; ++k) {
-      const bool bit = (m >> k) & 1u;
-      const unsigned long long bal = __ballot(bit);
-      const unsigned slot = __shfl(base, k) + (unsigned)__popcll(bal & lt);
-      if (bit && (long long)slot < pairs_cap) pairs[slot] = make_int2((int)r, ms[lane * V + k]);
-      if (lane == k) base += (unsigned)__popcll(bal);
-    }
-    __builtin_amdgcn_wave_barrier();
-  }
-}
-
 // Cuts every offset's pair range into ceil(count / target) nearly equal work items.  Called by a
 // whole workgroup; begin_of(k) returns the scanned pair offset of offset k (k = V: the total).
 template <typename BeginOf>
@@ -213,58 +163,123 @@ __device__ __forceinline__ void make_items(BeginOf begin_of, int V, unsigned tar
   }
 }
 
+// Most chunks for which the fill kernel adds up the per-chunk counts by itself: 64 lanes x steps.
+constexpr int kSelfScanSteps = 10;
+constexpr int kSelfScanChunks = 64 * kSelfScanSteps;
+
+// Writes the pairs (n, M[n][k]) of every offset in row order.  A workgroup takes one chunk: each
+// wave recounts its quarter, so that it knows where its rows start inside the chunk's range of
+// every offset.  The 64 map rows of a step are first copied to LDS with coalesced loads that are
+// all in flight together; the per-offset ballots then rank the present entries.  No pair is
+// written past pairs_cap.
+// Where the chunk's range starts: with SELF_SCAN the workgroup adds up the raw per-chunk counts
+// itself (every offset's total, and the part of it that the chunks before this one hold; 27 x
+// chunks counters, read from L2 by every workgroup, which is cheaper than a scan launch in between
+// while there are a few hundred chunks), and workgroup 0 also cuts the work items; otherwise
+// `counts` was scanned before the launch and the items are made elsewhere.
+template <int V, bool SELF_SCAN>
+__global__ void __launch_bounds__(256)
+    k_pair_fill(const int* __restrict__ map, const unsigned* __restrict__ mask, long long rows, int n_chunks,
+                int wave_rows, const unsigned* __restrict__ counts, int2* __restrict__ pairs, long long pairs_cap,
+                unsigned target, int max_items, int* __restrict__ seg, WgradItem* __restrict__ items,
+                int* __restrict__ item_seg) {
+  __shared__ int slab[4][64 * V];
+  __shared__ unsigned part[4][32];
+  __shared__ unsigned s_before[32], s_total[32], s_seg[34];
+  const int lane = threadIdx.x & 63, wib = threadIdx.x >> 6;
+  const long long w = blockIdx.x;
+  if (w >= n_chunks) return;
+  const int sub = wave_rows / 4;
+  const long long first = w * wave_rows + (long long)wib * sub;
+  // a wave per offset (wib, wib + 4, ...), lanes over the chunks; every counter load is issued
+  // before the first is used
+  constexpr int KPW = (V + 3) / 4;
+  unsigned cv[SELF_SCAN ? KPW : 1][SELF_SCAN ? kSelfScanSteps : 1];
+  if constexpr (SELF_SCAN) {
+#pragma unroll
+    for (int q = 0; q < KPW; ++q) {
+      const int k = wib + 4 * q;
+#pragma unroll
+      for (int i = 0; i < kSelfScanSteps; ++i) {
+        const int j = lane + 64 * i;
+        cv[q][i] = (k < V && j < n_chunks) ? counts[(long long)k * n_chunks + j] : 0u;
+      }
+    }
+  }
+  const unsigned mine = count_offsets(mask, rows, first, sub / 64, V, lane);
+  if (lane < 32) part[wib][lane] = lane < V ? mine : 0u;
+  if constexpr (SELF_SCAN) {
+#pragma unroll
+    for (int q = 0; q < KPW; ++q) {
+      const int k = wib + 4 * q;
+      unsigned tot = 0, bef = 0;
+#pragma unroll
+      for (int i = 0; i < kSelfScanSteps; ++i) {
+        tot += cv[q][i];
+        if (lane + 64 * i < w) bef += cv[q][i];
+      }
+      for (int o = 32; o > 0; o >>= 1) {
+        tot += __shfl_xor(tot, o);
+        bef += __shfl_xor(bef, o);
+      }
+      if (lane == 0 && k < V) {
+        s_total[k] = tot;
+        s_before[k] = bef;
+      }
+    }
+    __syncthreads();
+    if (wib == 0) {  // where each offset's pairs begin: exclusive scan of the totals; [V] = all pairs
+      const unsigned t = lane < V ? s_total[lane] : 0u;
+      unsigned incl = t;
+      for (int o = 1; o < 64; o <<= 1) {
+        const unsigned up = __shfl_up(incl, o);
+        if (lane >= o) incl += up;
+      }
+      if (lane <= V) s_seg[lane] = incl - t;
+    }
+  }
+  __syncthreads();
+  unsigned base = 0;  // lane k: next slot of offset k
+  if (lane < V) {
+    if constexpr (SELF_SCAN)
+      base = s_seg[lane] + s_before[lane];
+    else
+      base = counts[(long long)lane * n_chunks + w];
+    for (int i = 0; i < wib; ++i) base += part[i][lane];
+  }
+  if constexpr (SELF_SCAN) {
+    if (w == 0) make_items([&](int k) { return s_seg[k]; }, V, target, max_items, seg, items, item_seg);
+  }
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  int* ms = slab[wib];
+  for (int it = 0; it < sub / 64; ++it) {
+    const long long r0 = first + it * 64;
+    if (r0 >= rows) break;
+    const long long r = r0 + lane;
+    const unsigned m = r < rows ? mask[r] : 0u;
+    // rows r0 .. r0+63 are contiguous in the padded map (rows_pad is a multiple of 256)
+    const int* src = map + r0 * V;
+    int tmp[V];
+#pragma unroll
+    for (int i = 0; i < V; ++i) tmp[i] = src[lane + 64 * i];
+#pragma unroll
+    for (int i = 0; i < V; ++i) ms[lane + 64 * i] = tmp[i];
+    __builtin_amdgcn_wave_barrier();
+    for (int k = 0; k < V; ++k) {
+      const bool bit = (m >> k) & 1u;
+      const unsigned long long bal = __ballot(bit);
+      const unsigned slot = __shfl(base, k) + (unsigned)__popcll(bal & lt);
+      if (bit && (long long)slot < pairs_cap) pairs[slot] = make_int2((int)r, ms[lane * V + k]);
+      if (lane == k) base += (unsigned)__popcll(bal);
+    }
+    __builtin_amdgcn_wave_barrier();
+  }
+}
+
 __global__ void __launch_bounds__(256)
     k_make_items(const unsigned* __restrict__ scanned, int V, int n_waves, unsigned target, int max_items,
                  int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
   make_items([&](int k) { return scanned[(long long)k * n_waves]; }, V, target, max_items, seg, items, item_seg);
-}
-
-// Up to 16384 counters: exclusive scan in place and the work items in one launch (one workgroup
-// of 1024 threads; 16 consecutive counters per thread through LDS, wave-shuffle scan across threads).
-constexpr int kFusedPer = 16;
-constexpr int kFusedMax = 1024 * kFusedPer;
-constexpr size_t kFusedLds = (size_t)(kFusedMax + kFusedMax / 32 + 8) * sizeof(unsigned);
-__global__ void __launch_bounds__(1024)
-    k_scan_items(unsigned* __restrict__ counts, int n_counts, int V, int n_waves, unsigned target, int max_items,
-                 int* __restrict__ seg, WgradItem* __restrict__ items, int* __restrict__ item_seg) {
-  extern __shared__ unsigned tile[];
-  __shared__ unsigned wave_sum[16];
-  auto skew = [](int x) { return x + (x >> 5); };
-  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-#pragma unroll
-  for (int i = 0; i < kFusedPer; ++i) {
-    const int g = i * 1024 + t;
-    tile[skew(g)] = g < n_counts ? counts[g] : 0u;
-  }
-  __syncthreads();
-  unsigned v[kFusedPer], sum = 0;
-#pragma unroll
-  for (int i = 0; i < kFusedPer; ++i) {
-    v[i] = tile[skew(t * kFusedPer + i)];
-    sum += v[i];
-  }
-  unsigned incl = sum;
-#pragma unroll
-  for (int o = 1; o < 64; o <<= 1) {
-    const unsigned up = __shfl_up(incl, o);
-    if (lane >= o) incl += up;
-  }
-  if (lane == 63) wave_sum[wave] = incl;
-  __syncthreads();
-  unsigned run = incl - sum;
-  for (int w = 0; w < wave; ++w) run += wave_sum[w];
-#pragma unroll
-  for (int i = 0; i < kFusedPer; ++i) {
-    tile[skew(t * kFusedPer + i)] = run;
-    run += v[i];
-  }
-  __syncthreads();
-#pragma unroll
-  for (int i = 0; i < kFusedPer; ++i) {
-    const int g = i * 1024 + t;
-    if (g < n_counts) counts[g] = tile[skew(g)];
-  }
-  make_items([&](int k) { return tile[skew(k * n_waves)]; }, V, target, max_items, seg, items, item_seg);
 }
 
 }  // namespace
@@ -385,12 +400,10 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   p->target_pairs = target_pairs;
   p->pairs_cap = km->n_pairs >= 0 ? km->n_pairs : km->n_out * V;
   p->max_items = (int)std::min<int64_t>(V + ceil_div(p->pairs_cap, target_pairs), 1 << 20);
-  // rows per chunk (one workgroup, a quarter per wave): 256, or 512 when that lets the counters fit
-  // the fused scan-and-items launch
+  // rows per chunk (one workgroup, a quarter per wave): 256, or the next power of two up to 2048
+  // that lets the fill kernel add up the counters itself
   int wave_rows = 256;
-  if ((size_t)V * ceil_div(km->n_out, 256) + 1 > (size_t)kFusedMax &&
-      (size_t)V * ceil_div(km->n_out, 512) + 1 <= (size_t)kFusedMax)
-    wave_rows = 512;
+  while (ceil_div(km->n_out, wave_rows) > kSelfScanChunks && wave_rows < 2048) wave_rows *= 2;
   const int n_waves = (int)std::max<int64_t>(1, ceil_div(km->n_out, wave_rows));  // chunks
   const size_t n_counts = (size_t)V * n_waves + 1;  // the extra counter ends up holding the total
   const size_t n_sums = scan_sums_elems((int64_t)n_counts);
@@ -404,18 +417,10 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   hipLaunchKernelGGL(k_pair_count, dim3(blocks), dim3(256), 0, st, side.mask.as<unsigned>(), (long long)km->n_out, V,
                      n_waves, wave_rows, counts.as<unsigned>());
   SPC_LAUNCH_CHECK();
-  if (n_counts <= (size_t)kFusedMax) {
-    static bool attr_set = false;
-    if (!attr_set) {
-      SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_scan_items),
-                                  hipFuncAttributeMaxDynamicSharedMemorySize, (int)kFusedLds));
-      attr_set = true;
-    }
-    hipLaunchKernelGGL(k_scan_items, dim3(1), dim3(1024), kFusedLds, st, counts.as<unsigned>(), (int)n_counts, V, n_waves,
-                       (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
-                       p->item_seg.as<int>());
-    SPC_LAUNCH_CHECK();
-  } else {
+  // Up to kSelfScanChunks chunks the fill kernel adds up the raw counts itself; beyond that (its
+  // reads grow with the square of the chunk count) they are scanned by launches of their own.
+  const bool self_scan = n_waves <= kSelfScanChunks;
+  if (!self_scan) {
     SPC_TRY(scan_u32_inplace(counts.as<uint32_t>(), (int64_t)n_counts, counts.as<uint32_t>() + n_counts, st));
     hipLaunchKernelGGL(k_make_items, dim3(1), dim3(256), 0, st, counts.as<unsigned>(), V, n_waves,
                        (unsigned)target_pairs, p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(),
@@ -425,15 +430,18 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   const int* mp = side.map.as<int>();
   const unsigned* mk = side.mask.as<unsigned>();
   const long long cap = (long long)std::max<int64_t>(1, p->pairs_cap);  // elements the pair buffer holds
-  if (V == 27)
-    hipLaunchKernelGGL((k_pair_fill<27>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
-  else if (V == 8)
-    hipLaunchKernelGGL((k_pair_fill<8>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
-  else
-    hipLaunchKernelGGL((k_pair_fill<1>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out, n_waves,
-                       wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap);
+#define SPC_FILL(VV, SELF)                                                                                       \
+  hipLaunchKernelGGL((k_pair_fill<VV, SELF>), dim3(blocks), dim3(256), 0, st, mp, mk, (long long)km->n_out,       \
+                     n_waves, wave_rows, counts.as<unsigned>(), p->pairs.as<int2>(), cap, (unsigned)target_pairs, \
+                     p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(), p->item_seg.as<int>())
+  if (V == 27) {
+    if (self_scan) SPC_FILL(27, true); else SPC_FILL(27, false);
+  } else if (V == 8) {
+    if (self_scan) SPC_FILL(8, true); else SPC_FILL(8, false);
+  } else {
+    if (self_scan) SPC_FILL(1, true); else SPC_FILL(1, false);
+  }
+#undef SPC_FILL
   SPC_LAUNCH_CHECK();
   *out = p.get();
   km->wplans[target_pairs] = std::move(p);

@@ -188,17 +188,23 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
   const int n_chunks = (c_red + KC - 1) / KC;
   const int total = __popc(tmask) * n_chunks;
 
-  uint4 ra0[A_PASSES], rb0[B_PASSES];  // operands of the step that is on its way
+  // operands on their way: the weights of the next step, the gathered rows of the next two
+  uint4 ra0[A_PASSES] = {}, ra1[A_PASSES] = {}, rb0[B_PASSES] = {};
   const int a_seg = tid % SEG, a_row = tid / SEG;
 
-  auto load_regs = [&](uint4* ra, uint4* rb, int c, int chunk) {
+  auto load_a = [&](uint4* ra, int c, int chunk) {
+    // all map entries are read before the first load is issued (one LDS latency, not one per load)
+    int idx[A_PASSES];
+#pragma unroll
+    for (int ps = 0; ps < A_PASSES; ++ps) idx[ps] = mapS[(a_row + ps * A_RPP) * width + c];
     const unsigned col = (unsigned)(chunk * KC + a_seg * 8);
 #pragma unroll
     for (int ps = 0; ps < A_PASSES; ++ps) {
-      const int idx = mapS[(a_row + ps * A_RPP) * width + c];
       // idx = -1 wraps to just below 2^32: out of range
-      ra[ps] = buf_load16(x_rsrc, col < (unsigned)c_red ? (unsigned)idx * row_bytes + col * 2u : 0xFFFFFFFFu);
+      ra[ps] = buf_load16(x_rsrc, col < (unsigned)c_red ? (unsigned)idx[ps] * row_bytes + col * 2u : 0xFFFFFFFFu);
     }
+  };
+  auto load_b = [&](uint4* rb, int c, int chunk) {
     const int k = lo + c;
     const unsigned wk = (unsigned)(p.mirror ? p.V - 1 - k : k) * slice_bytes;
     if constexpr (!DGRAD) {  // rows of W[k]: reduction channel ci, 8 output channels per load
@@ -283,42 +289,69 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
     }
   };
 
-  // The steps in order: set bits of the tile mask, ascending, each with its chunks.  The loads of
-  // a step are issued one step ahead of the matrix cores and wait in registers; one step lives in
-  // LDS.  (A second register set, two steps ahead, was measured and changed nothing.)
-  unsigned m_rem = tmask;
-  int iss_c = 0, iss_chunk = 0, issued = 0;  // the next step to issue
-  if (total > 0) {
-    iss_c = __ffs((int)m_rem) - 1;
-    m_rem &= m_rem - 1;
-  }
-  int c_lds = 0, c_regs = 0;  // offsets of the step in LDS and of the step held in registers
-  auto issue = [&]() {
-    if (issued < total) {
-      load_regs(ra0, rb0, iss_c, iss_chunk);
-      c_regs = iss_c;
-      if (++iss_chunk == n_chunks) {
-        iss_chunk = 0;
-        iss_c = m_rem ? __ffs((int)m_rem) - 1 : 0;
-        m_rem &= m_rem - 1;
-      }
+  // The steps in order: set bits of the tile mask, ascending, each with its chunks.  One step lives
+  // in LDS.  The weight tile of the next step (an L2 hit) is loaded one step ahead; the gathered
+  // rows, which mostly come from beyond L2, two steps ahead, alternating between two register
+  // sets so that a set in flight is never copied (a copy would wait for it).
+  struct Cursor {  // walks the steps
+    unsigned rem;
+    int c, chunk, left;
+  };
+  auto cursor_begin = [&]() {
+    Cursor q{tmask, 0, 0, total};
+    if (total > 0) {
+      q.c = __ffs((int)q.rem) - 1;
+      q.rem &= q.rem - 1;
     }
-    ++issued;
+    return q;
+  };
+  auto cursor_next = [&](Cursor& q) {
+    --q.left;
+    if (++q.chunk == n_chunks) {
+      q.chunk = 0;
+      q.c = q.rem ? __ffs((int)q.rem) - 1 : 0;
+      q.rem &= q.rem - 1;
+    }
+  };
+  Cursor qa = cursor_begin(), qb = cursor_begin();  // next step whose rows / weights are to be issued
+  int c_lds = 0, c_regs = 0;  // offsets of the step in LDS and of the step whose weights are in registers
+  auto issue_a = [&](uint4* ra) {
+    if (qa.left > 0) {
+      load_a(ra, qa.c, qa.chunk);
+      cursor_next(qa);
+    }
+  };
+  auto issue_b = [&]() {
+    if (qb.left > 0) {
+      load_b(rb0, qb.c, qb.chunk);
+      c_regs = qb.c;
+      cursor_next(qb);
+    }
+  };
+  // one step: `cur` holds the rows of the next step (issued a step ago), `nxt` receives those of
+  // the step after it; returns true after the last step
+  auto step = [&](uint4* cur, uint4* nxt, int it) {
+    issue_b();
+    issue_a(nxt);
+    compute(c_lds);
+    if (it + 1 >= total) return true;
+    __syncthreads();  // everyone is done reading this step's tiles
+    store_lds(cur, rb0);
+    c_lds = c_regs;
+    __syncthreads();
+    return false;
   };
   if (total > 0) {
-    issue();
+    issue_b();
+    issue_a(ra0);
+    issue_a(ra1);
     store_lds(ra0, rb0);
     c_lds = c_regs;
   }
   __syncthreads();
-  for (int it = 0; it < total; ++it) {
-    issue();  // the next step travels while this one is on the matrix cores
-    compute(c_lds);
-    if (it + 1 >= total) break;
-    __syncthreads();  // everyone is done reading this step's tiles
-    store_lds(ra0, rb0);
-    c_lds = c_regs;
-    __syncthreads();
+  for (int it = 0; it < total; it += 2) {
+    if (step(ra1, ra0, it)) break;
+    if (step(ra0, ra1, it + 1)) break;
   }
 
   // D layout of the 16x16 MFMA: lane holds rows 4*(lane/16)+r, column lane%16

@@ -133,15 +133,14 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 
   {  // map slab and output rows of this tile: every load is issued before the first one is awaited
     // (the slab is BM * width consecutive ints; tiles start on 256-byte boundaries)
+    // through a buffer descriptor that ends with the slab: a load past the end returns zeros, so
+    // no load sits behind a branch and all of them are in flight together
     constexpr int SLAB_IT = (BM * 27 / 4 + NT - 1) / NT;
-    const int4* mp4 = reinterpret_cast<const int4*>(p.map[part] + row0 * width);
     const int n4 = BM * width / 4;
-    int4 slab[SLAB_IT];
+    const __amdgpu_buffer_rsrc_t m_rsrc = make_rsrc(p.map[part] + row0 * width, (unsigned)n4 * 16u);
+    uint4 slab[SLAB_IT];
 #pragma unroll
-    for (int i = 0; i < SLAB_IT; ++i) {
-      const int e = tid + NT * i;
-      if (e < n4) slab[i] = mp4[e];
-    }
+    for (int i = 0; i < SLAB_IT; ++i) slab[i] = buf_load16(m_rsrc, (unsigned)(tid + NT * i) * 16u);
     const int* pm = p.perm[part];
     for (int r = tid; r < BM; r += NT) {
       const long long g = row0 + r;
@@ -150,7 +149,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 #pragma unroll
     for (int i = 0; i < SLAB_IT; ++i) {
       const int e = tid + NT * i;
-      if (e < n4) reinterpret_cast<int4*>(mapS)[e] = slab[i];
+      if (e < n4) reinterpret_cast<uint4*>(mapS)[e] = slab[i];
     }
   }
   __syncthreads();

@@ -82,7 +82,7 @@ LAYER_WORKLOADS = {
 }
 
 
-def layer_report(name, reps):
+def layer_report(name, reps, fixed=None):
     """One JSON line for one of LAYER_WORKLOADS: kmap build and the three kernels under the tuner's
     kernel-only choice (mapping amortised over many layers), plus forward in the other dataflow."""
     import numpy as np
@@ -134,7 +134,13 @@ def layer_report(name, reps):
     for op, label, run in ((sp.OP_FWD, "fwd", lambda c: sp.fwd(x, w, km, c)),
                            (sp.OP_DGRAD, "dgrad", lambda c: sp.dgrad(g, w, km, c)),
                            (sp.OP_WGRAD, "wgrad", lambda c: sp.wgrad(x, g, km, c))):
-        cfg, _ = sp.tune(km, c_in, c_out, tdt, op, 1000)
+        if fixed is not None and op != sp.OP_WGRAD:   # untuned: every launch of the run is this configuration
+            cfg = sp.Config()
+            cfg.kernel, cfg.n_split, cfg.tile_m, cfg.tile_n = fixed
+        elif fixed is not None:
+            cfg = sp.Config()
+        else:
+            cfg, _ = sp.tune(km, c_in, c_out, tdt, op, 1000)
         ms = _events(lambda: run(cfg), reps, torch)
         out[label] = {"ms": round(ms, 4), "effective_tflops": round(flops / (ms * 1e-3) / 1e12, 1),
                       "frac_of_mfma_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS, 4),
@@ -160,6 +166,9 @@ def main():
     ap.add_argument("--fix-kernel-only-config", action="store_true",
                     help="kernel-only forward with n_split=1, tile_n=32, kernel=1 (the usual winner) instead of the "
                          "tuner's pick: under a counter-collecting profiler the tuner's timings are perturbed")
+    ap.add_argument("--layer-config", default=None, metavar="KERNEL,N_SPLIT,TILE_M,TILE_N",
+                    help="per-layer workloads: skip the tuner and run forward and dgrad in this configuration (wgrad in "
+                         "the automatic one), so that a profiler sees one configuration per kernel")
     ap.add_argument("--workload", default="lidar100k", choices=["lidar100k"] + sorted(LAYER_WORKLOADS),
                     help="lidar100k (default): the headline step; the others print a per-layer report instead")
     args = ap.parse_args()
@@ -170,7 +179,10 @@ def main():
         if not torch.cuda.is_available():
             sys.exit("bench.py needs a GPU")
         torch.cuda.set_device(0)
-        return layer_report(args.workload, args.kernel_reps)
+        fixed = tuple(int(v) for v in args.layer_config.split(",")) if args.layer_config else None
+        if fixed is not None and len(fixed) != 4:
+            sys.exit("bench.py: --layer-config takes four integers: kernel,n_split,tile_m,tile_n")
+        return layer_report(args.workload, args.kernel_reps, fixed)
 
     import numpy as np
     import torch

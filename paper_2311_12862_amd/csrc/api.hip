@@ -183,24 +183,32 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
     a.tile_n = c.tile_n;
     return fod_run(km, *wp, a, c.tile_m, dst, st);
   }
-  if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
-    // automatic tile height: 128 rows only when that still leaves several workgroups per CU
-    const int c_cols = op == SPCONV_OP_FWD ? C_out : C_in;
-    c.tile_m = ceil_div(rows_dst, 128) * ceil_div(c_cols, 128) >= 2048 ? 128 : 64;
-  }
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   const int c_red = os.dgrad ? C_out : C_in;
+  const int c_cols = os.dgrad ? C_in : C_out;
+  if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
+    // automatic tile height (measured on unsorted maps, 10k .. 300k rows): 128 rows when that still
+    // leaves several workgroups per CU, or when the reduction is long (>= 128 channels) and there
+    // are enough rows for a workgroup per CU anyway; 64 rows otherwise
+    c.tile_m = (ceil_div(rows_dst, 128) * ceil_div(c_cols, 128) >= 2048 || (rows_dst >= 25000 && c_red >= 128)) ? 128 : 64;
+  }
   bool wave = false;
   if (c.kernel != 2) {
-    const int c_cols = os.dgrad ? C_in : C_out;
     const int bn = igemm_wave_pick_bn(km->V, c.n_split, c_red, c_cols, c.tile_n, nullptr);
     wave = bn > 0;
     if (!wave && c.kernel == 1) return SPCONV_EINVAL;
-    // Automatic choice: the LDS-resident kernel gathers the input once per column tile, so it only
-    // pays while the output is at most two tiles wide (64 -> 64 is 2 x 32); wider layers go to
-    // the tiled kernel, which gathers once per 128 columns.
-    if (wave && c.kernel == 0 && (c_cols + bn - 1) / bn > 2) wave = false;
+    // Automatic choice: the LDS-resident kernel gathers the input once per column tile.  It wins
+    // while the output is at most two tiles wide (64 -> 64 is 2 x 32) and, beyond that, while
+    // tiles x reduced channels x rows stays small: few rows leave the tiled kernel without enough
+    // workgroups, many rows make the repeated gathers the larger cost (measured: 100k rows,
+    // 64 -> 256 in eight tiles 89 us against 114 us; 128 -> 128 in eight 16-column tiles 160 us
+    // against 131 us; 10k rows, 128 -> 128 25 us against 41 us; 300k rows, 64 -> 128 213 us
+    // against 171 us).
+    if (wave && c.kernel == 0) {
+      const int64_t tiles = ceil_div(c_cols, bn);
+      if (tiles > 2 && (double)tiles * c_red * (double)rows_dst > 6e7) wave = false;
+    }
   }
   if (!wave && c.tile_n == 16) return SPCONV_EINVAL;
   IgemmPlan* plan = nullptr;
@@ -214,6 +222,11 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   a.mirror = os.mirror;
   a.dtype = dtype;
   a.tile_n = c.tile_n;
+  // few row tiles: 64-column tiles double the workgroups of the tiled kernel (10k rows, 256 -> 256:
+  // 91 us against 104 us)
+  if (!wave && c.tile_n == 0 && dtype != SPCONV_F32 && c.tile_m == 64 && c_cols > 64 &&
+      ceil_div(rows_dst, 64) * ceil_div(c_cols, 128) < 400)
+    a.tile_n = 64;
   const int c_dst = os.dgrad ? C_in : C_out;
   if (plan->parts > 1) {
     SPC_TRY(km->scratch.reserve((size_t)plan->parts * plan->rows * c_dst * sizeof(float)));

@@ -136,3 +136,16 @@ def test_detection_style_stack(sp):
             fd, _, _, _ = sp.tune_group(dkm, [(c, co)], torch.float16)
             assert norm_err(sp.fwd(x, w, dkm, fd[0]), oc.forward(x32, w32, dref.M)) <= TOL["f16"], repr(fd[0])
             lvl = dref.out_coords
+
+
+def test_pair_lists_of_a_1_35m_voxel_cloud(sp):
+    """Beyond ~1.3M rows the per-chunk pair counts are scanned by launches of their own instead of
+    by the fill kernel (below, every fill workgroup adds them up itself): the weight gradient over
+    those pair lists against the plain definition, with the map bit-exact on the way."""
+    c = gen.uniform_cloud(1_350_000, 256, seed=77)
+    ref = oc.build_kmap(c, 3, 1)
+    (x32, x), _, (g32, g) = make_layer(ref.n_in, ref.n_out, 8, 8, 27, "f16", 9100)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    assert km.n_pairs() == int((ref.M >= 0).sum())
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4

@@ -151,6 +151,18 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
  * EHIP, ERANGE / EDUP of a pending build; on error *out is NULL. */
 SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out);
 
+/* The K = 1, stride 1 kmap over one of km's row sets: its input rows (on_outputs = 0) or its
+ * output rows (on_outputs = 1).  A 1x1x1 convolution (Eq. 1 with the single offset 0) pairs every
+ * row with itself, so nothing is hashed or probed: the rows were validated when km was built, and
+ * the call writes an identity map and copies the coordinates (exactly what spconv_build_kmap
+ * returns for those rows with K = 1, at a fraction of its cost: the projection shortcuts of a
+ * residual network take their kmaps from the level's 3x3x3 kmap this way).  *out is independent
+ * of km.  `stream` must be ordered after the work that built km; an unresolved asynchronous build
+ * is resolved first and its error, if any, is returned.  Errors: EINVAL (null arguments,
+ * on_outputs other than 0 or 1), ENOMEM, EHIP, ERANGE / EDUP of a pending build; on error *out
+ * is NULL. */
+SPCONV_API int spconv_kmap_pointwise(spconv_kmap* km, int on_outputs, void* stream, spconv_kmap** out);
+
 /* Resolves an asynchronous build: waits until the build's last kernel has published its result
  * (a word in pinned host memory that the host reads: nothing is recorded on the stream, and no
  * wait at all once that kernel has finished), returns SPCONV_OK, SPCONV_ERANGE or SPCONV_EDUP, and

@@ -62,6 +62,7 @@ def load_library():
         "spconv_build_kmap_async": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
         "spconv_kmap_status": (i32, [vp, vp]),
         "spconv_kmap_transpose": (i32, [vp, vp, C.POINTER(vp)]),
+        "spconv_kmap_pointwise": (i32, [vp, i32, vp, C.POINTER(vp)]),
         "spconv_kmap_sizes": (i32, [vp, C.POINTER(i64), C.POINTER(i64), C.POINTER(i64)]),
         "spconv_kmap_out_coords": (i32, [vp, vp, vp]),
         "spconv_kmap_in_coords": (i32, [vp, vp, vp]),
@@ -170,6 +171,13 @@ class KMap:
         h = C.c_void_p()
         _check(load_library().spconv_kmap_transpose(self.handle, _stream(stream), C.byref(h)), "spconv_kmap_transpose")
         return KMap(h, self.K)
+
+    def pointwise(self, on_outputs: bool = False, stream=None) -> "KMap":
+        """spconv_kmap_pointwise: the K = 1 kmap over this kmap's input (or output) rows."""
+        h = C.c_void_p()
+        _check(load_library().spconv_kmap_pointwise(self.handle, int(bool(on_outputs)), _stream(stream), C.byref(h)),
+               "spconv_kmap_pointwise")
+        return KMap(h, 1)
 
     def n_pairs(self) -> int:
         v = C.c_int64()

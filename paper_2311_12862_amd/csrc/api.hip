@@ -272,6 +272,15 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
   return kmap_build(coords, N, K, stride, transposed, true, (hipStream_t)stream, out);
 }
 
+SPCONV_API int spconv_kmap_pointwise(spconv_kmap* km, int on_outputs, void* stream, spconv_kmap** out) {
+  StreamScope scope((hipStream_t)stream);
+  if (!out) return SPCONV_EINVAL;
+  *out = nullptr;
+  if (!km || (on_outputs != 0 && on_outputs != 1)) return SPCONV_EINVAL;
+  km->last_stream = (hipStream_t)stream;
+  return kmap_pointwise(km, on_outputs, (hipStream_t)stream, out);
+}
+
 SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out) {
   StreamScope scope((hipStream_t)stream);
   if (!out) return SPCONV_EINVAL;

@@ -138,6 +138,7 @@ int kmap_status(spconv_kmap* km, hipStream_t st);  // resolves a pending asynchr
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);
 int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out);
+int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap** out);
 
 // ---- sort.hip
 // Stable LSD radix sort of n (key, value) pairs on key bits [0, key_bits).

@@ -340,6 +340,15 @@ __global__ void __launch_bounds__(256)
 }
 
 // Plain fills (in place of memset calls, which must stay out of anything a caller may capture).
+// The K = 1 map of a row set: row r meets itself; rows of the padding meet nothing.
+__global__ void __launch_bounds__(256) k_identity_map(int* __restrict__ map, unsigned* __restrict__ mask,
+                                                      long long rows, long long rows_pad) {
+  const long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows_pad) return;
+  map[r] = r < rows ? (int)r : -1;
+  mask[r] = r < rows ? 1u : 0u;
+}
+
 __global__ void __launch_bounds__(256) k_fill_u32(unsigned* __restrict__ dst, long long n, unsigned v) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = v;
@@ -974,6 +983,45 @@ int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
 // outputs exchanged.  Its output-stationary table is src's input-side table and the other way
 // round, so no table is built and nothing is probed: one scatter pass (unless src has its input
 // side already) and device-to-device copies.
+int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap** out) {
+  if (src->pending) SPC_TRY(kmap_status(src, st));  // a failed build has no rows to stand on
+  std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
+  if (!km) return SPCONV_ENOMEM;
+  const int64_t rows = on_outputs ? src->n_out : src->n_in;
+  km->K = 1;
+  km->V = 1;
+  km->stride = 1;
+  km->transposed = 0;
+  km->n_in = km->n_out = km->n_pairs = rows;
+  km->build_stream = st;
+  km->last_stream = st;
+  SideMap& side = km->out_side;
+  side.rows = rows;
+  side.rows_pad = round_up(rows > 0 ? rows : 1, kRowPad);
+  SPC_TRY(side.map.alloc((size_t)side.rows_pad * sizeof(int)));
+  SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
+  hipLaunchKernelGGL(k_identity_map, dim3(blocks_for(side.rows_pad, 256)), dim3(256), 0, st, side.map.as<int>(),
+                     side.mask.as<unsigned>(), (long long)rows, (long long)side.rows_pad);
+  SPC_LAUNCH_CHECK();
+  side.ready = true;
+  // Which buffer of src holds that side's rows: a kmap keeps the caller's rows and, for stride > 1,
+  // the coarse set; with stride 1 the two sets are one (in_coords of a forward kmap, out_coords of
+  // a transposed one).
+  const DevBuf* from;
+  if (!src->transposed)
+    from = (on_outputs && src->stride > 1) ? &src->out_coords : &src->in_coords;
+  else
+    from = (!on_outputs && src->stride > 1) ? &src->in_coords : &src->out_coords;
+  if (rows == 0 || !from->p) {
+    SPC_TRY(km->in_coords.alloc(16));
+  } else {
+    SPC_TRY(km->in_coords.alloc((size_t)rows * 16));
+    SPC_HIP(hipMemcpyAsync(km->in_coords.p, from->p, (size_t)rows * 16, hipMemcpyDeviceToDevice, st));
+  }
+  *out = km.release();
+  return SPCONV_OK;
+}
+
 int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out) {
   if (src->pending) SPC_TRY(kmap_status(src, st));  // a failed build has no transpose
   SPC_TRY(kmap_build_in_side(src, st));

@@ -260,3 +260,41 @@ def test_transpose_of_empty_and_pending_builds(sp):
     with pytest.raises(sp.SpconvError) as e:
         bad.transpose()
     assert e.value.status == -3          # SPCONV_EDUP
+
+
+@pytest.mark.parametrize("stride,transposed", [(1, False), (2, False), (2, True), (3, False)])
+def test_pointwise_equals_a_k1_build(sp, stride, transposed):
+    """spconv_kmap_pointwise: the K = 1 kmap over either row set of a kmap is what a K = 1 build on
+    those rows returns (map, mask, coordinates, sizes), and a 1x1x1 layer through it is X . W[0]."""
+    import torch
+    from _util import make_layer, norm_err, TOL
+    c = gen.lidar_scene(96, target_n=2200)
+    ref = oc.build_kmap(c, 3, stride, transposed)
+    km = sp.build_kmap(coords_dev(c), 3, stride, transposed)
+    for on_outputs, rows_ref in ((False, ref.in_coords), (True, ref.out_coords)):
+        one_ref = oc.build_kmap(rows_ref, 1, 1)
+        got = km.pointwise(on_outputs)
+        want = sp.build_kmap(coords_dev(rows_ref), 1, 1)
+        assert (got.n_in, got.n_out, got.n_pairs()) == (one_ref.n_in, one_ref.n_out, len(rows_ref))
+        np.testing.assert_array_equal(got.export().cpu().numpy(), one_ref.M)
+        np.testing.assert_array_equal(got.export().cpu().numpy(), want.export().cpu().numpy())
+        np.testing.assert_array_equal(got.export_mask().cpu().numpy(), want.export_mask().cpu().numpy())
+        np.testing.assert_array_equal(got.out_coords().cpu().numpy(), rows_ref)
+        (x32, x), (w32, w), (g32, g) = make_layer(one_ref.n_in, one_ref.n_out, 32, 48, 1, "f16", 61)
+        assert norm_err(sp.fwd(x, w, got), x32.astype(np.float64) @ w32[0].astype(np.float64)) <= TOL["f16"]
+        assert norm_err(sp.dgrad(g, w, got), oc.dgrad(g32, w32, one_ref.M, one_ref.n_in)) <= TOL["f16"]
+        assert norm_err(sp.wgrad(x, g, got), oc.wgrad(x32, g32, one_ref.M)) <= 1e-4
+
+
+def test_pointwise_of_empty_and_pending_builds(sp):
+    import torch
+    empty = sp.build_kmap(torch.zeros((0, 4), dtype=torch.int32, device="cuda"), 3, 1)
+    one = empty.pointwise()
+    assert (one.n_in, one.n_out, one.n_pairs()) == (0, 0, 0)
+    c = gen.lidar_scene(97, target_n=1500)
+    km = sp.build_kmap(coords_dev(c), 3, 1, asynchronous=True)
+    np.testing.assert_array_equal(km.pointwise().export().cpu().numpy(), np.arange(len(c), dtype=np.int32)[:, None])
+    bad = sp.build_kmap(coords_dev(np.vstack([c, c[:1]])), 3, 1, asynchronous=True)
+    with pytest.raises(sp.SpconvError) as e:
+        bad.pointwise()
+    assert e.value.status == -3          # SPCONV_EDUP

@@ -50,7 +50,7 @@ class GpuBackend:
         for l in range(5):
             self.sub.append(sp.build_kmap(lvl, 3, 1))
             if l < 4:
-                self.one.append(sp.build_kmap(lvl, 1, 1))
+                self.one.append(self.sub[-1].pointwise())   # 1x1x1 shortcuts stand on the level's validated rows
                 self.down.append(sp.build_kmap(lvl, 3, 2))
                 self.up.append(self.down[-1].transpose())   # the up-convolution pairs with this down-convolution
                 lvl = self.down[-1].out_coords()

@@ -49,6 +49,8 @@ def test_argument_errors_need_no_gpu():
     assert lib.spconv_build_kmap(None, 0, 3, 1, 0, None, None) == -1
     assert lib.spconv_kmap_transpose(None, None, ctypes.byref(out)) == -1 and out.value is None
     assert lib.spconv_kmap_transpose(None, None, None) == -1
+    assert lib.spconv_kmap_pointwise(None, 0, None, ctypes.byref(out)) == -1 and out.value is None
+    assert lib.spconv_kmap_pointwise(None, 0, None, None) == -1
     assert lib.spconv_kmap_status(None, None) == -1
     assert lib.spconv_dgrad(None, None, None, 64, 64, 1, None, None, None) == -1
     assert lib.spconv_wgrad(None, None, None, 64, 64, 1, None, None, None) == -1

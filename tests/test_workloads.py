@@ -64,3 +64,16 @@ def test_features_and_weights_are_exact_in_their_dtype(dtype, eps):
     assert abs(float(w32.std()) - 1.0 / np.sqrt(27 * 16)) < 0.2 / np.sqrt(27 * 16)
     again, _ = gen.round_to_dtype(x32, dtype)
     assert np.array_equal(again, x32)                                # already representable: rounding is idempotent
+
+
+def test_bench_refuses_more_than_one_gpu_and_bad_layer_configs():
+    """bench.py runs on one GPU only and says so; argument errors surface before any GPU work."""
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "one GPU" in (r.stderr + r.stdout)
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "no_such_workload"],
+                       capture_output=True, text=True)
+    assert r.returncode != 0 and "invalid choice" in r.stderr

@@ -18,6 +18,8 @@
 // to whole tiles so that no map access needs a bounds check (Section 3.2).
 #include "common.h"
 
+#include <atomic>
+
 namespace spc {
 namespace {
 
@@ -499,15 +501,15 @@ int launch_igemm(const IgemmParams& p, dim3 grid, hipStream_t st) {
   typedef IgemmSmem<BM, BN, KC, false> SF;
   typedef IgemmSmem<BM, BN, KC, true> SD;
   static_assert(BM * (KC / 8) >= NW * 64, "every thread stages at least one segment of the gathered rows");
-  static bool attr_set = false;
+  static std::atomic<bool> attr_set{false};  // (set twice by racing threads at worst: the calls are idempotent)
   auto fwd = k_igemm<T, BM, BN, KC, NW, false>;
   auto dgr = k_igemm<T, BM, BN, KC, NW, true>;
-  if (!attr_set) {
+  if (!attr_set.load(std::memory_order_acquire)) {
     SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fwd), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)SF::total));
     SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(dgr), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)SD::total));
-    attr_set = true;
+    attr_set.store(true, std::memory_order_release);
   }
   if (p.dgrad)
     hipLaunchKernelGGL(dgr, grid, dim3(NW * 64), SD::total, st, p);

@@ -20,6 +20,8 @@
 //     as whole 16-byte segments.
 #include "common.h"
 
+#include <atomic>
+
 #include <algorithm>
 #include <cstdlib>
 
@@ -344,12 +346,12 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
 
 template <typename T, int KS, int NB, int DEPTH>
 int launch_wave_d(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
-  static size_t attr_bytes = 0;
+  static std::atomic<size_t> attr_bytes{0};  // largest dynamic LDS size announced for this instance so far
   auto fn = k_igemm_wave<T, KS, NB, DEPTH>;
-  if (smem > attr_bytes) {
+  if (smem > attr_bytes.load(std::memory_order_acquire)) {
     SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
-    attr_bytes = smem;
+    attr_bytes.store(smem, std::memory_order_release);
   }
   hipLaunchKernelGGL(fn, grid, dim3(threads), smem, st, p);
   SPC_LAUNCH_CHECK();

@@ -10,6 +10,8 @@
 // coordinates of strided maps into their canonical order.
 #include "common.h"
 
+#include <atomic>
+
 namespace spc {
 namespace {
 
@@ -196,11 +198,11 @@ int scan_u32_inplace(uint32_t* data, int64_t elems, uint32_t* sums, hipStream_t 
     return SPCONV_OK;
   }
   if (elems <= kScanBig) {
-    static bool attr_set = false;
-    if (!attr_set) {
+    static std::atomic<bool> attr_set{false};  // (set twice by racing threads at worst: the calls are idempotent)
+    if (!attr_set.load(std::memory_order_acquire)) {
       SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_scan_tile<kScanBigPer>),
                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)scan_lds_bytes<kScanBigPer>()));
-      attr_set = true;
+      attr_set.store(true, std::memory_order_release);
     }
     hipLaunchKernelGGL((k_scan_tile<kScanBigPer>), dim3(1), dim3(1024), scan_lds_bytes<kScanBigPer>(), st, data,
                        (long long)elems, (unsigned*)nullptr);

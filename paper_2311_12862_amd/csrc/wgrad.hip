@@ -15,6 +15,8 @@
 // in item order, so results are bit-reproducible.
 #include "common.h"
 
+#include <atomic>
+
 namespace spc {
 namespace {
 
@@ -323,13 +325,13 @@ int wgrad_run(spconv_kmap* km, const WgradPlan& wp, const void* feats, const voi
       const unsigned gx = (unsigned)std::min<int64_t>(wp.max_items, std::max<unsigned>(64u, 512u / tiles));
       dim3 grid(gx, (unsigned)ceil_div(C_in, tile), (unsigned)ceil_div(C_out, tile));
       const size_t smem = (size_t)2 * 2 * WG_BK * (tile + 16) * 2;
-      static bool attr_set = false;
-      if (!attr_set) {
+      static std::atomic<bool> attr_set{false};  // (set twice by racing threads at worst: the calls are idempotent)
+      if (!attr_set.load(std::memory_order_acquire)) {
         SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad<_Float16, 128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)8 * WG_BK * 144)));
         SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(k_wgrad<__bf16, 128>),
                                     hipFuncAttributeMaxDynamicSharedMemorySize, (int)((size_t)8 * WG_BK * 144)));
-        attr_set = true;
+        attr_set.store(true, std::memory_order_release);
       }
       if (dtype == SPCONV_F16) {
         if (tile == 32) hipLaunchKernelGGL((k_wgrad<_Float16, 32>), grid, dim3(256), smem, st, p);

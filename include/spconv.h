@@ -101,11 +101,15 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *                  spent on absent neighbours; results are the same up to
  *                  the order of the fp32 additions (which varies from call to
  *                  call).  Needs n_split = 0, else SPCONV_EINVAL;
- *               0: never 3; 1 where it fits and the layer is narrow, else 2.
- *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 128);
+ *               0: never 3; 1 where it fits and either the output is at most two
+ *                  column tiles wide or (column tiles x reduced channels x
+ *                  rows) is small, else 2.
+ *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 64 or
+ *               128, from the row count and the channel counts);
  *               pairs per workgroup of kernel 3: 64 or 128 (0 = 64).
  *   tile_n      output channels per workgroup: 16, 32, 64 (kernel 1) or 32, 64,
- *               128 (kernels 2 and 3); 0 = chosen from the channel counts.
+ *               128 (kernels 2 and 3); 0 = chosen from the channel counts (and,
+ *               for kernel 2, from how many workgroups the rows give).
  *   wgrad_pairs target number of (output,input) pairs per wgrad workgroup
  *               (0 = chosen from the pair count); ignored by fwd / dgrad.
  */

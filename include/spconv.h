@@ -148,9 +148,10 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
 /* The kmap of the transposed convolution that pairs with km: the same (input, output) pairs with
  * the two roles exchanged, i.e. exactly what spconv_build_kmap returns for the same rows with
  * `transposed` flipped, without building a table or probing again (one scatter pass over km's
- * map plus copies).  An encoder-decoder network derives each up-convolution's kmap from its
- * down-convolution this way.  *out is independent of km (own buffers; destroy both).  `stream`
- * must be ordered after the work that built km; an unresolved asynchronous build is resolved
+ * map, unless km's dgrad has made it already; nothing is copied).  An encoder-decoder network derives each up-convolution's kmap from its
+ * down-convolution this way.  *out shares km's tables and coordinate sets (reference-counted: destroy both
+ * kmaps, in either order) and the plans cached on them, so the rule against concurrent calls on one kmap
+ * covers the pair.  `stream` must be ordered after the work that built km; an unresolved asynchronous build is resolved
  * first (one synchronisation) and its error, if any, is returned.  Errors: EINVAL, ENOMEM,
  * EHIP, ERANGE / EDUP of a pending build; on error *out is NULL. */
 SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap** out);

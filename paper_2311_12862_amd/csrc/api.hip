@@ -371,9 +371,11 @@ SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
   SPC_HIP(hipDeviceSynchronize());
   km->out_side.plans.clear();
   km->in_side.plans.clear();
-  km->in_side.map.release();
-  km->in_side.mask.release();
-  km->in_side.ready = false;
+  if (km->in_ref.use_count() == 1) {  // (a transposed partner uses this table as its own map)
+    km->in_side.map.release();
+    km->in_side.mask.release();
+    km->in_side.ready = false;
+  }
   km->wplans.clear();
   return SPCONV_OK;
 }

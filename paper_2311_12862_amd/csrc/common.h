@@ -115,9 +115,26 @@ struct spconv_kmap {
   int64_t n_in = 0, n_out = 0, n_pairs = -1;
   hipStream_t build_stream = nullptr;
   hipStream_t last_stream = nullptr;  // stream of the most recent call that used this kmap
-  spc::DevBuf in_coords, out_coords;
-  spc::SideMap out_side;  // M: rows = n_out, entries index input rows
-  spc::SideMap in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)
+  // coordinate sets, reference-counted like the tables (a transposed partner holds the same two)
+  std::shared_ptr<spc::DevBuf> in_coords_ref, out_coords_ref;
+  spc::DevBuf& in_coords;
+  spc::DevBuf& out_coords;
+  // The two tables are reference-counted: a kmap and the kmap of its paired transposed
+  // convolution hold the same two tables with the roles exchanged (spconv_kmap_transpose).
+  std::shared_ptr<spc::SideMap> out_ref, in_ref;
+  spc::SideMap& out_side;  // M: rows = n_out, entries index input rows
+  spc::SideMap& in_side;   // T: rows = n_in, T[j][k] = n  <=>  M[n][k] = j (built on demand)
+  spconv_kmap()
+      : in_coords_ref(std::make_shared<spc::DevBuf>()), out_coords_ref(std::make_shared<spc::DevBuf>()),
+        in_coords(*in_coords_ref), out_coords(*out_coords_ref), out_ref(std::make_shared<spc::SideMap>()),
+        in_ref(std::make_shared<spc::SideMap>()), out_side(*out_ref), in_side(*in_ref) {}
+  spconv_kmap(std::shared_ptr<spc::SideMap> out_table, std::shared_ptr<spc::SideMap> in_table,
+              std::shared_ptr<spc::DevBuf> in_rows, std::shared_ptr<spc::DevBuf> out_rows)
+      : in_coords_ref(std::move(in_rows)), out_coords_ref(std::move(out_rows)), in_coords(*in_coords_ref),
+        out_coords(*out_coords_ref), out_ref(std::move(out_table)), in_ref(std::move(in_table)), out_side(*out_ref),
+        in_side(*in_ref) {}
+  spconv_kmap(const spconv_kmap&) = delete;
+  spconv_kmap& operator=(const spconv_kmap&) = delete;
   std::map<int64_t, std::unique_ptr<spc::WgradPlan>> wplans;  // by target_pairs
   spc::DevBuf scratch;    // split partial sums / wgrad partial tiles
   // build whose status was not read yet: the pinned block the probe kernel publishes flags and

@@ -1025,7 +1025,22 @@ int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap
 int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out) {
   if (src->pending) SPC_TRY(kmap_status(src, st));  // a failed build has no transpose
   SPC_TRY(kmap_build_in_side(src, st));
-  std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
+  // The transposed convolution's output-stationary table is the source's input-side table and the
+  // other way round, and its coordinate sets are the source's with the roles exchanged: the two
+  // kmaps share all four buffers (and whatever plans get cached on the tables); nothing is copied.
+  // A kmap keeps the caller's rows and, for stride > 1, the coarse set; with stride 1 the two sets
+  // are one and only the caller's rows are kept (in_coords of a forward kmap, out_coords of a
+  // transposed one), the other buffer stays empty.
+  auto none = []() { return std::make_shared<DevBuf>(); };
+  std::shared_ptr<DevBuf> in_rows, out_rows;
+  if (!src->transposed) {
+    out_rows = src->in_coords_ref;
+    in_rows = src->stride > 1 ? src->out_coords_ref : none();
+  } else {
+    in_rows = src->out_coords_ref;
+    out_rows = src->stride > 1 ? src->in_coords_ref : none();
+  }
+  std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap(src->in_ref, src->out_ref, in_rows, out_rows));
   if (!km) return SPCONV_ENOMEM;
   km->K = src->K;
   km->V = src->V;
@@ -1036,36 +1051,6 @@ int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out) {
   km->n_pairs = src->n_pairs;
   km->build_stream = st;
   km->last_stream = st;
-  const int V = km->V;
-  auto copy_side = [&](SideMap& dst, const SideMap& from) -> int {
-    dst.rows = from.rows;
-    dst.rows_pad = from.rows_pad;
-    const size_t map_bytes = (size_t)from.rows_pad * V * sizeof(int), mask_bytes = (size_t)from.rows_pad * sizeof(unsigned);
-    SPC_TRY(dst.map.alloc(map_bytes));
-    SPC_TRY(dst.mask.alloc(mask_bytes));
-    SPC_HIP(hipMemcpyAsync(dst.map.p, from.map.p, map_bytes, hipMemcpyDeviceToDevice, st));
-    SPC_HIP(hipMemcpyAsync(dst.mask.p, from.mask.p, mask_bytes, hipMemcpyDeviceToDevice, st));
-    dst.ready = true;
-    return SPCONV_OK;
-  };
-  SPC_TRY(copy_side(km->out_side, src->in_side));
-  SPC_TRY(copy_side(km->in_side, src->out_side));
-  auto copy_rows = [&](DevBuf& dst, const DevBuf& from, int64_t rows) -> int {
-    if (rows == 0 || !from.p) return dst.alloc(16);
-    SPC_TRY(dst.alloc((size_t)rows * 16));
-    SPC_HIP(hipMemcpyAsync(dst.p, from.p, (size_t)rows * 16, hipMemcpyDeviceToDevice, st));
-    return SPCONV_OK;
-  };
-  // A kmap keeps the caller's rows and, for stride > 1, the coarse set; with stride 1 the two
-  // sets are one and only the caller's rows are kept (in_coords of a forward kmap, out_coords
-  // of a transposed one).
-  if (!src->transposed) {
-    SPC_TRY(copy_rows(km->out_coords, src->in_coords, src->n_in));
-    if (src->stride > 1) SPC_TRY(copy_rows(km->in_coords, src->out_coords, src->n_out));
-  } else {
-    SPC_TRY(copy_rows(km->in_coords, src->out_coords, src->n_out));
-    if (src->stride > 1) SPC_TRY(copy_rows(km->out_coords, src->in_coords, src->n_in));
-  }
   *out = km.release();
   return SPCONV_OK;
 }

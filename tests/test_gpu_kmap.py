@@ -262,7 +262,7 @@ def test_transpose_of_empty_and_pending_builds(sp):
     assert e.value.status == -3          # SPCONV_EDUP
 
 
-@pytest.mark.parametrize("stride,transposed", [(1, False), (2, False), (2, True), (3, False)])
+@pytest.mark.parametrize("stride,transposed", [(1, False), (1, True), (2, False), (2, True), (3, False)])
 def test_pointwise_equals_a_k1_build(sp, stride, transposed):
     """spconv_kmap_pointwise: the K = 1 kmap over either row set of a kmap is what a K = 1 build on
     those rows returns (map, mask, coordinates, sizes), and a 1x1x1 layer through it is X . W[0]."""
@@ -298,3 +298,21 @@ def test_pointwise_of_empty_and_pending_builds(sp):
     with pytest.raises(sp.SpconvError) as e:
         bad.pointwise()
     assert e.value.status == -3          # SPCONV_EDUP
+
+
+def test_transposed_partner_outlives_its_source(sp):
+    """A kmap and its transpose share their tables by reference count: either may be destroyed
+    first, and dropping the source's plans leaves the partner's map intact."""
+    c = gen.lidar_scene(98, target_n=1800)
+    ref_t = oc.build_kmap(c, 3, 2, True)
+    down = sp.build_kmap(coords_dev(c), 3, 2)
+    up = down.transpose()
+    down.drop_plans()
+    np.testing.assert_array_equal(up.export().cpu().numpy(), ref_t.M)
+    down.destroy()
+    np.testing.assert_array_equal(up.export().cpu().numpy(), ref_t.M)
+    np.testing.assert_array_equal(up.out_coords().cpu().numpy(), ref_t.out_coords)
+    again = up.transpose()          # back to the strided map, from the partner alone
+    np.testing.assert_array_equal(again.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)
+    up.destroy()
+    np.testing.assert_array_equal(again.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)

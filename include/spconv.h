@@ -203,7 +203,10 @@ SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, voi
  * (Section 6.1 separates them the same way).  May synchronise the stream. */
 SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_config* cfg_or_null, void* stream);
 
-/* Drops every cached plan (not the map itself), so that mapping can be timed again. */
+/* Drops every cached plan (not the map itself), so that mapping can be timed again: the sorted
+ * and reordered maps of both tables, the pair lists, and the input-side table unless a transposed
+ * partner (spconv_kmap_transpose) uses it as its map.  Plans cached on tables shared with a partner
+ * are dropped for both.  Synchronises the device. */
 SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km);
 
 /* Permutation of split `split` of the cached plan of (op, cfg): int32

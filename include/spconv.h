@@ -69,7 +69,9 @@ typedef enum spconv_status {
   SPCONV_EDUP = -3,    /* two input rows carry the same coordinate (Section 2 assumes Unique was applied) */
   SPCONV_ENOMEM = -4,  /* device or host allocation failed */
   SPCONV_ESHAPE = -5,  /* channel counts or row counts do not fit the kmap */
-  SPCONV_EHIP = -6     /* a HIP call failed; see spconv_last_hip_error() */
+  SPCONV_EHIP = -6,    /* a HIP call failed; see spconv_last_hip_error() */
+  SPCONV_ENOPLAN = -7, /* spconv_fwd_noalloc: the plan of this configuration was not prepared */
+  SPCONV_ELIMIT = -8   /* spconv_fwd_noalloc: partial sums exceed SPCONV_NOALLOC_SCRATCH_BYTES */
 } spconv_status;
 
 typedef enum spconv_dtype { SPCONV_F32 = 0, SPCONV_F16 = 1, SPCONV_BF16 = 2 } spconv_dtype;
@@ -232,6 +234,23 @@ SPCONV_API void spconv_kmap_destroy(spconv_kmap* km);
  * of 8 (F16/BF16) or 4 (F32).  km is not const because plans are cached. */
 SPCONV_API int spconv_fwd(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out,
                spconv_dtype dtype, const spconv_config* cfg_or_null, void* out, void* stream);
+
+/* spconv_fwd for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc.  Same arguments, same kernels and same result as
+ * spconv_fwd, but the call makes no allocation of any kind (no hipMalloc / hipFree, no allocator
+ * callback, no pool):
+ *   - the plan of cfg must exist already, made by spconv_kmap_prepare(km, SPCONV_OP_FWD, cfg) or by
+ *     an earlier spconv_fwd with the same cfg; otherwise SPCONV_ENOPLAN.  kernel = 3 (fetch on
+ *     demand) is refused with SPCONV_EINVAL;
+ *   - the fp32 partial sums of n_split >= 2 (n_split * n_out * C_out * 4 bytes) go to a fixed
+ *     array of SPCONV_NOALLOC_SCRATCH_BYTES that every GPU the library runs on holds until the
+ *     process ends; a larger need is refused with SPCONV_ELIMIT and nothing is launched.
+ * All calls on one GPU share that array and it keeps the previous call's contents (every element a
+ * call reads it has written before, so nothing needs clearing); two calls that overlap on one GPU -
+ * different streams, or several host threads - race on it and must be ordered by the caller. */
+#define SPCONV_NOALLOC_SCRATCH_BYTES (64u << 20)
+SPCONV_API int spconv_fwd_noalloc(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out,
+                       spconv_dtype dtype, const spconv_config* cfg_or_null, void* out, void* stream);
 
 /* Input gradient of Equation 1 (the dgrad kernel of Section 4.2):
  *   din[j] = sum over (n, k) with M[n][k] = j of dout[n] . W[k]^T.

@@ -74,6 +74,7 @@ def load_library():
         "spconv_kmap_mac_units": (i32, [vp, i32, cfgp, C.POINTER(i64), C.POINTER(i64), vp]),
         "spconv_kmap_destroy": (None, [vp]),
         "spconv_fwd": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
+        "spconv_fwd_noalloc": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_dgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_wgrad": (i32, [vp, vp, vp, i32, i32, i32, cfgp, vp, vp]),
         "spconv_tune": (i32, [vp, i32, i32, i32, i32, i32, cfgp, C.POINTER(C.c_float), vp]),
@@ -269,6 +270,20 @@ def fwd(feats, weights, kmap: KMap, cfg: Config | None = None, out=None, stream=
         out = torch.empty((kmap.n_out, c_out), dtype=feats.dtype, device=feats.device)
     _check(load_library().spconv_fwd(_ptr(feats), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
                                      _ptr(out), _stream(stream)), "spconv_fwd")
+    return out
+
+
+def fwd_noalloc(feats, weights, kmap: KMap, out, cfg: Config | None = None, stream=None):
+    """spconv_fwd_noalloc: spconv_fwd into the caller's `out` on a prepared plan, without any allocation."""
+    dt = _conv_args(feats, weights, kmap, kmap.n_in)
+    V, c_in, c_out = weights.shape
+    if V != kmap.V or c_in != feats.shape[1]:
+        raise SpconvError(-5, "weights shape does not fit")
+    _dev_tensor(out, feats.dtype)
+    if tuple(out.shape) != (kmap.n_out, c_out):
+        raise SpconvError(-5, "out shape does not fit")
+    _check(load_library().spconv_fwd_noalloc(_ptr(feats), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
+                                             _ptr(out), _stream(stream)), "spconv_fwd_noalloc")
     return out
 
 

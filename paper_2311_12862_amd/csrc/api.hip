@@ -158,8 +158,36 @@ int64_t auto_wgrad_pairs(spconv_kmap* km, int C_in, int C_out) {
   return std::max<int64_t>(1024, ceil_div(pairs, want_items));
 }
 
+// ---- the fixed scratch array of the entry point that allocates nothing --------------------
+// Split partial sums of spconv_fwd_noalloc live here instead of in a buffer of the kmap.  In
+// host code the array's name is only a stand-in: the device address comes from
+// hipGetSymbolAddress, once per device (each GPU holds its own copy), with that device current.
+constexpr size_t kStaticScratchBytes = (size_t)SPCONV_NOALLOC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+std::mutex g_scratch_mu;
+void* g_scratch_ptr[kMaxDevices] = {};
+
+int static_scratch(void** out) {
+  int dev = -1;
+  SPC_HIP(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return SPCONV_EINVAL;
+  std::lock_guard<std::mutex> lk(g_scratch_mu);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    SPC_HIP(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return SPCONV_EHIP;
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return SPCONV_OK;
+}
+
+// prepared_only: the call may not allocate.  Plans are looked up, never built (SPCONV_ENOPLAN when
+// missing), and split partial sums go to the fixed scratch array (SPCONV_ELIMIT beyond its size).
 int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap* km, int C_in, int C_out,
-                 spconv_dtype dtype, const spconv_config* cfg, void* dst, hipStream_t st) {
+                 spconv_dtype dtype, const spconv_config* cfg, void* dst, hipStream_t st,
+                 bool prepared_only = false) {
   if (!km || !dtype_ok(dtype)) return SPCONV_EINVAL;
   SPC_TRY(check_channels(C_in, C_out, dtype));
   km->last_stream = st;
@@ -169,6 +197,7 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
   if (c.kernel == 3) {  // fetch-on-demand dataflow over the weight-stationary pair lists
+    if (prepared_only) return SPCONV_EINVAL;
     const int dgrad = op == SPCONV_OP_DGRAD;
     if (!fod_supported(km, dgrad, C_in, C_out, dtype)) return SPCONV_EINVAL;
     WgradPlan* wp = nullptr;
@@ -184,7 +213,12 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
     return fod_run(km, *wp, a, c.tile_m, dst, st);
   }
   OpSide os;
-  SPC_TRY(side_for(km, op, st, &os));
+  if (prepared_only) {
+    if (op != SPCONV_OP_FWD) return SPCONV_EINVAL;
+    os = {&km->out_side, 0, 0};
+  } else {
+    SPC_TRY(side_for(km, op, st, &os));
+  }
   const int c_red = os.dgrad ? C_out : C_in;
   const int c_cols = os.dgrad ? C_in : C_out;
   if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
@@ -212,7 +246,14 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   }
   if (!wave && c.tile_n == 16) return SPCONV_EINVAL;
   IgemmPlan* plan = nullptr;
-  SPC_TRY(plan_get(km, *os.side, c.n_split, wave ? 16 : c.tile_m, st, &plan));
+  if (prepared_only) {
+    if (c.n_split > km->V) return SPCONV_EINVAL;
+    auto it = os.side->plans.find(std::make_pair((int)c.n_split, wave ? 16 : (int)c.tile_m));
+    if (it == os.side->plans.end()) return SPCONV_ENOPLAN;
+    plan = it->second.get();
+  } else {
+    SPC_TRY(plan_get(km, *os.side, c.n_split, wave ? 16 : c.tile_m, st, &plan));
+  }
   IgemmArgs a{};
   a.feats = src;
   a.weights = weights;
@@ -229,8 +270,16 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
     a.tile_n = 64;
   const int c_dst = os.dgrad ? C_in : C_out;
   if (plan->parts > 1) {
-    SPC_TRY(km->scratch.reserve((size_t)plan->parts * plan->rows * c_dst * sizeof(float)));
-    a.partial = km->scratch.as<float>();
+    const size_t need = (size_t)plan->parts * plan->rows * c_dst * sizeof(float);
+    if (prepared_only) {
+      if (need > kStaticScratchBytes) return SPCONV_ELIMIT;
+      void* ptr = nullptr;
+      SPC_TRY(static_scratch(&ptr));
+      a.partial = reinterpret_cast<float*>(ptr);
+    } else {
+      SPC_TRY(km->scratch.reserve(need));
+      a.partial = km->scratch.as<float>();
+    }
     a.out = nullptr;
     SPC_TRY(wave ? igemm_wave_run(km, *os.side, *plan, a, st) : igemm_run(km, *os.side, *plan, a, st));
     return split_reduce(a.partial, plan->parts, plan->rows, c_dst, dtype, dst, st);
@@ -428,6 +477,11 @@ SPCONV_API int spconv_fwd(const void* feats, const void* weights, spconv_kmap* k
                const spconv_config* cfg, void* out, void* stream) {
   StreamScope scope((hipStream_t)stream);
   return run_igemm_op(SPCONV_OP_FWD, feats, weights, km, C_in, C_out, dtype, cfg, out, (hipStream_t)stream);
+}
+
+SPCONV_API int spconv_fwd_noalloc(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out,
+                                  spconv_dtype dtype, const spconv_config* cfg, void* out, void* stream) {
+  return run_igemm_op(SPCONV_OP_FWD, feats, weights, km, C_in, C_out, dtype, cfg, out, (hipStream_t)stream, true);
 }
 
 SPCONV_API int spconv_dgrad(const void* dout, const void* weights, spconv_kmap* km, int C_in, int C_out, spconv_dtype dtype,
@@ -819,6 +873,8 @@ SPCONV_API const char* spconv_strerror(int status) {
     case SPCONV_ENOMEM: return "out of memory";
     case SPCONV_ESHAPE: return "channel or row counts do not fit";
     case SPCONV_EHIP: return "HIP call failed";
+    case SPCONV_ENOPLAN: return "no prepared plan for this configuration (call spconv_kmap_prepare first)";
+    case SPCONV_ELIMIT: return "partial sums exceed the fixed scratch array of the allocation-free entry point";
   }
   return "unknown status";
 }

@@ -114,6 +114,13 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *               for kernel 2, from how many workgroups the rows give).
  *   wgrad_pairs target number of (output,input) pairs per wgrad workgroup
  *               (0 = chosen from the pair count); ignored by fwd / dgrad.
+ *   flags       SPCONV_FLAG_SLABS: the sort key of every row of a sorted map (n_split >= 1)
+ *               starts with the row's spatial slab (eight equal slabs along the longest axis
+ *               of the coordinates), and the kernel with resident weights hands each of the
+ *               chip's eight L2 domains a contiguous range of that order, so that its gathers
+ *               stay within about one eighth of the input.  Any visiting order gives the same
+ *               result; this one trades some lock-step redundancy for less traffic beyond
+ *               L2.  Without the flag the library uses slabs from 2^20 rows on.
  */
 typedef struct spconv_config {
   int32_t n_split;
@@ -121,8 +128,12 @@ typedef struct spconv_config {
   int32_t tile_n;
   int32_t wgrad_pairs;
   int32_t kernel;
-  int32_t reserved[3];
+  int32_t flags;
+  int32_t reserved[2];
 } spconv_config;
+
+/* spconv_config.flags */
+#define SPCONV_FLAG_SLABS 1 /* sorted maps (n_split >= 1): see above */
 
 /* Kernel-map construction ("mapping operations", Sections 3.1, 4.2, 6.2).
  *   coords      device, int32 [N][4] = (b, x, y, z), unique rows.

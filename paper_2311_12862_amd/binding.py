@@ -11,6 +11,7 @@ import os
 import torch
 
 OP_FWD, OP_DGRAD, OP_WGRAD = 0, 1, 2
+FLAG_SLABS = 1
 _DTYPES = {torch.float32: 0, torch.float16: 1, torch.bfloat16: 2}
 
 
@@ -26,11 +27,11 @@ class SpconvError(RuntimeError):
 class Config(C.Structure):
     """Mirror of spconv_config (zero = library defaults)."""
     _fields_ = [("n_split", C.c_int32), ("tile_m", C.c_int32), ("tile_n", C.c_int32),
-                ("wgrad_pairs", C.c_int32), ("kernel", C.c_int32), ("reserved", C.c_int32 * 3)]
+                ("wgrad_pairs", C.c_int32), ("kernel", C.c_int32), ("flags", C.c_int32), ("reserved", C.c_int32 * 2)]
 
     def __repr__(self):
         return (f"Config(n_split={self.n_split}, tile_m={self.tile_m}, tile_n={self.tile_n}, "
-                f"wgrad_pairs={self.wgrad_pairs}, kernel={self.kernel})")
+                f"wgrad_pairs={self.wgrad_pairs}, kernel={self.kernel}" + (f", flags={self.flags}" if self.flags else "") + ")")
 
 
 class LayerShape(C.Structure):

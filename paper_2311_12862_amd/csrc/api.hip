@@ -117,7 +117,7 @@ int resolve_config(const spconv_config* cfg, spconv_dtype dtype, spconv_config* 
   if (c.tile_m == 0) c.tile_m = 128;
   if (c.tile_m != 64 && c.tile_m != 128 && c.tile_m != 256) return SPCONV_EINVAL;
   if (c.tile_n != 0 && c.tile_n != 16 && c.tile_n != 32 && c.tile_n != 64 && c.tile_n != 128) return SPCONV_EINVAL;
-  if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 3) return SPCONV_EINVAL;
+  if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 3 || (c.flags & ~SPCONV_FLAG_SLABS)) return SPCONV_EINVAL;
   if (c.kernel == 3) {  // fetch-on-demand: unsorted pair lists, tiles of 64 or 128 pairs, 16-bit types
     if (cfg->tile_m == 0) c.tile_m = 64;
     if (dtype == SPCONV_F32 || c.n_split != 0 || c.tile_m == 256 || c.tile_n == 16) return SPCONV_EINVAL;
@@ -128,6 +128,11 @@ int resolve_config(const spconv_config* cfg, spconv_dtype dtype, spconv_config* 
   }
   *out = c;
   return SPCONV_OK;
+}
+
+// Tile height of the plan a configuration uses, as the plan cache keys it.
+int plan_tile(const spconv_config& c, bool wave) {
+  return (wave ? 16 : c.tile_m) | ((c.flags & SPCONV_FLAG_SLABS) && c.n_split > 0 ? kPlanSlabs : 0);
 }
 
 // Which table an op walks, and with which weight indexing.
@@ -248,11 +253,11 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   IgemmPlan* plan = nullptr;
   if (prepared_only) {
     if (c.n_split > km->V) return SPCONV_EINVAL;
-    auto it = os.side->plans.find(std::make_pair((int)c.n_split, wave ? 16 : (int)c.tile_m));
+    auto it = os.side->plans.find(std::make_pair((int)c.n_split, plan_tile(c, wave)));
     if (it == os.side->plans.end()) return SPCONV_ENOPLAN;
     plan = it->second.get();
   } else {
-    SPC_TRY(plan_get(km, *os.side, c.n_split, wave ? 16 : c.tile_m, st, &plan));
+    SPC_TRY(plan_get(km, *os.side, c.n_split, plan_tile(c, wave), st, &plan));
   }
   IgemmArgs a{};
   a.feats = src;
@@ -411,7 +416,7 @@ SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_c
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
-  return plan_get(km, *os.side, c.n_split, c.kernel == 1 ? 16 : c.tile_m, st, &plan);
+  return plan_get(km, *os.side, c.n_split, plan_tile(c, c.kernel == 1), st, &plan);
 }
 
 SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
@@ -440,7 +445,7 @@ SPCONV_API int spconv_kmap_export_perm(spconv_kmap* km, spconv_op op, const spco
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
-  SPC_TRY(plan_get(km, *os.side, c.n_split, c.tile_m, st, &plan));
+  SPC_TRY(plan_get(km, *os.side, c.n_split, plan_tile(c, false), st, &plan));
   if (plan->rows == 0) return SPCONV_OK;
   SPC_HIP(hipMemcpyAsync(dst, plan->perm.as<int>() + (size_t)split * plan->rows_pad,
                          (size_t)plan->rows * sizeof(int32_t), hipMemcpyDeviceToDevice, st));
@@ -463,7 +468,7 @@ SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
   IgemmPlan* plan = nullptr;
-  SPC_TRY(plan_get(km, *os.side, c.n_split, c.tile_m, st, &plan));
+  SPC_TRY(plan_get(km, *os.side, c.n_split, plan_tile(c, false), st, &plan));
   return plan_mac_units(km, *os.side, plan, 16, st, executed);
 }
 

@@ -14,6 +14,7 @@ namespace spc {
 constexpr int kMaxSplit = 4;
 constexpr int kRowPad = 256;  // map rows are padded to a multiple of the largest tile_m
 constexpr int kWave = 64;
+constexpr int kPlanSlabs = 0x10000;  // or-ed into the tile height of a plan key: sort keys start with a spatial slab
 
 int hip_fail(hipError_t e, const char* what, const char* file, int line);
 #define SPC_HIP(expr)                                                        \
@@ -82,6 +83,7 @@ struct IgemmPlan {
   DevBuf maps;      // reordered maps, part i: int32 [rows_pad][width[i]]  (unused when n_split == 0)
   DevBuf perm;      // int32 [parts][rows_pad]                              (unused when n_split == 0)
   DevBuf tilemask;  // uint32 [parts][n_tiles] bits relative to lo[i]
+  bool slabs = false;  // sort keys start with a spatial slab: contiguous ranges of the order are spatially compact
 };
 
 struct WgradItem {
@@ -173,6 +175,7 @@ int radix_sort_u64(uint64_t* key_a, uint64_t* key_b, int64_t n, uint64_t varying
                    hipStream_t st, int* in_b);
 
 // ---- plan.hip
+// tile_m may carry kPlanSlabs (a plan of its own in the cache)
 int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out);
 int plan_mac_units(spconv_kmap* km, SideMap& side, IgemmPlan* plan, int group_rows, hipStream_t st,
                    int64_t* executed);

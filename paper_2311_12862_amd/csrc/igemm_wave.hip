@@ -64,6 +64,8 @@ struct WaveParams {
   int slab_bytes;  // per-wave LDS slab: map rows, then the output staging tile
   int map_bytes;   // size of the map part of the slab
   unsigned feats_bytes;  // size of the gathered tensor, < 2^32 - 16 KiB
+  int quad;     // gathers issued by quads of lanes per row and permuted to the operand layout
+  int xcd_ranges;  // blocks are dealt to the 8 XCDs as contiguous ranges (gridDim.x is a multiple of 8)
 };
 
 // physical 16-byte chunk of logical chunk q in weight row n (row pitch = 4*KS chunks)
@@ -86,11 +88,12 @@ __device__ __forceinline__ uint4 buf_load16(__amdgpu_buffer_rsrc_t r, unsigned b
   return make_uint4(v.x, v.y, v.z, v.w);
 }
 
+constexpr int kLoopUnroll = 3;  // trips through the DEPTH slots per loop iteration (see the offset loop)
 constexpr int kMapVecs = 7;  // ceil(16 rows * 27 offsets / 64 lanes)
 
 // DEPTH = offsets whose A-fragments are in flight per wave.  DEPTH 8 needs more than the 128
 // registers a 16-wave workgroup leaves per lane, so it runs with 8 waves.
-template <typename T, int KS, int NB, int DEPTH>
+template <typename T, int KS, int NB, int DEPTH, bool QUAD>
 __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const WaveParams p) {
   constexpr int BN = NB * 16;
   constexpr int ROW_CHUNKS = 4 * KS;        // 16-byte chunks per weight row
@@ -118,8 +121,17 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   // blocks go first and the tail of the kernel is made of light ones).  A wave's first ticket is
   // its index; further ones come from a counter in LDS.
   __shared__ unsigned next_ticket;
-  const int nj = p.n_blocks > blockIdx.x ? (int)((p.n_blocks - blockIdx.x + gridDim.x - 1) / gridDim.x) : 0;
-  auto block_of = [&](int t) { return (long long)(nj - 1 - t) * gridDim.x + blockIdx.x; };
+  // With p.xcd_ranges the blocks are cut into eight contiguous ranges, one per XCD (workgroups go
+  // to the XCDs round-robin by their index), and a workgroup takes every (gridDim.x / 8)-th block
+  // of its XCD's range: with rows whose sort key starts with a spatial slab, an XCD's gathers stay
+  // within one eighth of the input, which its 4 MB L2 holds.
+  const int n_rng = p.xcd_ranges ? 8 : 1;
+  const int rng = p.xcd_ranges ? (int)(blockIdx.x & 7) : 0;
+  const int wi = p.xcd_ranges ? (int)(blockIdx.x >> 3) : (int)blockIdx.x;  // workgroup within the range
+  const int wpr = (int)gridDim.x / n_rng;                                    // workgroups per range
+  const long long rlo = p.n_blocks * rng / n_rng, rhi = p.n_blocks * (rng + 1) / n_rng;
+  const int nj = rhi - rlo > wi ? (int)((rhi - rlo - wi + wpr - 1) / wpr) : 0;
+  auto block_of = [&](int t) { return rlo + (long long)(nj - 1 - t) * wpr + wi; };
   const bool has_work = wave < nj;
   if (tid == 0) next_ticket = (unsigned)n_waves;
   const unsigned row_bytes = (unsigned)c_red * 2u;
@@ -130,13 +142,22 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   T* stage = reinterpret_cast<T*>(slab + p.map_bytes);
 
   // per-lane constants of the offset loop
+  // With QUAD a gathered row is loaded by a quad of adjacent lanes (lane / 4 = row of the block,
+  // lane % 4 = 16-byte chunk of the k-step): the four requests of a quad fall into one cache line
+  // and travel as one, where the MFMA operand layout itself (lane % 16 = row) sends sixteen rows
+  // per quarter-wave and every 16-byte piece on its own (measured on random 128-byte rows out of
+  // an L2-resident array: 21 TB/s against 8 TB/s).  consume() then moves each dword to the lane
+  // the MFMA wants it in with one cross-lane permute (8 per offset: they pay on bitmask-sorted
+  // maps, whose blocks hold few absent rows, and cost more than they save on unsorted ones).
   constexpr unsigned kAbsent = 0xFFFF0000u;  // byte offset that is out of range with any lane offset added
-  const unsigned lane_map = (unsigned)(arow * width) * 4u;  // this lane's map row in the slab
-  unsigned lane_col[KS];  // this lane's 8 channels within a gathered row (bytes), or out of range
+  const int grow = QUAD ? lane >> 2 : arow, gq = QUAD ? lane & 3 : aq;  // gather role: block row, chunk of a k-step
+  const unsigned lane_map = (unsigned)(grow * width) * 4u;  // this lane's map row in the slab
+  const int frag_src = (4 * arow + aq) * 4;  // (byte address of) the lane that gathered this lane's MFMA fragment
+  unsigned lane_col[KS];  // the 8 channels this lane gathers of a row (bytes), or out of range
   unsigned lane_b[KS];    // this lane's weight chunk within an offset's slice (bytes, first 16 columns)
 #pragma unroll
   for (int ks = 0; ks < KS; ++ks) {
-    const unsigned col = (unsigned)(ks * 4 + aq) * 8u;
+    const unsigned col = (unsigned)(ks * 4 + gq) * 8u;
     lane_col[ks] = col < (unsigned)c_red ? col * 2u : 0x80000000u;
     lane_b[ks] = (unsigned)(arow * ROW_HALFS + swz<KS>(ks * 4 + aq, arow) * 8) * 2u;
   }
@@ -287,10 +308,17 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       const unsigned char* wk = smem + (unsigned)cc[s] * (unsigned)(BN * ROW_HALFS * 2);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
+        uint4 af = fr[s][ks];
+        if constexpr (QUAD) {  // gather layout -> MFMA A-fragment layout
+          af.x = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].x);
+          af.y = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].y);
+          af.z = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].z);
+          af.w = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].w);
+        }
 #pragma unroll
         for (int nb = 0; nb < NB; ++nb) {
           const uint4 bf = *reinterpret_cast<const uint4*>(wk + lane_b[ks] + nb * (16 * ROW_HALFS * 2));
-          acc[nb] = MfmaW<T>::run(fr[s][ks], bf, acc[nb]);
+          acc[nb] = MfmaW<T>::run(af, bf, acc[nb]);
         }
       }
     };
@@ -299,10 +327,13 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
     // bookkeeping at the loop head sees only the steady state: DEPTH - 1 slots in flight.
     for (;;) {
 #pragma unroll
-      for (int s = 0; s < DEPTH; ++s) {
-        if (cc[s] < 0) goto offsets_done;
-        consume(s);
-        issue(s);
+      for (int rep = 0; rep < kLoopUnroll; ++rep) {
+#pragma unroll
+        for (int s = 0; s < DEPTH; ++s) {
+          if (cc[s] < 0) goto offsets_done;
+          consume(s);
+          issue(s);
+        }
       }
     }
   offsets_done:
@@ -344,10 +375,10 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   }
 }
 
-template <typename T, int KS, int NB, int DEPTH>
-int launch_wave_d(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+template <typename T, int KS, int NB, int DEPTH, bool QUAD>
+int launch_wave_q(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
   static std::atomic<size_t> attr_bytes{0};  // largest dynamic LDS size announced for this instance so far
-  auto fn = k_igemm_wave<T, KS, NB, DEPTH>;
+  auto fn = k_igemm_wave<T, KS, NB, DEPTH, QUAD>;
   if (smem > attr_bytes.load(std::memory_order_acquire)) {
     SPC_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(fn), hipFuncAttributeMaxDynamicSharedMemorySize,
                                 (int)smem));
@@ -358,9 +389,17 @@ int launch_wave_d(const WaveParams& p, dim3 grid, int threads, size_t smem, hipS
   return SPCONV_OK;
 }
 
+template <typename T, int KS, int NB, int DEPTH>
+int launch_wave_d(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
+  if (p.quad) return launch_wave_q<T, KS, NB, DEPTH, true>(p, grid, threads, smem, st);
+  return launch_wave_q<T, KS, NB, DEPTH, false>(p, grid, threads, smem, st);
+}
+
 template <typename T, int KS, int NB>
 int launch_wave(const WaveParams& p, dim3 grid, int threads, size_t smem, hipStream_t st) {
-  if (threads <= 512 && KS <= 2) return launch_wave_d<T, KS, NB, 8>(p, grid, threads, smem, st);
+  if constexpr (KS <= 2) {
+    if (threads <= 512) return launch_wave_d<T, KS, NB, 8>(p, grid, threads, smem, st);
+  }
   return launch_wave_d<T, KS, NB, 4>(p, grid, threads, smem, st);
 }
 
@@ -473,6 +512,9 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
   // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block
   int64_t per_slice = std::max<int64_t>(1, 256 / ((int64_t)n_tiles_n * plan.parts));
   per_slice = std::min<int64_t>(per_slice, ceil_div(plan.n_tiles, waves));
+  if (per_slice > 8) per_slice = per_slice / 8 * 8;
+  p.xcd_ranges = plan.slabs && per_slice % 8 == 0;  // (contiguous ranges of a purely bitmask-sorted order are unequal work)
+  p.quad = plan.n_split > 0;
   dim3 grid((unsigned)per_slice, (unsigned)n_tiles_n, (unsigned)plan.parts);
   if (a.dtype == SPCONV_F16) return launch_wave_ks<_Float16>(ks, bn / 16, p, grid, waves * 64, smem, st);
   return launch_wave_ks<__bf16>(ks, bn / 16, p, grid, waves * 64, smem, st);

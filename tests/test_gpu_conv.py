@@ -195,6 +195,34 @@ def test_sort_invariants(sp, cloud, n_split):
         assert (np.diff(perm)[same] > 0).all()
 
 
+@pytest.mark.parametrize("kernel", [1, 2])
+@pytest.mark.parametrize("n_split", [1, 2, 3])
+def test_spatial_slabs_in_front_of_the_sort_keys(sp, cloud, kernel, n_split):
+    """SPCONV_FLAG_SLABS: rows are visited slab by slab (eight equal slabs along the longest axis)
+    and in stable bitmask order inside a slab.  Any order is valid, so the results are checked
+    against the oracle as always, and the order against the rule the header states."""
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 32, 27, "f16", 91)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    cfg = _cfg(sp, n_split, kernel=kernel)
+    cfg.flags = sp.FLAG_SLABS
+    assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+    assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    ext = c[:, 1:].max(0).astype(np.int64) - c[:, 1:].min(0) + 1
+    axis = int(np.argmax(ext))                  # first of the longest axes
+    slab = (c[:, 1 + axis].astype(np.int64) - c[:, 1 + axis].min()) * 8 // ext[axis]
+    mask = oc.bitmask(ref.M).astype(np.uint64)
+    for i, (lo, hi) in enumerate(oc.split_ranges(27, n_split)):
+        perm = km.export_perm(sp.OP_FWD, cfg, i).cpu().numpy()
+        assert sorted(perm.tolist()) == list(range(ref.n_out))
+        key = (slab[perm] << 27) | ((mask[perm] >> np.uint64(lo)) & np.uint64((1 << (hi - lo)) - 1)).astype(np.int64)
+        assert (np.diff(key) >= 0).all()
+        assert (np.diff(perm)[np.diff(key) == 0] > 0).all()
+    plain = _cfg(sp, n_split, kernel=kernel)    # the plan without slabs is a different plan
+    assert not np.array_equal(km.export_perm(sp.OP_FWD, plain, 0).cpu().numpy(),
+                              km.export_perm(sp.OP_FWD, cfg, 0).cpu().numpy())
+
+
 @pytest.mark.parametrize("n_split", [0, 1, 2, 3])
 def test_mac_units_match_oracle_model(sp, cloud, n_split):
     c, ref = cloud

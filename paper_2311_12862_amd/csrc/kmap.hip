@@ -148,13 +148,17 @@ __global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ co
                                                      long long map_vec4, unsigned* __restrict__ mask,
                                                      long long mask_n) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  // The row is requested before the preset stores go out: behind 100 bytes of stores per thread
+  // the load took 10 us to come back (23 600 clk mean L1 -> L2 read latency in this kernel, by
+  // the counters), and the insert, which needs it, is the kernel's critical path.
+  int4 c = make_int4(0, 0, 0, 0);
+  if (j < n) c = coords[j];
   if (map4) {
     const long long stride = (long long)gridDim.x * blockDim.x;
     for (long long i = j; i < map_vec4; i += stride) map4[i] = make_int4(-1, -1, -1, -1);
     for (long long i = j; i < mask_n; i += stride) mask[i] = 0u;
   }
   if (j >= n) return;
-  const int4 c = coords[j];
   keep[j] = c;  // the kmap's own copy of the caller's rows
   if (!coord_ok(c.x, c.y, c.z, c.w)) {
     atomicOr(&ctl->flags, FLAG_RANGE);
@@ -415,26 +419,28 @@ __global__ void __launch_bounds__(256)
   if (lane == 0) wave_pairs[threadIdx.x >> 6] = 2u * (unsigned)__popcll(bal & ~centre) + (unsigned)__popcll(bal & centre);
   __syncthreads();
   // The workgroup that arrives last sums the pair counters and writes the result into pinned
-  // host memory.  Arrival is counted in two levels (per pair slot, then over the slots) so that
-  // no address sees more than gridDim/64 or 64 atomics.  Every value the last workgroup reads
-  // was produced by an atomic whose return its producer waited for before counting itself in,
-  // and is read with an atomic, so no cache write-back is needed.
-  __shared__ int is_last;
+  // host memory.  A pair slot is one 64-bit counter: pairs in its low 40 bits, arrivals above, so
+  // that one atomic both adds the workgroup's pairs and tells it whether it was the slot's last
+  // (a second level counts the finished slots: no address sees more than gridDim/64 or 64
+  // atomics).  Only the first wave waits for that atomic; the others leave after the barrier and
+  // free their slots on the CU (two returning atomics in a row, awaited by the whole workgroup,
+  // kept every wave of this kernel resident for 7 us).  Every value the last workgroup reads was
+  // produced by an atomic whose return its producer waited for before counting itself in, and is
+  // read with an atomic, so no cache write-back is needed.
+  if (threadIdx.x >= 64) return;
+  constexpr unsigned long long kArrive = 1ull << 40;
+  int last = 0;
   if (threadIdx.x == 0) {
     const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
     const unsigned slot = blockIdx.x % kPairSlots;
-    const unsigned long long before = atomicAdd(&ctl->pairs[slot * 16], (unsigned long long)n);
+    const unsigned long long before = atomicAdd(&ctl->pairs[slot * 16], (unsigned long long)n + kArrive);
     const unsigned slot_wgs = (gridDim.x - slot + kPairSlots - 1) / kPairSlots;
     const unsigned used_slots = gridDim.x < (unsigned)kPairSlots ? gridDim.x : (unsigned)kPairSlots;
-    // (before >> 63) is zero; it ties the arrival to the completed pair add
-    const unsigned arrived = atomicAdd(&ctl->tick[slot * 16], 1u + (unsigned)(before >> 63));
-    int last = 0;
-    if (arrived + 1 == slot_wgs) last = atomicAdd(&ctl->tick_top, 1u) + 1 == used_slots;
-    is_last = last;
+    if ((unsigned)(before >> 40) + 1 == slot_wgs) last = atomicAdd(&ctl->tick_top, 1u) + 1 == used_slots;
   }
-  __syncthreads();
-  if (is_last && threadIdx.x < 64) {
-    unsigned long long v = atomicAdd(&ctl->pairs[threadIdx.x * 16], 0ull);  // kPairSlots == 64 lanes
+  last = __builtin_amdgcn_readfirstlane(last);
+  if (last) {
+    unsigned long long v = atomicAdd(&ctl->pairs[threadIdx.x * 16], 0ull) & (kArrive - 1);  // kPairSlots == 64 lanes
     for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
     if (threadIdx.x == 0)
       host->word = kHostReady | ((unsigned long long)(ctl->flags & 0xFFu) << 48) | (v & 0xFFFFFFFFFFFFull);

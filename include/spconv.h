@@ -184,7 +184,10 @@ SPCONV_API int spconv_kmap_pointwise(spconv_kmap* km, int on_outputs, void* stre
 /* Resolves an asynchronous build: waits until the build's last kernel has published its result
  * (a word in pinned host memory that the host reads: nothing is recorded on the stream, and no
  * wait at all once that kernel has finished), returns SPCONV_OK, SPCONV_ERANGE or SPCONV_EDUP, and
- * makes the pair count available.  SPCONV_OK at once for other kmaps.  `stream` is unused for
+ * makes the pair count available.  The verdict stays with the kmap: every later call returns it
+ * again, also when another call (spconv_kmap_sizes asking for the pair count,
+ * spconv_kmap_mac_units, a tuner) was the one that waited for the build.  SPCONV_OK at once for
+ * kmaps built synchronously (their errors were returned by the build).  `stream` is unused for
  * kmaps built asynchronously (the build's own stream is waited for if the result is late). */
 SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream);
 
@@ -194,14 +197,16 @@ SPCONV_API int spconv_kmap_status(spconv_kmap* km, void* stream);
  * runs a small reduction on the kmap's build stream and synchronises it. */
 SPCONV_API int spconv_kmap_sizes(const spconv_kmap* km, int64_t* n_in, int64_t* n_out, int64_t* n_pairs);
 
-/* Copies P_out (int32 [n_out][4]) to dst (device). */
+/* Copies P_out, the output coordinates q_n of Equation 1 (Section 2.1), int32 [n_out][4], to dst
+ * (device): the caller's rows for stride 1, the sorted unique floor(p / s) otherwise. */
 SPCONV_API int spconv_kmap_out_coords(const spconv_kmap* km, int32_t* dst, void* stream);
 
-/* Copies P_in (int32 [n_in][4]) to dst (device): the caller's rows for
- * transposed = 0, the sorted coarse set for transposed = 1. */
+/* Copies P_in, the input coordinates p_j of Equation 1 (Section 2.1), int32 [n_in][4], to dst
+ * (device): the caller's rows for transposed = 0, the sorted coarse set for transposed = 1. */
 SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* stream);
 
-/* Copies the canonical map M (int32 [n_out][K^3], -1 = absent) to dst (device). */
+/* Copies the output-stationary map of Section 3.1 to dst (device): int32 [n_out][K^3],
+ * M[n][k] = j where p_j = s*q_n + delta_k (the pairs that Equation 1 sums over), -1 = absent. */
 SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* stream);
 
 /* Copies the neighbour bitmasks (uint32 [n_out], Section 2.2.3) to dst (device). */
@@ -242,7 +247,7 @@ SPCONV_API void spconv_kmap_destroy(spconv_kmap* km);
  *   out     device [n_out][C_out], fully overwritten.
  * dtype applies to feats, weights and out; accumulation is fp32 with one
  * rounding (to nearest even) at the end.  C_in and C_out must be multiples
- * of 8 (F16/BF16) or 4 (F32).  km is not const because plans are cached. */
+ * of 8 (F16/BF16) or 4 (F32), else SPCONV_EINVAL.  km is not const because plans are cached. */
 SPCONV_API int spconv_fwd(const void* feats, const void* weights, spconv_kmap* km, int C_in, int C_out,
                spconv_dtype dtype, const spconv_config* cfg_or_null, void* out, void* stream);
 
@@ -329,10 +334,16 @@ SPCONV_API int spconv_copy_cols(const void* src, int src_ld, int src_off, void* 
  * (so that a framework's caching allocator can back them); NULL, NULL restores
  * the library's own pool over hipMalloc.  alloc returns a device pointer aligned
  * to 256 bytes, or NULL when out of memory; both run on the calling host thread,
- * inside library calls.  Switch allocators only while no kmap is alive: a block
+ * inside library calls.  `stream` is the hipStream_t (as void*) of the library
+ * call in progress: the block is first used by work enqueued on that stream, and
+ * a block is handed back while work of that stream may still be using it, so a
+ * stream-ordered allocator must order its reuse behind that stream (exactly what
+ * hipFreeAsync(ptr, stream), or a caching allocator keyed by stream, does).
+ * spconv_kmap_destroy and spconv_kmap_drop_plans pass the stream of the last
+ * call that used the kmap.  Switch allocators only while no kmap is alive: a block
  * goes back to whatever is installed when it is released. */
-SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* user), void (*free_)(void* ptr, void* user),
-                         void* user);
+SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* stream, void* user),
+                         void (*free_)(void* ptr, void* stream, void* user), void* user);
 
 SPCONV_API const char* spconv_strerror(int status);
 /* Text of the last failing HIP call on this host thread ("" if none). */

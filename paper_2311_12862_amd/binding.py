@@ -96,15 +96,16 @@ def load_library():
     return lib
 
 
-_ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p)
-_FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p)
+_ALLOC_FN = C.CFUNCTYPE(C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p)
+_FREE_FN = C.CFUNCTYPE(None, C.c_void_p, C.c_void_p, C.c_void_p)
 _allocator_refs = None   # keeps the ctypes thunks of the installed callbacks alive
 
 
 def set_allocator(alloc=None, free=None):
-    """spconv_set_allocator: alloc(bytes) -> device address (int, 0 = out of memory) and free(address)
-    serve every device allocation the library makes from now on; (None, None) restores its own pool.
-    Switch only while no kmap is alive."""
+    """spconv_set_allocator: alloc(bytes, stream) -> device address (int, 0 = out of memory) and
+    free(address, stream) serve every device allocation the library makes from now on; stream is the
+    raw hipStream_t (int, 0 = null stream) of the library call in progress.  (None, None) restores the
+    library's own pool.  Switch only while no kmap is alive."""
     global _allocator_refs
     if (alloc is None) != (free is None):
         raise ValueError("give both callbacks or neither")
@@ -113,8 +114,8 @@ def set_allocator(alloc=None, free=None):
         _check(lib.spconv_set_allocator(None, None, None), "spconv_set_allocator")
         _allocator_refs = None
         return
-    a = _ALLOC_FN(lambda n, _user: int(alloc(int(n))) or None)
-    f = _FREE_FN(lambda ptr, _user: free(int(ptr or 0)))
+    a = _ALLOC_FN(lambda n, stream, _user: int(alloc(int(n), int(stream or 0))) or None)
+    f = _FREE_FN(lambda ptr, stream, _user: free(int(ptr or 0), int(stream or 0)))
     _check(lib.spconv_set_allocator(C.cast(a, C.c_void_p), C.cast(f, C.c_void_p), None), "spconv_set_allocator")
     _allocator_refs = (a, f)
 
@@ -251,6 +252,15 @@ def build_kmap(coords, K: int = 3, stride: int = 1, transposed: bool = False, st
     return KMap(h, K)
 
 
+def _out_tensor(out, shape, dtype, like):
+    """A caller-supplied output: exactly the shape, type and device the call writes (the C ABI has
+    no row count to catch a wrong one), contiguous."""
+    _dev_tensor(out, dtype)
+    if tuple(out.shape) != tuple(shape) or out.device != like.device:
+        raise SpconvError(-5, f"out is {tuple(out.shape)} on {out.device}, the call writes {tuple(shape)} on {like.device}")
+    return out
+
+
 def _conv_args(a, w_or_b, kmap, rows_a):
     _dev_tensor(a)
     if a.dtype not in _DTYPES:
@@ -269,6 +279,7 @@ def fwd(feats, weights, kmap: KMap, cfg: Config | None = None, out=None, stream=
         raise SpconvError(-5, "weights shape does not fit")
     if out is None:
         out = torch.empty((kmap.n_out, c_out), dtype=feats.dtype, device=feats.device)
+    _out_tensor(out, (kmap.n_out, c_out), feats.dtype, feats)
     _check(load_library().spconv_fwd(_ptr(feats), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
                                      _ptr(out), _stream(stream)), "spconv_fwd")
     return out
@@ -280,9 +291,7 @@ def fwd_noalloc(feats, weights, kmap: KMap, out, cfg: Config | None = None, stre
     V, c_in, c_out = weights.shape
     if V != kmap.V or c_in != feats.shape[1]:
         raise SpconvError(-5, "weights shape does not fit")
-    _dev_tensor(out, feats.dtype)
-    if tuple(out.shape) != (kmap.n_out, c_out):
-        raise SpconvError(-5, "out shape does not fit")
+    _out_tensor(out, (kmap.n_out, c_out), feats.dtype, feats)
     _check(load_library().spconv_fwd_noalloc(_ptr(feats), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
                                              _ptr(out), _stream(stream)), "spconv_fwd_noalloc")
     return out
@@ -296,6 +305,7 @@ def dgrad(dout, weights, kmap: KMap, cfg: Config | None = None, out=None, stream
         raise SpconvError(-5, "weights shape does not fit")
     if out is None:
         out = torch.empty((kmap.n_in, c_in), dtype=dout.dtype, device=dout.device)
+    _out_tensor(out, (kmap.n_in, c_in), dout.dtype, dout)
     _check(load_library().spconv_dgrad(_ptr(dout), _ptr(weights), kmap.handle, c_in, c_out, dt, _cfg(cfg),
                                        _ptr(out), _stream(stream)), "spconv_dgrad")
     return out
@@ -309,6 +319,7 @@ def wgrad(feats, dout, kmap: KMap, cfg: Config | None = None, out=None, stream=N
     c_in, c_out = feats.shape[1], dout.shape[1]
     if out is None:
         out = torch.empty((kmap.V, c_in, c_out), dtype=torch.float32, device=feats.device)
+    _out_tensor(out, (kmap.V, c_in, c_out), torch.float32, feats)
     _check(load_library().spconv_wgrad(_ptr(feats), _ptr(dout), kmap.handle, c_in, c_out, dt, _cfg(cfg),
                                        _ptr(out), _stream(stream)), "spconv_wgrad")
     return out

@@ -25,8 +25,8 @@ int hip_fail(hipError_t e, const char* what, const char* file, int line) {
 // that stream for the duration of the call (StreamScope).
 namespace {
 std::mutex g_mem_mu;
-void* (*g_user_alloc)(size_t, void*) = nullptr;
-void (*g_user_free)(void*, void*) = nullptr;
+void* (*g_user_alloc)(size_t, void*, void*) = nullptr;
+void (*g_user_free)(void*, void*, void*) = nullptr;
 void* g_user_ctx = nullptr;
 
 struct Block {
@@ -52,7 +52,7 @@ StreamScope::~StreamScope() { t_stream = saved_; }
 
 void* dev_alloc(size_t bytes) {
   std::lock_guard<std::mutex> lk(g_mem_mu);
-  if (g_user_alloc) return g_user_alloc(bytes, g_user_ctx);
+  if (g_user_alloc) return g_user_alloc(bytes, (void*)t_stream, g_user_ctx);  // the stream of the call in progress
   bytes = (size_t)round_up((int64_t)bytes, 256);
   int best = -1;
   for (int i = 0; i < (int)g_free_blocks.size(); ++i) {
@@ -84,7 +84,7 @@ void dev_free(void* p) {
   if (!p) return;
   std::lock_guard<std::mutex> lk(g_mem_mu);
   if (g_user_free && g_live.find(p) == g_live.end()) {
-    g_user_free(p, g_user_ctx);
+    g_user_free(p, (void*)t_stream, g_user_ctx);
     return;
   }
   auto it = g_live.find(p);
@@ -105,7 +105,7 @@ bool dtype_ok(int d) { return d == SPCONV_F32 || d == SPCONV_F16 || d == SPCONV_
 
 int check_channels(int C_in, int C_out, spconv_dtype dtype) {
   const int q = dtype == SPCONV_F32 ? 4 : 8;
-  if (C_in <= 0 || C_out <= 0 || C_in % q || C_out % q || C_in > 4096 || C_out > 4096) return SPCONV_ESHAPE;
+  if (C_in <= 0 || C_out <= 0 || C_in % q || C_out % q || C_in > 4096 || C_out > 4096) return SPCONV_EINVAL;
   return SPCONV_OK;
 }
 
@@ -860,7 +860,7 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
   return SPCONV_OK;
 }
 
-SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t, void*), void (*free_)(void*, void*), void* user) {
+SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t, void*, void*), void (*free_)(void*, void*, void*), void* user) {
   if ((alloc == nullptr) != (free_ == nullptr)) return SPCONV_EINVAL;
   std::lock_guard<std::mutex> lk(g_mem_mu);
   g_user_alloc = alloc;

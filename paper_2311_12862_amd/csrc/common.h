@@ -142,8 +142,8 @@ struct spconv_kmap {
   // build whose status was not read yet: the pinned block the probe kernel publishes flags and
   // pair count to, with the event that marks the probe's completion
   void* pending_host = nullptr;
-  spc::DevBuf pending_ctl;  // device control block, kept until the publish kernel has read it
   bool pending = false;
+  int build_status = SPCONV_OK;  // verdict of the build once resolved: every later spconv_kmap_status returns it
   ~spconv_kmap();
   bool submanifold() const { return stride == 1 && !transposed; }
 };

@@ -15,7 +15,7 @@ enum EwOp { EW_RELU = 0, EW_ADD = 1, EW_ADD_RELU = 2, EW_RELU_BWD = 3 };
 
 // out[i] = op(a[i], b[i]); RELU: max(a,0); ADD: a+b; ADD_RELU: max(a+b,0); RELU_BWD: b > 0 ? a : 0
 template <typename T, int OP>
-__global__ void __launch_bounds__(256) k_ew(const T* __restrict__ a, const T* __restrict__ b, T* __restrict__ out,
+__global__ void __launch_bounds__(256) k_ew(const T* a, const T* b, T* out,  // (out may alias a or b: no __restrict__)
                                             long long n) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) {

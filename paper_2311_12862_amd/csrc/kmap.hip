@@ -731,7 +731,7 @@ struct HostCtlHandle {
 // wait_stream: wait for the whole stream (the synchronous build: everything on it is the build);
 // otherwise only for the probe's result word.
 int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
-  if (!km->pending) return SPCONV_OK;
+  if (!km->pending) return km->build_status;
   HostCtl* hc = static_cast<HostCtl*>(km->pending_host);
   if (wait_stream) {
     SPC_HIP(hipStreamSynchronize(st));
@@ -744,6 +744,7 @@ int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
     km->pending = false;
     km->pending_host = nullptr;
     host_ctl_release(hc);
+    km->build_status = SPCONV_EHIP;
     return SPCONV_EHIP;
   }
   const unsigned long long word = hc->res.word;
@@ -754,6 +755,7 @@ int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
   km->pending = false;
   km->pending_host = nullptr;
   host_ctl_release(hc);
+  km->build_status = status;  // kept: whoever resolved the build (a pair count, a tuner), spconv_kmap_status still reports it
   return status;
 }
 

@@ -478,6 +478,7 @@ int plan_mac_units(spconv_kmap* km, SideMap& side, IgemmPlan* plan, int group_ro
 }
 
 int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan** out) {
+  const int64_t requested = target_pairs;  // (the cache key; the item size may be raised below)
   auto it = km->wplans.find(target_pairs);
   if (it != km->wplans.end()) {
     *out = it->second.get();
@@ -491,9 +492,13 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
   if (!p) return SPCONV_ENOMEM;
   const int V = km->V;
   const SideMap& side = km->out_side;
-  p->target_pairs = target_pairs;
   p->pairs_cap = km->n_pairs >= 0 ? km->n_pairs : km->n_out * V;
-  p->max_items = (int)std::min<int64_t>(V + ceil_div(p->pairs_cap, target_pairs), 1 << 20);
+  // At most 2^20 work items: a smaller request is raised to the item size that covers every pair
+  // (the item cutter gives later offsets no item once the list is full, which would drop pairs).
+  constexpr int64_t kMaxItems = 1 << 20;
+  if (V + ceil_div(p->pairs_cap, target_pairs) > kMaxItems) target_pairs = ceil_div(p->pairs_cap, kMaxItems - V);
+  p->target_pairs = target_pairs;
+  p->max_items = (int)(V + ceil_div(p->pairs_cap, target_pairs));
   // rows per chunk (one workgroup, a quarter per wave): 256, or the next power of two up to 2048
   // that lets the fill kernel add up the counters itself
   int wave_rows = 256;
@@ -538,7 +543,7 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
 #undef SPC_FILL
   SPC_LAUNCH_CHECK();
   *out = p.get();
-  km->wplans[target_pairs] = std::move(p);
+  km->wplans[requested] = std::move(p);
   return SPCONV_OK;
 }
 

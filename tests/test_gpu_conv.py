@@ -175,7 +175,18 @@ def test_shape_and_config_errors(sp, cloud):
     w12 = torch.zeros((27, 12, 64), dtype=torch.float16, device="cuda")
     with pytest.raises(sp.SpconvError) as e:
         sp.fwd(x12, w12, km)
-    assert e.value.status == -5
+    assert e.value.status == -1        # channel counts that are not a multiple of 8
+    # a caller-supplied output of the wrong shape, type or layout never reaches the library
+    for bad in (torch.empty((ref.n_out, 32), dtype=torch.float16, device="cuda"),
+                torch.empty((ref.n_out - 1, 64), dtype=torch.float16, device="cuda"),
+                torch.empty((ref.n_out, 64), dtype=torch.bfloat16, device="cuda"),
+                torch.empty((ref.n_out, 128), dtype=torch.float16, device="cuda")[:, ::2],
+                torch.empty((ref.n_out, 64), dtype=torch.float16)):
+        for call in (lambda o: sp.fwd(x, w, km, out=o), lambda o: sp.dgrad(x, w, km, out=o)):
+            with pytest.raises((sp.SpconvError, ValueError)):
+                call(bad)
+    with pytest.raises((sp.SpconvError, ValueError)):
+        sp.wgrad(x, x, km, out=torch.empty((27, 64, 32), dtype=torch.float32, device="cuda"))
 
 
 @pytest.mark.parametrize("n_split", [1, 2, 4])

@@ -163,7 +163,18 @@ def test_asynchronous_build(sp):
     with pytest.raises(sp.SpconvError) as e:
         km.status()
     assert e.value.status == -3
-    km.status()  # the error was delivered once; the handle stays usable for destroy
+    with pytest.raises(sp.SpconvError) as e:   # the verdict stays with the kmap
+        km.status()
+    assert e.value.status == -3
+    # calls that resolve the pending build on their own (pair count, executed MACs, tuner) do not swallow it
+    import torch
+    for resolve in (lambda k: k.n_pairs(), lambda k: k.mac_units(sp.OP_FWD),
+                    lambda k: sp.tune(k, 16, 16, torch.float16, sp.OP_WGRAD, 1)):
+        km = sp.build_kmap(coords_dev(dup), 3, 1, asynchronous=True)
+        resolve(km)
+        with pytest.raises(sp.SpconvError) as e:
+            km.status()
+        assert e.value.status == -3
     bad = c.copy()
     bad[9, 2] = 40000
     km = sp.build_kmap(coords_dev(bad), 3, 1, asynchronous=True)
@@ -185,13 +196,13 @@ def test_caller_allocator_backs_every_device_allocation(sp):
     (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, 27, "f16", 92)
     live, calls = {}, [0, 0]
 
-    def alloc(n):
+    def alloc(n, stream):
         t = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")
         live[t.data_ptr()] = t
         calls[0] += 1
         return t.data_ptr()
 
-    def free(ptr):
+    def free(ptr, stream):
         calls[1] += 1
         live.pop(ptr)
 
@@ -212,6 +223,55 @@ def test_caller_allocator_backs_every_device_allocation(sp):
         sp.set_allocator(None, None)
     km = sp.build_kmap(coords_dev(c), 3, 2)                # the library's own pool serves again
     np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+
+
+def test_stream_ordered_allocator_on_a_side_stream(sp):
+    """The allocator callbacks receive the stream of the call in progress.  A stream-ordered
+    caching allocator (PyTorch's, which only reuses a block on the stream it was allocated on)
+    backs a kmap that lives entirely on a non-default stream: every callback names that stream,
+    results match the oracle, and every block comes back."""
+    import torch
+    from _util import TOL, make_layer, norm_err
+    c = gen.lidar_scene(95, target_n=3000)
+    ref = oc.build_kmap(c, 3, 2)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, 27, "f16", 96)
+    side = torch.cuda.Stream()
+    live, seen = {}, set()
+
+    def alloc(n, stream):
+        seen.add(stream)
+        with torch.cuda.stream(torch.cuda.ExternalStream(stream) if stream else torch.cuda.default_stream()):
+            t = torch.empty(max(n, 1), dtype=torch.uint8, device="cuda")   # the caching allocator files it under that stream
+        live[t.data_ptr()] = t
+        return t.data_ptr()
+
+    def free(ptr, stream):
+        seen.add(stream)
+        live.pop(ptr)        # back to the allocator's pool of the stream it was allocated on
+
+    coords = coords_dev(c)
+    torch.cuda.synchronize()
+    sp.set_allocator(alloc, free)
+    try:
+        with torch.cuda.stream(side):
+            for rep in range(3):                            # blocks are recycled between the rounds
+                km = sp.build_kmap(coords, 3, 2)
+                cfg = sp.Config()
+                cfg.n_split, cfg.kernel = 2, 1 + rep % 2
+                y = sp.fwd(x, w, km, cfg)
+                dx = sp.dgrad(g, w, km, cfg)
+                dw = sp.wgrad(x, g, km)
+                m = km.export()
+                km.destroy()
+                side.synchronize()
+                np.testing.assert_array_equal(m.cpu().numpy(), ref.M)
+                assert norm_err(y, oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+                assert norm_err(dx, oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+                assert norm_err(dw, oc.wgrad(x32, g32, ref.M)) <= 1e-4
+                assert not live
+        assert seen == {side.cuda_stream}
+    finally:
+        sp.set_allocator(None, None)
 
 
 @pytest.mark.parametrize("K,stride", [(3, 2), (2, 2), (3, 1), (3, 3), (1, 1)])

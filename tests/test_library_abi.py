@@ -43,6 +43,7 @@ def test_argument_errors_need_no_gpu():
     assert lib.spconv_build_kmap(None, 0, 2, 1, 0, None, ctypes.byref(out)) == -1
     assert lib.spconv_kmap_sizes(None, None, None, None) == -1
     assert lib.spconv_fwd(None, None, None, 64, 64, 1, None, None, None) == -1
+    assert lib.spconv_fwd_noalloc(None, None, None, 64, 64, 1, None, None, None) == -1
     for K, stride, transposed in ((4, 1, 0), (5, 1, 0), (3, 0, 0), (3, 65, 0), (3, 1, 2), (2, 1, 0), (2, 3, 0)):
         assert lib.spconv_build_kmap(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1, (K, stride)
         assert lib.spconv_build_kmap_async(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1
@@ -59,7 +60,7 @@ def test_argument_errors_need_no_gpu():
     assert lib.spconv_ew(9, None, None, None, 4, 1, None) == -1
     assert lib.spconv_ew(0, None, None, None, 0, 1, None) == 0          # nothing to do
     assert lib.spconv_copy_cols(None, 8, 4, None, 8, 0, 8, 4, 1, None) == -1   # columns past the row
-    alloc = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p)(lambda n, u: None)
+    alloc = ctypes.CFUNCTYPE(ctypes.c_void_p, ctypes.c_size_t, ctypes.c_void_p, ctypes.c_void_p)(lambda n, s, u: None)
     assert lib.spconv_set_allocator(ctypes.cast(alloc, ctypes.c_void_p), None, None) == -1   # both or neither
     assert lib.spconv_set_allocator(None, None, None) == 0
     lib.spconv_kmap_destroy(None)                                        # a no-op

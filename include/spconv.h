@@ -345,6 +345,13 @@ SPCONV_API int spconv_copy_cols(const void* src, int src_ld, int src_off, void* 
 SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* stream, void* user),
                          void (*free_)(void* ptr, void* stream, void* user), void* user);
 
+/* Measures, on the current device, what roofline reports quote beside the published peaks:
+ * the rate of a plain streaming copy of 1 GiB (bytes read + bytes written per second, in GB/s:
+ * what HBM delivers to a kernel with perfect access patterns) and the rate of back-to-back
+ * 16x16x32 fp16 matrix instructions on every SIMD (dense TFLOP/s).  Either pointer may be NULL.
+ * Blocking; allocates 2 GiB for the copy; takes about 10 ms. */
+SPCONV_API int spconv_measure_peaks(double* hbm_copy_gbs, double* mfma_f16_tflops, void* stream);
+
 SPCONV_API const char* spconv_strerror(int status);
 /* Text of the last failing HIP call on this host thread ("" if none). */
 SPCONV_API const char* spconv_last_hip_error(void);

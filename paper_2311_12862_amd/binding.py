@@ -84,6 +84,7 @@ def load_library():
         "spconv_ew": (i32, [i32, vp, vp, vp, i64, i32, vp]),
         "spconv_copy_cols": (i32, [vp, i32, i32, vp, i32, i32, i32, i64, i32, vp]),
         "spconv_set_allocator": (i32, [vp, vp, vp]),
+        "spconv_measure_peaks": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_double), vp]),
         "spconv_strerror": (C.c_char_p, [i32]),
         "spconv_last_hip_error": (C.c_char_p, []),
         "spconv_version": (i32, []),
@@ -347,6 +348,13 @@ def tune_group(kmap: KMap, layers, dtype, training: bool = False, bind_fwd_dgrad
                                             fwd, dg, wg, C.byref(us), _stream(stream)), "spconv_tune_group")
     copy = lambda arr: None if arr is None else [Config.from_buffer_copy(c) for c in arr]
     return copy(fwd), copy(dg), copy(wg), us.value
+
+
+def measure_peaks(stream=None):
+    """spconv_measure_peaks: (streaming-copy GB/s, fp16 MFMA TFLOP/s) measured on the current device."""
+    hbm, mfma = C.c_double(), C.c_double()
+    _check(load_library().spconv_measure_peaks(C.byref(hbm), C.byref(mfma), _stream(stream)), "spconv_measure_peaks")
+    return hbm.value, mfma.value
 
 
 EW_RELU, EW_ADD, EW_ADD_RELU, EW_RELU_BWD = 0, 1, 2, 3

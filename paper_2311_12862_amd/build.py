@@ -4,8 +4,7 @@
 
 Every translation unit under csrc/ is compiled with hipcc for gfx950 and
 linked into one shared library with a C ABI (include/spconv.h).  Objects go to
-_build/ (not committed).  The measurement programs under csrc/probes/ become
-executables named <source>_probe next to the library.
+_build/ (not committed).
 """
 from __future__ import annotations
 
@@ -19,7 +18,6 @@ ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 BUILD = os.path.join(ROOT, "_build")
 LIB = os.path.join(HERE, "libspconv.so")
-PROBES = os.path.join(CSRC, "probes")   # stand-alone measurement programs, one executable each
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -58,15 +56,6 @@ def build(verbose: bool = True) -> str:
         raise RuntimeError(f"link failed:\n{r.stderr}")
     if verbose:
         print(f"built {LIB}")
-    for src in sorted(f for f in os.listdir(PROBES) if f.endswith(".hip")):
-        exe = os.path.join(HERE, src.replace(".hip", "_probe"))
-        r = subprocess.run([HIPCC, "--offload-arch=gfx950", "-O3", "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-                            os.path.join(PROBES, src), "-o", exe],
-                           capture_output=True, text=True)
-        if r.returncode != 0:
-            raise RuntimeError(f"hipcc failed on probes/{src}:\n{r.stderr}")
-        if verbose:
-            print(f"built {exe}")
     return LIB
 
 

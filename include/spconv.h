@@ -345,6 +345,35 @@ SPCONV_API int spconv_copy_cols(const void* src, int src_ld, int src_off, void* 
 SPCONV_API int spconv_set_allocator(void* (*alloc)(size_t bytes, void* stream, void* user),
                          void (*free_)(void* ptr, void* stream, void* user), void* user);
 
+/* What spconv_fwd / spconv_dgrad would launch for one side of a map: host arithmetic only (no GPU
+ * is touched, none is needed), for tests and tools.  The library's run functions take every
+ * launch dimension, LDS size and table size from the same functions that fill this structure.
+ *   K        kernel size of the map (K^3 offsets)
+ *   rows     rows of the side that is walked (outputs for forward, inputs for dgrad)
+ *   rows_src rows of the tensor that is gathered from
+ *   C_red    reduced channels (C_in for forward, C_out for dgrad), C_cols the produced ones
+ *   dgrad    0 / 1 (the tiled kernel's LDS layout differs)
+ * Returns SPCONV_EINVAL for every shape or configuration the compute calls refuse, SPCONV_OK with
+ * an all-zero structure for rows = 0 (nothing is launched). */
+typedef struct spconv_launch_info {
+  int32_t kernel;         /* 1: weights resident in LDS, 16-row blocks; 2: workgroup tiles */
+  int32_t parts;          /* max(1, n_split) */
+  int32_t sorted;         /* n_split >= 1: rows are visited through a permutation */
+  int32_t tile_m, tile_n; /* rows per block / tile, output channels per workgroup */
+  int32_t k_steps;        /* kernel 1: 32-channel steps per offset; kernel 2: channels per LDS stage */
+  int32_t waves, threads; /* per workgroup */
+  int32_t grid[3];        /* kernel 1: workgroups per slice, column tiles, parts; kernel 2: tiles, column tiles, parts */
+  int32_t xcd_ranges;     /* kernel 1: blocks are dealt to the XCDs as eight contiguous ranges */
+  int32_t lo[4], width[4];      /* offset range of each part */
+  int64_t lds_bytes;            /* dynamic LDS of the launch */
+  int64_t slab_bytes, slab_map_bytes; /* kernel 1: per-wave LDS slab and its map part */
+  int64_t rows_pad, n_tiles;    /* padded rows of the map; 16-row blocks (kernel 1) or tiles (kernel 2) */
+  int64_t map_elems[4];         /* int32 elements of the table each part's kernel indexes */
+} spconv_launch_info;
+SPCONV_API int spconv_describe_launch(int K, int64_t rows, int64_t rows_src, int C_red, int C_cols,
+                                      spconv_dtype dtype, const spconv_config* cfg_or_null, int dgrad,
+                                      spconv_launch_info* out);
+
 /* Measures, on the current device, what roofline reports quote beside the published peaks:
  * the rate of a plain streaming copy of 1 GiB (bytes read + bytes written per second, in GB/s:
  * what HBM delivers to a kernel with perfect access patterns) and the rate of back-to-back

@@ -6,5 +6,5 @@ Importing it without the built library raises: there is no fallback path.
 """
 from .binding import (  # noqa: F401
     Config, KMap, SpconvError, build_kmap, dgrad, fwd, fwd_noalloc, lib_path, load_library, tune, tune_group, wgrad,
-    OP_FWD, OP_DGRAD, OP_WGRAD, FLAG_SLABS, EW_RELU, EW_ADD, EW_ADD_RELU, EW_RELU_BWD, ew, copy_cols, set_allocator, measure_peaks,
+    OP_FWD, OP_DGRAD, OP_WGRAD, FLAG_SLABS, EW_RELU, EW_ADD, EW_ADD_RELU, EW_RELU_BWD, ew, copy_cols, set_allocator, measure_peaks, describe_launch, LaunchInfo,
 )

@@ -39,6 +39,15 @@ class LayerShape(C.Structure):
     _fields_ = [("c_in", C.c_int32), ("c_out", C.c_int32)]
 
 
+class LaunchInfo(C.Structure):
+    """Mirror of spconv_launch_info."""
+    _fields_ = [("kernel", C.c_int32), ("parts", C.c_int32), ("sorted", C.c_int32), ("tile_m", C.c_int32),
+                ("tile_n", C.c_int32), ("k_steps", C.c_int32), ("waves", C.c_int32), ("threads", C.c_int32),
+                ("grid", C.c_int32 * 3), ("xcd_ranges", C.c_int32), ("lo", C.c_int32 * 4), ("width", C.c_int32 * 4),
+                ("lds_bytes", C.c_int64), ("slab_bytes", C.c_int64), ("slab_map_bytes", C.c_int64),
+                ("rows_pad", C.c_int64), ("n_tiles", C.c_int64), ("map_elems", C.c_int64 * 4)]
+
+
 _LIB = None
 
 
@@ -84,6 +93,7 @@ def load_library():
         "spconv_ew": (i32, [i32, vp, vp, vp, i64, i32, vp]),
         "spconv_copy_cols": (i32, [vp, i32, i32, vp, i32, i32, i32, i64, i32, vp]),
         "spconv_set_allocator": (i32, [vp, vp, vp]),
+        "spconv_describe_launch": (i32, [i32, i64, i64, i32, i32, i32, cfgp, i32, C.POINTER(LaunchInfo)]),
         "spconv_measure_peaks": (i32, [C.POINTER(C.c_double), C.POINTER(C.c_double), vp]),
         "spconv_strerror": (C.c_char_p, [i32]),
         "spconv_last_hip_error": (C.c_char_p, []),
@@ -348,6 +358,15 @@ def tune_group(kmap: KMap, layers, dtype, training: bool = False, bind_fwd_dgrad
                                             fwd, dg, wg, C.byref(us), _stream(stream)), "spconv_tune_group")
     copy = lambda arr: None if arr is None else [Config.from_buffer_copy(c) for c in arr]
     return copy(fwd), copy(dg), copy(wg), us.value
+
+
+def describe_launch(K: int, rows: int, rows_src: int, c_red: int, c_cols: int, dtype, cfg: Config | None = None,
+                    dgrad: bool = False) -> LaunchInfo:
+    """spconv_describe_launch: the launch geometry of a forward / dgrad call (host arithmetic; needs no GPU)."""
+    info = LaunchInfo()
+    _check(load_library().spconv_describe_launch(K, rows, rows_src, c_red, c_cols, _DTYPES[dtype], _cfg(cfg), int(dgrad),
+                                                 C.byref(info)), "spconv_describe_launch")
+    return info
 
 
 def measure_peaks(stream=None):

@@ -163,6 +163,51 @@ int64_t auto_wgrad_pairs(spconv_kmap* km, int C_in, int C_out) {
   return std::max<int64_t>(1024, ceil_div(pairs, want_items));
 }
 
+// Which kernel runs a forward / dgrad call and on which tiles: the caller's configuration with
+// the automatic choices filled in.  Pure host arithmetic (spconv_describe_launch reports it).
+struct KernelChoice {
+  bool wave = false;  // kernel 1 (weights resident in LDS) instead of kernel 2 (workgroup tiles)
+  int tile_m = 0;     // plan tile height: 16 for kernel 1
+  int tile_n = 0;     // as passed to the kernel (0: its own default)
+};
+int choose_kernel(int V, int64_t rows_dst, int c_red, int c_cols, spconv_dtype dtype, bool tile_m_given,
+                  const spconv_config& c, KernelChoice* out) {
+  KernelChoice k;
+  int tile_m = c.tile_m;
+  if (!tile_m_given && dtype != SPCONV_F32) {
+    // automatic tile height (measured on unsorted maps, 10k .. 300k rows): 128 rows when that still
+    // leaves several workgroups per CU, or when the reduction is long (>= 128 channels) and there
+    // are enough rows for a workgroup per CU anyway; 64 rows otherwise
+    tile_m = (ceil_div(rows_dst, 128) * ceil_div(c_cols, 128) >= 2048 || (rows_dst >= 25000 && c_red >= 128)) ? 128 : 64;
+  }
+  if (c.kernel != 2 && dtype != SPCONV_F32) {
+    const int bn = igemm_wave_pick_bn(V, c.n_split, c_red, c_cols, c.tile_n, nullptr);
+    k.wave = bn > 0;
+    if (!k.wave && c.kernel == 1) return SPCONV_EINVAL;
+    // Automatic choice: the LDS-resident kernel gathers the input once per column tile.  It wins
+    // while the output is at most two tiles wide (64 -> 64 is 2 x 32) and, beyond that, while
+    // tiles x reduced channels x rows stays small: few rows leave the tiled kernel without enough
+    // workgroups, many rows make the repeated gathers the larger cost (measured: 100k rows,
+    // 64 -> 256 in eight tiles 89 us against 114 us; 128 -> 128 in eight 16-column tiles 160 us
+    // against 131 us; 10k rows, 128 -> 128 25 us against 41 us; 300k rows, 64 -> 128 213 us
+    // against 171 us).
+    if (k.wave && c.kernel == 0) {
+      const int64_t tiles = ceil_div(c_cols, bn);
+      if (tiles > 2 && (double)tiles * c_red * (double)rows_dst > 6e7) k.wave = false;
+    }
+  }
+  if (!k.wave && c.tile_n == 16) return SPCONV_EINVAL;
+  k.tile_m = k.wave ? 16 : tile_m;
+  k.tile_n = c.tile_n;
+  // few row tiles: 64-column tiles double the workgroups of the tiled kernel (10k rows, 256 -> 256:
+  // 91 us against 104 us)
+  if (!k.wave && c.tile_n == 0 && dtype != SPCONV_F32 && tile_m == 64 && c_cols > 64 &&
+      ceil_div(rows_dst, 64) * ceil_div(c_cols, 128) < 400)
+    k.tile_n = 64;
+  *out = k;
+  return SPCONV_OK;
+}
+
 // ---- the fixed scratch array of the entry point that allocates nothing --------------------
 // Split partial sums of spconv_fwd_noalloc live here instead of in a buffer of the kmap.  In
 // host code the array's name is only a stand-in: the device address comes from
@@ -226,30 +271,10 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   }
   const int c_red = os.dgrad ? C_out : C_in;
   const int c_cols = os.dgrad ? C_in : C_out;
-  if ((!cfg || cfg->tile_m == 0) && dtype != SPCONV_F32) {
-    // automatic tile height (measured on unsorted maps, 10k .. 300k rows): 128 rows when that still
-    // leaves several workgroups per CU, or when the reduction is long (>= 128 channels) and there
-    // are enough rows for a workgroup per CU anyway; 64 rows otherwise
-    c.tile_m = (ceil_div(rows_dst, 128) * ceil_div(c_cols, 128) >= 2048 || (rows_dst >= 25000 && c_red >= 128)) ? 128 : 64;
-  }
-  bool wave = false;
-  if (c.kernel != 2) {
-    const int bn = igemm_wave_pick_bn(km->V, c.n_split, c_red, c_cols, c.tile_n, nullptr);
-    wave = bn > 0;
-    if (!wave && c.kernel == 1) return SPCONV_EINVAL;
-    // Automatic choice: the LDS-resident kernel gathers the input once per column tile.  It wins
-    // while the output is at most two tiles wide (64 -> 64 is 2 x 32) and, beyond that, while
-    // tiles x reduced channels x rows stays small: few rows leave the tiled kernel without enough
-    // workgroups, many rows make the repeated gathers the larger cost (measured: 100k rows,
-    // 64 -> 256 in eight tiles 89 us against 114 us; 128 -> 128 in eight 16-column tiles 160 us
-    // against 131 us; 10k rows, 128 -> 128 25 us against 41 us; 300k rows, 64 -> 128 213 us
-    // against 171 us).
-    if (wave && c.kernel == 0) {
-      const int64_t tiles = ceil_div(c_cols, bn);
-      if (tiles > 2 && (double)tiles * c_red * (double)rows_dst > 6e7) wave = false;
-    }
-  }
-  if (!wave && c.tile_n == 16) return SPCONV_EINVAL;
+  KernelChoice kc;
+  SPC_TRY(choose_kernel(km->V, rows_dst, c_red, c_cols, dtype, cfg && cfg->tile_m != 0, c, &kc));
+  const bool wave = kc.wave;
+  c.tile_m = wave ? c.tile_m : kc.tile_m;
   IgemmPlan* plan = nullptr;
   if (prepared_only) {
     if (c.n_split > km->V) return SPCONV_EINVAL;
@@ -267,12 +292,7 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   a.dgrad = os.dgrad;
   a.mirror = os.mirror;
   a.dtype = dtype;
-  a.tile_n = c.tile_n;
-  // few row tiles: 64-column tiles double the workgroups of the tiled kernel (10k rows, 256 -> 256:
-  // 91 us against 104 us)
-  if (!wave && c.tile_n == 0 && dtype != SPCONV_F32 && c.tile_m == 64 && c_cols > 64 &&
-      ceil_div(rows_dst, 64) * ceil_div(c_cols, 128) < 400)
-    a.tile_n = 64;
+  a.tile_n = kc.tile_n;
   const int c_dst = os.dgrad ? C_in : C_out;
   if (plan->parts > 1) {
     const size_t need = (size_t)plan->parts * plan->rows * c_dst * sizeof(float);
@@ -857,6 +877,60 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
     total += best;
   }
   if (group_us) *group_us = total;
+  return SPCONV_OK;
+}
+
+SPCONV_API int spconv_describe_launch(int K, int64_t rows, int64_t rows_src, int C_red, int C_cols, spconv_dtype dtype,
+                                      const spconv_config* cfg, int dgrad, spconv_launch_info* out) {
+  if (!out || !dtype_ok(dtype) || (K != 1 && K != 2 && K != 3) || rows < 0 || rows_src < 0 || (dgrad != 0 && dgrad != 1))
+    return SPCONV_EINVAL;
+  std::memset(out, 0, sizeof(*out));
+  SPC_TRY(check_channels(C_red, C_cols, dtype));
+  spconv_config c;
+  SPC_TRY(resolve_config(cfg, dtype, &c));
+  if (c.kernel == 3) return SPCONV_EINVAL;  // (fetch-on-demand launches are sized by the pair lists, not by these shapes)
+  const int V = K * K * K;
+  if (c.n_split > V) return SPCONV_EINVAL;
+  if (rows == 0) return SPCONV_OK;  // nothing is launched
+  KernelChoice kc;
+  SPC_TRY(choose_kernel(V, rows, C_red, C_cols, dtype, cfg && cfg->tile_m != 0, c, &kc));
+  PlanShape ps;
+  SPC_TRY(plan_shape(V, rows, c.n_split, kc.tile_m, &ps));
+  out->kernel = kc.wave ? 1 : 2;
+  out->tile_m = kc.tile_m;
+  out->parts = ps.parts;
+  out->rows_pad = ps.rows_pad;
+  out->n_tiles = ps.n_tiles;
+  for (int i = 0; i < ps.parts; ++i) {
+    out->lo[i] = ps.lo[i];
+    out->width[i] = ps.width[i];
+    out->map_elems[i] = (int64_t)ps.rows_pad * (c.n_split == 0 ? V : ps.width[i]);
+  }
+  out->sorted = c.n_split > 0;
+  if (kc.wave) {
+    WaveShape w;
+    SPC_TRY(igemm_wave_shape(V, c.n_split, rows, rows_src, C_red, C_cols, kc.tile_n, &w));
+    out->tile_n = w.bn;
+    out->k_steps = w.ks;
+    out->waves = w.waves;
+    out->threads = w.threads;
+    out->lds_bytes = (int64_t)w.lds_bytes;
+    out->slab_bytes = w.slab_bytes;
+    out->slab_map_bytes = w.map_bytes;
+    for (int i = 0; i < 3; ++i) out->grid[i] = (int32_t)w.grid[i];
+    out->xcd_ranges = ((c.flags & SPCONV_FLAG_SLABS) || rows >= (1 << 20)) && c.n_split > 0 && w.grid[0] % 8 == 0;
+  } else {
+    TileShape t;
+    SPC_TRY(igemm_tile_shape(V, c.n_split, rows, rows_src, C_red, C_cols, kc.tile_m, kc.tile_n, dtype == SPCONV_F32,
+                             dgrad != 0, &t));
+    out->tile_m = t.bm;
+    out->tile_n = t.bn;
+    out->k_steps = t.kc;
+    out->waves = t.nw;
+    out->threads = t.threads;
+    out->lds_bytes = (int64_t)t.lds_bytes;
+    for (int i = 0; i < 3; ++i) out->grid[i] = (int32_t)t.grid[i];
+  }
   return SPCONV_OK;
 }
 

@@ -174,6 +174,38 @@ int radix_sort_u32(uint32_t* key_a, uint32_t* key_b, int32_t* val_a, int32_t* va
 int radix_sort_u64(uint64_t* key_a, uint64_t* key_b, int64_t n, uint64_t varying, uint32_t* hist,
                    hipStream_t st, int* in_b);
 
+// ---- launch arithmetic.  Everything a launch derives from the layer's shape is computed by these
+// host functions and by nothing else (the run functions call them), so that it can be checked on
+// the CPU: spconv_describe_launch reports it, and a test walks the index formulas of the kernels
+// over a grid of shapes.  They return SPCONV_EINVAL for shapes the kernels do not take.
+struct PlanShape {  // plan_get: parts of the offset range, padded rows, tiles
+  int parts = 1;
+  int lo[kMaxSplit] = {0}, width[kMaxSplit] = {0};
+  size_t map_off[kMaxSplit] = {0};  // element offsets of the parts' reordered maps
+  size_t map_elems = 0;             // all parts together
+  int64_t rows_pad = 0, n_tiles = 0;
+};
+int plan_shape(int V, int64_t rows, int n_split, int tile_m, PlanShape* s);
+
+struct WaveShape {  // igemm_wave_run (kernel 1)
+  int bn = 0, waves = 0, ks = 0, max_width = 0, threads = 0;
+  int slab_bytes = 0, map_bytes = 0;
+  size_t lds_bytes = 0;
+  unsigned grid[3] = {0, 0, 0};
+  unsigned feats_bytes = 0;
+};
+int igemm_wave_shape(int V, int n_split, int64_t rows, int64_t rows_src, int c_red, int c_out, int tile_n,
+                     WaveShape* s);
+
+struct TileShape {  // igemm_run (kernel 2 and the fp32 kernel)
+  int bm = 0, bn = 0, kc = 0, nw = 0, threads = 0;
+  size_t lds_bytes = 0;
+  unsigned grid[3] = {0, 0, 0};
+  unsigned feats_bytes = 0;
+};
+int igemm_tile_shape(int V, int n_split, int64_t rows, int64_t rows_src, int c_red, int c_out, int tile_m, int tile_n,
+                     bool f32, bool dgrad, TileShape* s);
+
 // ---- plan.hip
 // tile_m may carry kPlanSlabs (a plan of its own in the cache)
 int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out);

@@ -43,6 +43,10 @@ struct IgemmParams {
   int dgrad, mirror;
   int heavy_first;   // sorted maps: tiles late in the sort order hold the most offsets; start them first
   unsigned feats_bytes;  // size of the gathered tensor (16-bit kernels address it through a buffer descriptor)
+  // sizes of the tables that a tile index reaches (read through range-checked buffer descriptors:
+  // beyond the end zeros, no access): each part's map, the permutation (rows_pad entries), the tile masks
+  unsigned map_part_bytes[kMaxSplit];
+  unsigned rows_pad_bytes, tiles_bytes;
 };
 
 template <typename T> struct Mfma;
@@ -127,7 +131,8 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
   const int n0 = blockIdx.y * BN;
   const int width = p.width[part], lo = p.lo[part];
   const long long row0 = tile * BM;
-  const unsigned tmask = p.tilemask[part][tile];
+  const unsigned tmask = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(p.tilemask[part], p.tiles_bytes),
+                                                                       (unsigned)tile * 4u, 0, 0);
   const int c_red = p.c_red;
   const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
   const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 2));
@@ -135,18 +140,21 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
 
   {  // map slab and output rows of this tile: every load is issued before the first one is awaited
     // (the slab is BM * width consecutive ints; tiles start on 256-byte boundaries)
-    // through a buffer descriptor that ends with the slab: a load past the end returns zeros, so
-    // no load sits behind a branch and all of them are in flight together
+    // through a buffer descriptor over the part's map that ends with the slab: a load past the
+    // end returns zeros, so no load sits behind a branch and all of them are in flight together
     constexpr int SLAB_IT = (BM * 27 / 4 + NT - 1) / NT;
     const int n4 = BM * width / 4;
-    const __amdgpu_buffer_rsrc_t m_rsrc = make_rsrc(p.map[part] + row0 * width, (unsigned)n4 * 16u);
+    const unsigned slab_begin = (unsigned)(row0 * width) * 4u, slab_end = slab_begin + (unsigned)n4 * 16u;
+    const __amdgpu_buffer_rsrc_t m_rsrc =
+        make_rsrc(p.map[part], slab_end < p.map_part_bytes[part] ? slab_end : p.map_part_bytes[part]);
     uint4 slab[SLAB_IT];
 #pragma unroll
-    for (int i = 0; i < SLAB_IT; ++i) slab[i] = buf_load16(m_rsrc, (unsigned)(tid + NT * i) * 16u);
+    for (int i = 0; i < SLAB_IT; ++i) slab[i] = buf_load16(m_rsrc, slab_begin + (unsigned)(tid + NT * i) * 16u);
     const int* pm = p.perm[part];
+    const __amdgpu_buffer_rsrc_t p_rsrc = make_rsrc(pm, p.rows_pad_bytes);
     for (int r = tid; r < BM; r += NT) {
       const long long g = row0 + r;
-      permS[r] = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+      permS[r] = pm ? __builtin_amdgcn_raw_buffer_load_b32(p_rsrc, (unsigned)g * 4u, 0, 0) : (g < p.rows ? (int)g : -1);
     }
 #pragma unroll
     for (int i = 0; i < SLAB_IT; ++i) {
@@ -391,17 +399,21 @@ __global__ void __launch_bounds__(256) k_igemm_f32(const IgemmParams p) {
   const int n0 = blockIdx.y * F32_BN;
   const int width = p.width[part], lo = p.lo[part];
   const long long row0 = tile * F32_BM;
-  const unsigned tmask = p.tilemask[part][tile];
+  const unsigned tmask = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(p.tilemask[part], p.tiles_bytes),
+                                                                       (unsigned)tile * 4u, 0, 0);
   const float* feats = reinterpret_cast<const float*>(p.feats);
   const float* wts = reinterpret_cast<const float*>(p.weights);
   const int c_red = p.c_red;
   {
-    const int* mp = p.map[part] + row0 * width;
-    for (int e = tid; e < F32_BM * width; e += 256) mapS[e] = mp[e];
+    const __amdgpu_buffer_rsrc_t m_rsrc = make_rsrc(p.map[part], p.map_part_bytes[part]);
+    const unsigned slab_begin = (unsigned)(row0 * width) * 4u;
+    for (int e = tid; e < F32_BM * width; e += 256)
+      mapS[e] = __builtin_amdgcn_raw_buffer_load_b32(m_rsrc, slab_begin + (unsigned)e * 4u, 0, 0);
     const int* pm = p.perm[part];
     if (tid < F32_BM) {
       const long long g = row0 + tid;
-      permS[tid] = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+      permS[tid] = pm ? __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(pm, p.rows_pad_bytes), (unsigned)g * 4u, 0, 0)
+                      : (g < p.rows ? (int)g : -1);
     }
   }
   __syncthreads();
@@ -550,6 +562,74 @@ int launch_bm(const IgemmParams& p, int bm, int bn, int kc, int nw, dim3 grid, h
 
 }  // namespace
 
+namespace {
+// dynamic LDS of the tiled 16-bit kernel for a tile shape it is built for (0: no such kernel)
+template <int BM, int BN> size_t tile_lds_kc(int kc, bool dgrad) {
+  if (kc == 64) return dgrad ? IgemmSmem<BM, BN, 64, true>::total : IgemmSmem<BM, BN, 64, false>::total;
+  if (kc == 32) return dgrad ? IgemmSmem<BM, BN, 32, true>::total : IgemmSmem<BM, BN, 32, false>::total;
+  return 0;
+}
+template <int BM> size_t tile_lds_bn(int bn, int kc, bool dgrad) {
+  switch (bn) {
+    case 32: return tile_lds_kc<BM, 32>(kc, dgrad);
+    case 64: return tile_lds_kc<BM, 64>(kc, dgrad);
+    case 128: return tile_lds_kc<BM, 128>(kc, dgrad);
+  }
+  return 0;
+}
+size_t tile_lds_bytes(int bm, int bn, int kc, bool dgrad) {
+  switch (bm) {
+    case 64: return tile_lds_bn<64>(bn, kc, dgrad);
+    case 128: return tile_lds_bn<128>(bn, kc, dgrad);
+    case 256: return tile_lds_bn<256>(bn, kc, dgrad);
+  }
+  return 0;
+}
+}  // namespace
+
+int igemm_tile_shape(int V, int n_split, int64_t rows, int64_t rows_src, int c_red, int c_out, int tile_m, int tile_n,
+                     bool f32, bool dgrad, TileShape* s) {
+  *s = TileShape{};
+  const int q = f32 ? 4 : 8;
+  if (rows < 1 || rows_src < 0 || c_red < q || c_out < q || c_red % q || c_out % q) return SPCONV_EINVAL;
+  if (f32) tile_m = F32_BM;
+  PlanShape ps;
+  SPC_TRY(plan_shape(V, rows, n_split, tile_m, &ps));
+  if ((uint64_t)ps.rows_pad * 27 * 4 >= 0xFFFF0000ull) return SPCONV_EINVAL;  // maps are read through 32-bit buffer offsets
+  s->bm = tile_m;
+  if (f32) {
+    s->bn = F32_BN;
+    s->kc = F32_KC;
+    s->nw = 4;
+    s->threads = 256;
+    s->lds_bytes = sizeof(float) * (F32_BM * (F32_KC + 1) + F32_KC * (F32_BN + 4)) + sizeof(int) * (F32_BM * 27 + F32_BM);
+    s->grid[0] = (unsigned)ps.n_tiles;
+    s->grid[1] = (unsigned)ceil_div(c_out, F32_BN);
+    s->grid[2] = (unsigned)ps.parts;
+    return SPCONV_OK;
+  }
+  const uint64_t bytes = (uint64_t)rows_src * c_red * 2;
+  if (bytes >= 0xFFFFC000ull) return SPCONV_EINVAL;  // buffer descriptors address 32 bits
+  s->feats_bytes = (unsigned)bytes;
+  int bn = tile_n;
+  if (bn == 0) bn = c_out <= 32 ? 32 : (c_out <= 64 ? 64 : 128);
+  if (bn != 32 && bn != 64 && bn != 128) return SPCONV_EINVAL;
+  s->bn = bn;
+  s->kc = (c_red % 64 == 0) ? 64 : 32;
+  // Eight waves per workgroup where the reduction runs in 32-channel chunks (channel counts that
+  // are not multiples of 64) on tiles of 128 rows or more: the steps are short there and twice the
+  // waves hide their load latency (300k voxels, 96 -> 96: 150 us against 219 us); with 64-channel
+  // chunks four waves with larger per-wave tiles are faster (256 -> 256: 602 us against 696 us).
+  s->nw = (s->kc == 32 && tile_m >= 128) ? 8 : 4;
+  s->threads = s->nw * 64;
+  s->lds_bytes = tile_lds_bytes(tile_m, bn, s->kc, dgrad);
+  if (s->lds_bytes == 0 || s->lds_bytes > 160 * 1024) return SPCONV_EINVAL;
+  s->grid[0] = (unsigned)ps.n_tiles;
+  s->grid[1] = (unsigned)ceil_div(c_out, bn);
+  s->grid[2] = (unsigned)ps.parts;
+  return SPCONV_OK;
+}
+
 int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
               hipStream_t st) {
   if (plan.rows == 0) return SPCONV_OK;
@@ -567,6 +647,11 @@ int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan,
   p.mirror = a.mirror;
   p.c_red = a.dgrad ? a.C_out : a.C_in;
   p.c_out = a.dgrad ? a.C_in : a.C_out;
+  const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
+  TileShape sh;
+  SPC_TRY(igemm_tile_shape(km->V, plan.n_split, plan.rows, rows_src, p.c_red, p.c_out, plan.tile_m, a.tile_n,
+                           a.dtype == SPCONV_F32, a.dgrad != 0, &sh));
+  if (sh.bm != plan.tile_m || sh.grid[0] != (unsigned)plan.n_tiles) return SPCONV_EINVAL;  // (the plan was cut for another tile height)
   const int64_t tiles_alloc = plan.n_tiles > 0 ? plan.n_tiles : 1;
   for (int i = 0; i < plan.parts; ++i) {
     p.lo[i] = plan.lo[i];
@@ -579,33 +664,22 @@ int igemm_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan,
       p.map[i] = plan.maps.as<int>() + plan.map_off[i];
       p.perm[i] = plan.perm.as<int>() + (size_t)i * plan.rows_pad;
     }
+    p.map_part_bytes[i] = (unsigned)((uint64_t)plan.rows_pad * plan.width[i] * 4);
   }
+  p.rows_pad_bytes = (unsigned)((uint64_t)plan.rows_pad * 4);
+  p.tiles_bytes = (unsigned)((uint64_t)plan.n_tiles * 4);
+  p.feats_bytes = sh.feats_bytes;
+  dim3 grid(sh.grid[0], sh.grid[1], sh.grid[2]);
   if (a.dtype == SPCONV_F32) {
-    dim3 grid((unsigned)plan.n_tiles, (unsigned)ceil_div(p.c_out, F32_BN), (unsigned)plan.parts);
     hipLaunchKernelGGL(k_igemm_f32, grid, dim3(256), 0, st, p);
     SPC_LAUNCH_CHECK();
     return SPCONV_OK;
   }
-  {
-    const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
-    const uint64_t bytes = (uint64_t)rows_src * p.c_red * 2;
-    if (bytes >= 0xFFFFC000ull) return SPCONV_EINVAL;  // buffer descriptors address 32 bits
-    p.feats_bytes = (unsigned)bytes;
-  }
-  int bn = a.tile_n;
-  if (bn == 0) bn = p.c_out <= 32 ? 32 : (p.c_out <= 64 ? 64 : 128);
-  const int kc = (p.c_red % 64 == 0) ? 64 : 32;
-  dim3 grid((unsigned)plan.n_tiles, (unsigned)ceil_div(p.c_out, bn), (unsigned)plan.parts);
   // tiles late in a bitmask-sorted order hold the most offsets: they start first, so that the
   // grid does not end on its longest workgroups
   p.heavy_first = plan.n_split > 0 ? 1 : 0;
-  // Eight waves per workgroup where the reduction runs in 32-channel chunks (channel counts that
-  // are not multiples of 64) on tiles of 128 rows or more: the steps are short there and twice the
-  // waves hide their load latency (300k voxels, 96 -> 96: 150 us against 219 us); with 64-channel
-  // chunks four waves with larger per-wave tiles are faster (256 -> 256: 602 us against 696 us).
-  const int nw = (kc == 32 && plan.tile_m >= 128) ? 8 : 4;
-  if (a.dtype == SPCONV_F16) return launch_bm<_Float16>(p, plan.tile_m, bn, kc, nw, grid, st);
-  return launch_bm<__bf16>(p, plan.tile_m, bn, kc, nw, grid, st);
+  if (a.dtype == SPCONV_F16) return launch_bm<_Float16>(p, plan.tile_m, sh.bn, sh.kc, sh.nw, grid, st);
+  return launch_bm<__bf16>(p, plan.tile_m, sh.bn, sh.kc, sh.nw, grid, st);
 }
 
 int split_reduce(const float* partial, int parts, int64_t rows, int c, spconv_dtype dtype, void* out,

@@ -64,6 +64,9 @@ struct WaveParams {
   int slab_bytes;  // per-wave LDS slab: map rows, then the output staging tile
   int map_bytes;   // size of the map part of the slab
   unsigned feats_bytes;  // size of the gathered tensor, < 2^32 - 16 KiB
+  unsigned map_part_bytes[kMaxSplit];  // sizes of the tables a plan index reaches: each part's map,
+  unsigned rows_pad_bytes;             //   the permutation and the row masks (rows_pad entries),
+  unsigned blocks_bytes;               //   the block masks (n_blocks entries)
   int quad;     // gathers issued by quads of lanes per row and permuted to the operand layout
   int xcd_ranges;  // blocks are dealt to the 8 XCDs as contiguous ranges (gridDim.x is a multiple of 8)
 };
@@ -166,16 +169,26 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   int mreg[kMapVecs];
   unsigned bm_next = 0;
   int orow_next = -1;
+  // Every table that a block index reaches is read through a range-checked buffer descriptor
+  // (beyond the end: zeros, no access), like the gathered rows: a wrong index cannot fault.
   auto prefetch_block = [&](long long b) {
-    const int* mp = map_part + b * map_len;
+    const __amdgpu_buffer_rsrc_t m_rsrc = make_rsrc(map_part, p.map_part_bytes[part]);
+    const unsigned mbase = (unsigned)(b * map_len) * 4u;
 #pragma unroll
     for (int i = 0; i < kMapVecs; ++i) {
       const int e = lane + 64 * i;
-      mreg[i] = mp[e < map_len ? e : map_len - 1];
+      mreg[i] = __builtin_amdgcn_raw_buffer_load_b32(m_rsrc, e < map_len ? mbase + (unsigned)e * 4u : 0xFFFFFFFFu, 0, 0);
     }
-    bm_next = p.rowmask ? p.rowmask[b * 16 + arow] : bmask[b];  // OR-reduced when the block starts
+    const unsigned g4 = (unsigned)(b * 16 + arow) * 4u;
+    if (p.rowmask)  // OR-reduced when the block starts
+      bm_next = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(p.rowmask, p.rows_pad_bytes), g4, 0, 0);
+    else
+      bm_next = (unsigned)__builtin_amdgcn_raw_buffer_load_b32(make_rsrc(bmask, p.blocks_bytes), (unsigned)b * 4u, 0, 0);
     const long long g = b * 16 + arow;
-    orow_next = pm ? pm[g] : (g < p.rows ? (int)g : -1);
+    if (pm)
+      orow_next = __builtin_amdgcn_raw_buffer_load_b32(make_rsrc(pm, p.rows_pad_bytes), g4, 0, 0);
+    else
+      orow_next = g < p.rows ? (int)g : -1;
   };
 
   uint4 fr[DEPTH][KS];
@@ -460,6 +473,41 @@ int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int
   return 0;
 }
 
+int igemm_wave_shape(int V, int n_split, int64_t rows, int64_t rows_src, int c_red, int c_out, int tile_n,
+                     WaveShape* s) {
+  *s = WaveShape{};
+  if (rows < 1 || rows_src < 0 || c_red < 8 || c_out < 8 || c_red % 8 || c_out % 8) return SPCONV_EINVAL;
+  PlanShape ps;
+  SPC_TRY(plan_shape(V, rows, n_split, 16, &ps));
+  const uint64_t feats_bytes = (uint64_t)rows_src * c_red * 2;
+  // buffer descriptors address 32 bits; "absent" is the byte offset 0xFFFF0000, and lanes beyond a
+  // channel count that is not a multiple of 32 add 2^31 to stay out of range
+  if (feats_bytes >= (c_red % 32 ? 0x7FFF0000ull : 0xFFFF0000ull)) return SPCONV_EINVAL;
+  s->feats_bytes = (unsigned)feats_bytes;
+  int waves = 8;
+  s->bn = igemm_wave_pick_bn(V, n_split, c_red, c_out, tile_n, &waves);
+  if (s->bn == 0) return SPCONV_EINVAL;
+  s->waves = waves;
+  s->threads = waves * 64;
+  s->ks = (c_red + 31) / 32;
+  for (int i = 0; i < ps.parts; ++i) s->max_width = std::max(s->max_width, ps.width[i]);
+  // the map, the permutation and the masks are read through 32-bit buffer offsets as well
+  if ((uint64_t)ps.rows_pad * s->max_width * 4 >= 0xFFFF0000ull) return SPCONV_EINVAL;
+  s->slab_bytes = (int)slab_bytes_for(s->max_width, s->bn, ps.parts);
+  s->map_bytes = (int)map_bytes_for(s->max_width);
+  s->lds_bytes = (size_t)s->max_width * s->bn * s->ks * 64 + (size_t)waves * s->slab_bytes;
+  if (s->lds_bytes > kLdsBudget) return SPCONV_EINVAL;
+  const int n_tiles_n = (int)ceil_div(c_out, s->bn);
+  // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block
+  int64_t per_slice = std::max<int64_t>(1, 256 / ((int64_t)n_tiles_n * ps.parts));
+  per_slice = std::min<int64_t>(per_slice, ceil_div(ps.n_tiles, waves));
+  if (per_slice > 8) per_slice = per_slice / 8 * 8;  // (whole rounds over the eight XCDs)
+  s->grid[0] = (unsigned)per_slice;
+  s->grid[1] = (unsigned)n_tiles_n;
+  s->grid[2] = (unsigned)ps.parts;
+  return SPCONV_OK;
+}
+
 int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& plan, const IgemmArgs& a,
                    hipStream_t st) {
   if (plan.rows == 0) return SPCONV_OK;
@@ -480,21 +528,13 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
   p.c_red = a.dgrad ? a.C_out : a.C_in;
   p.c_out = a.dgrad ? a.C_in : a.C_out;
   const int64_t rows_src = (&side == &km->out_side) ? km->n_in : km->n_out;
-  const uint64_t feats_bytes = (uint64_t)rows_src * p.c_red * 2;
-  // buffer descriptors address 32 bits; "absent" is the byte offset 0xFFFF0000, and lanes beyond a
-  // channel count that is not a multiple of 32 add 2^31 to stay out of range
-  if (feats_bytes >= (p.c_red % 32 ? 0x7FFF0000ull : 0xFFFF0000ull)) return SPCONV_EINVAL;
-  p.feats_bytes = (unsigned)feats_bytes;
-  int waves = 8;
-  const int bn = igemm_wave_pick_bn(km->V, plan.n_split, p.c_red, p.c_out, a.tile_n, &waves);
-  if (bn == 0) return SPCONV_EINVAL;
-  const int ks = (p.c_red + 31) / 32;
-  int max_width = 0;
+  WaveShape sh;
+  SPC_TRY(igemm_wave_shape(km->V, plan.n_split, plan.rows, rows_src, p.c_red, p.c_out, a.tile_n, &sh));
+  p.feats_bytes = sh.feats_bytes;
   const int64_t tiles_alloc = plan.n_tiles > 0 ? plan.n_tiles : 1;
   for (int i = 0; i < plan.parts; ++i) {
     p.lo[i] = plan.lo[i];
     p.width[i] = plan.width[i];
-    max_width = std::max(max_width, plan.width[i]);
     p.blkmask[i] = plan.tilemask.as<unsigned>() + (size_t)i * tiles_alloc;
     if (plan.n_split == 0) {
       p.map[i] = side.map.as<int>();
@@ -504,20 +544,17 @@ int igemm_wave_run(const spconv_kmap* km, const SideMap& side, const IgemmPlan& 
       p.map[i] = plan.maps.as<int>() + plan.map_off[i];
       p.perm[i] = plan.perm.as<int>() + (size_t)i * plan.rows_pad;
     }
+    p.map_part_bytes[i] = (unsigned)((uint64_t)plan.rows_pad * plan.width[i] * 4);
   }
-  p.slab_bytes = (int)slab_bytes_for(max_width, bn, plan.parts);
-  p.map_bytes = (int)map_bytes_for(max_width);
-  const size_t smem = (size_t)max_width * bn * ks * 64 + (size_t)waves * p.slab_bytes;
-  const int n_tiles_n = (int)ceil_div(p.c_out, bn);
-  // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block
-  int64_t per_slice = std::max<int64_t>(1, 256 / ((int64_t)n_tiles_n * plan.parts));
-  per_slice = std::min<int64_t>(per_slice, ceil_div(plan.n_tiles, waves));
-  if (per_slice > 8) per_slice = per_slice / 8 * 8;
-  p.xcd_ranges = plan.slabs && per_slice % 8 == 0;  // (contiguous ranges of a purely bitmask-sorted order are unequal work)
+  p.rows_pad_bytes = (unsigned)((uint64_t)plan.rows_pad * 4);
+  p.blocks_bytes = (unsigned)((uint64_t)plan.n_tiles * 4);
+  p.slab_bytes = sh.slab_bytes;
+  p.map_bytes = sh.map_bytes;
+  p.xcd_ranges = plan.slabs && sh.grid[0] % 8 == 0;  // (contiguous ranges of a purely bitmask-sorted order are unequal work)
   p.quad = plan.n_split > 0;
-  dim3 grid((unsigned)per_slice, (unsigned)n_tiles_n, (unsigned)plan.parts);
-  if (a.dtype == SPCONV_F16) return launch_wave_ks<_Float16>(ks, bn / 16, p, grid, waves * 64, smem, st);
-  return launch_wave_ks<__bf16>(ks, bn / 16, p, grid, waves * 64, smem, st);
+  dim3 grid(sh.grid[0], sh.grid[1], sh.grid[2]);
+  if (a.dtype == SPCONV_F16) return launch_wave_ks<_Float16>(sh.ks, sh.bn / 16, p, grid, sh.threads, sh.lds_bytes, st);
+  return launch_wave_ks<__bf16>(sh.ks, sh.bn / 16, p, grid, sh.threads, sh.lds_bytes, st);
 }
 
 }  // namespace spc

@@ -363,13 +363,33 @@ __global__ void __launch_bounds__(256)
 
 }  // namespace
 
-int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out) {
+int plan_shape(int V, int64_t rows, int n_split, int tile_m, PlanShape* s) {
   // every part needs at least one offset (a K = 1 map has a single one): the kernels index the
   // last column of a part's map
-  if (n_split < 0 || n_split > kMaxSplit || n_split > km->V) return SPCONV_EINVAL;
+  if (V < 1 || V > 27 || rows < 0 || n_split < 0 || n_split > kMaxSplit || n_split > V) return SPCONV_EINVAL;
+  if (tile_m != 16 && tile_m != 64 && tile_m != 128 && tile_m != 256) return SPCONV_EINVAL;
+  *s = PlanShape{};
+  s->parts = std::max(1, n_split);
+  s->rows_pad = round_up(rows > 0 ? rows : 1, kRowPad);  // a multiple of every tile height: tiles never run past the map
+  s->n_tiles = ceil_div(rows, tile_m);
+  size_t off = 0;
+  for (int i = 0; i < s->parts; ++i) {
+    s->lo[i] = (int)(((int64_t)i * V) / s->parts);
+    s->width[i] = (int)(((int64_t)(i + 1) * V) / s->parts) - s->lo[i];
+    s->map_off[i] = off;
+    off += (size_t)s->rows_pad * s->width[i];
+  }
+  s->map_elems = off;
+  return SPCONV_OK;
+}
+
+int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_t st, IgemmPlan** out) {
   const bool force_slabs = (tile_m & kPlanSlabs) != 0 && n_split > 0;
   auto key = std::make_pair(n_split, n_split > 0 ? tile_m : (tile_m & ~kPlanSlabs));
   tile_m &= ~kPlanSlabs;
+  PlanShape sh;
+  SPC_TRY(plan_shape(km->V, side.rows, n_split, tile_m, &sh));
+  if (side.rows > 0 && sh.rows_pad != side.rows_pad) return SPCONV_EINVAL;  // (the map was padded by the same rule)
   auto it = side.plans.find(key);
   if (it != side.plans.end()) {
     *out = it->second.get();
@@ -380,17 +400,16 @@ int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_
   const int V = km->V;
   p->n_split = n_split;
   p->tile_m = tile_m;
-  p->parts = std::max(1, n_split);
+  p->parts = sh.parts;
   p->rows = side.rows;
-  p->rows_pad = side.rows_pad;
-  p->n_tiles = ceil_div(side.rows, tile_m);
-  size_t off = 0;
+  p->rows_pad = sh.rows_pad;
+  p->n_tiles = sh.n_tiles;
   for (int i = 0; i < p->parts; ++i) {
-    p->lo[i] = (int)(((int64_t)i * V) / p->parts);
-    p->width[i] = (int)(((int64_t)(i + 1) * V) / p->parts) - p->lo[i];
-    p->map_off[i] = off;
-    off += (size_t)p->rows_pad * p->width[i];
+    p->lo[i] = sh.lo[i];
+    p->width[i] = sh.width[i];
+    p->map_off[i] = sh.map_off[i];
   }
+  const size_t off = sh.map_elems;
   const int64_t tiles_alloc = std::max<int64_t>(1, p->n_tiles);
   SPC_TRY(p->tilemask.alloc((size_t)p->parts * tiles_alloc * sizeof(unsigned)));
   const unsigned tile_blocks = blocks_for(tiles_alloc, 4);

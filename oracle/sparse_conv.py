@@ -20,14 +20,20 @@ silent (each is pinned by a test against a dense torch convolution):
   W[delta] (cross-correlation, no kernel flip).
 * Stride 1: P_out = P_in in input order (submanifold).  Stride s > 1:
   P_out = sorted unique floor(p / s), lexicographic in (b, x, y, z).
+* dilate=True (stride-1 convolution whose output set is not the input set, the
+  other reading of Equation 1's "q_k in P_out"): P_out = every q that has at
+  least one input among its neighbours, { q : exists delta in Delta^3(K) with
+  q + delta in P_in }, sorted lexicographically in (b, x, y, z).
 * Transposed convolution with stride s: the caller supplies the fine set F
   (the outputs).  The inputs are Q = P_out(F, s) in that sorted order, and
   y_F[j] = sum over (i, delta) with F_j = s*Q_i + delta of x_Q[i] . W[delta].
 
 Pins (tests/test_oracle_*.py): brute-force O(N^2) neighbour search, the
 submanifold map symmetry, K=1 == dense linear layer, fully occupied grid ==
-torch conv3d / strided conv3d / conv_transpose3d in float64, adjoint
-identities, finite differences and torch.autograd on the dense grid.
+torch conv3d / strided conv3d / conv_transpose3d in float64 (K = 3, 5 and 2),
+a sparse cloud in a zero-filled dense grid == conv3d read on the dilated set
+(and exactly zero off it), adjoint identities, finite differences and
+torch.autograd on the dense grid.
 
 Parity unpinned: the paper's worked 2-D example (22 effective MACs; 34 / 26 /
 22 redundant MACs for unsorted / sorted / three splits, Sections 2.2.3 and
@@ -101,21 +107,32 @@ class KMap:
     transposed: bool
 
 
-def build_kmap(coords, K: int, stride: int = 1, transposed: bool = False) -> KMap:
+def dilated_coords(coords, K: int) -> np.ndarray:
+    """P_out of a stride-1 convolution that writes wherever it can read something: every q with
+    an input at q + delta for some delta in Delta^3(K), sorted."""
+    offs = offsets(K)
+    q = {(b, x - dx, y - dy, z - dz) for (b, x, y, z) in _as_tuples(coords) for (dx, dy, dz) in offs}
+    return np.asarray(sorted(q), dtype=np.int64).reshape(-1, 4)
+
+
+def build_kmap(coords, K: int, stride: int = 1, transposed: bool = False, dilate: bool = False) -> KMap:
     """Kernel map of Equation 1.
 
     transposed=False: coords are P_in; M[n, k] = j with p_j = s*q_n + delta_k.
     transposed=True : coords are the fine output set F; inputs are the coarse
     set Q = downsample_coords(F, s); M[j, k] = i with F_j = s*Q_i + delta_k.
+    dilate=True (stride 1, not transposed): P_out = dilated_coords(coords, K).
     """
     if stride < 1:
         raise ValueError("stride must be >= 1")
+    if dilate and (stride != 1 or transposed):
+        raise ValueError("dilated output sets are defined here for stride 1, not transposed")
     offs = offsets(K)
     pts = _as_tuples(coords)
     _table(pts)  # duplicate check on what the caller handed over
     if not transposed:
         tab = _table(pts)
-        out = downsample_coords(coords, stride)
+        out = dilated_coords(coords, K) if dilate else downsample_coords(coords, stride)
         out_pts = _as_tuples(out) if len(out) else []
         M = np.full((len(out_pts), len(offs)), -1, dtype=np.int64)
         for n, (b, x, y, z) in enumerate(out_pts):
@@ -184,10 +201,14 @@ def wgrad(X, dY, M) -> np.ndarray:
 
 def bitmask(M) -> np.ndarray:
     """Neighbour bitmask of Section 2.2.3: bit k of mask[n] is set iff the
-    k-th neighbour of output n is present."""
+    k-th neighbour of output n is present.  uint32 up to 32 offsets; beyond (K = 5 has 125), an
+    object array of Python integers, which have no width."""
     M = np.asarray(M)
     if M.shape[1] > 32:
-        raise ValueError("bitmask wider than 32 bits")
+        m = np.zeros(M.shape[0], dtype=object)
+        for n in range(M.shape[0]):
+            m[n] = sum(1 << k for k in np.nonzero(M[n] >= 0)[0].tolist())
+        return m
     m = np.zeros(M.shape[0], dtype=np.uint64)
     for k in range(M.shape[1]):
         m |= (M[:, k] >= 0).astype(np.uint64) << np.uint64(k)
@@ -221,11 +242,12 @@ def redundancy(M, tile_rows: int, n_split: int):
     if n_split == 0:
         parts = [(0, V, np.arange(n))]
     else:
-        mask = bitmask(M).astype(np.uint64)
+        mask = [int(v) for v in bitmask(M)]     # Python integers: any width
         parts = []
         for lo, hi in split_ranges(V, n_split):
-            key = (mask >> np.uint64(lo)) & np.uint64((1 << (hi - lo)) - 1)
-            parts.append((lo, hi, np.argsort(key, kind="stable")))
+            key = [(v >> lo) & ((1 << (hi - lo)) - 1) for v in mask]
+            # ascending by the number the bits spell, ties in original order
+            parts.append((lo, hi, np.asarray(sorted(range(n), key=key.__getitem__), dtype=np.int64)))
     for lo, hi, order in parts:
         for t in range(0, n, tile_rows):
             rows = order[t:t + tile_rows]

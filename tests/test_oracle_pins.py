@@ -347,3 +347,109 @@ def test_redundancy_limits():
     assert ex == eff                       # one row per group: nothing is wasted
     ex_all, _ = oc.redundancy(M, 64, 0)
     assert ex_all == 64 * (M >= 0).any(axis=0).sum()
+
+
+# ------------------------------------------- K = 5 and dilated output sets
+def test_offsets_k5():
+    offs = oc.offsets(5)
+    assert len(offs) == 125 and offs[0] == (-2, -2, -2) and offs[62] == (0, 0, 0) and offs[124] == (2, 2, 2)
+    for k, (dx, dy, dz) in enumerate(offs):
+        assert k == 25 * (dx + 2) + 5 * (dy + 2) + (dz + 2)
+
+
+@pytest.mark.parametrize("seed", [6, 7])
+def test_kmap_k5_bruteforce_and_symmetry(seed):
+    c = gen.uniform_cloud(120, 8, seed, lo=-3)
+    km = oc.build_kmap(c, 5, 1)
+    np.testing.assert_array_equal(km.M, _brute_kmap(c, c, 5, 1))
+    for n in range(km.n_out):
+        assert km.M[n, 62] == n
+        for k in range(125):
+            if km.M[n, k] >= 0:
+                assert km.M[km.M[n, k], 124 - k] == n
+
+
+def test_forward_k5_full_grid_is_dense_conv3d_kernel5():
+    """Pins the offset order and sign of K = 5 jointly, as conv3d(padding=1) does for K = 3."""
+    rng = np.random.default_rng(55)
+    G, B = 6, 2
+    c = gen.full_grid(G, B, seed=8)
+    X = rng.standard_normal((len(c), 3))
+    W = rng.standard_normal((125, 3, 4))
+    km = oc.build_kmap(c, 5, 1)
+    Y = oc.forward(X, W, km.M)
+    ref = torch.nn.functional.conv3d(_dense_from_sparse(c, X, B, G), _torch_weight(W, 5), padding=2)
+    for (b, x, y, z), row in zip(c, Y):
+        np.testing.assert_allclose(row, ref[b, :, x, y, z].numpy(), rtol=1e-12, atol=1e-12)
+    # and its gradients through the adjoint identity
+    G_out = rng.standard_normal(Y.shape)
+    lhs = float((Y * G_out).sum())
+    np.testing.assert_allclose(lhs, float((X * oc.dgrad(G_out, W, km.M, km.n_in)).sum()), rtol=1e-12)
+    np.testing.assert_allclose(lhs, float((W * oc.wgrad(X, G_out, km.M)).sum()), rtol=1e-12)
+
+
+def test_wide_bitmask_and_redundancy_beyond_32_offsets():
+    M = oc.build_kmap(gen.uniform_cloud(70, 6, 19), 5, 1).M
+    m = oc.bitmask(M)
+    assert m.dtype == object
+    for n in (0, 13, 69):
+        assert [k for k in range(125) if (int(m[n]) >> k) & 1] == np.nonzero(M[n] >= 0)[0].tolist()
+    for n_split in (0, 1, 3, 4):
+        assert oc.redundancy(M, 4, n_split) == _brute_redundancy(M, 4, n_split)
+
+
+def _brute_dilated(c, K):
+    """Every lattice point of the bounding box (grown by the kernel radius) that has an input in
+    its neighbourhood, by exhaustive search, in lexicographic order."""
+    r = (K - 1) // 2
+    pts = {tuple(int(v) for v in p) for p in c}
+    lo, hi = c[:, 1:].min(0) - r, c[:, 1:].max(0) + r
+    out = []
+    for b in sorted(set(int(v) for v in c[:, 0])):
+        for x, y, z in itertools.product(*(range(int(l), int(h) + 1) for l, h in zip(lo, hi))):
+            if any((b, x + dx, y + dy, z + dz) in pts for dx, dy, dz in itertools.product(range(-r, r + 1), repeat=3)):
+                out.append((b, x, y, z))
+    return np.asarray(out, dtype=np.int64)
+
+
+@pytest.mark.parametrize("seed,lo", [(31, 0), (32, -4)])
+def test_dilated_output_set_bruteforce(seed, lo):
+    c = gen.uniform_cloud(60, 7, seed, lo=lo)
+    c[:20, 0] = 1
+    km = oc.build_kmap(c, 3, 1, dilate=True)
+    want = _brute_dilated(c, 3)
+    np.testing.assert_array_equal(km.out_coords, want)
+    np.testing.assert_array_equal(km.M, _brute_kmap(c, want, 3, 1))
+    assert (km.M >= 0).any(axis=1).all()                 # no output without a neighbour (minimal)
+    assert km.n_out > km.n_in and km.n_in == 60
+    # every input is the centre neighbour of the output at its own coordinate
+    where = {tuple(q): n for n, q in enumerate(km.out_coords.tolist())}
+    for j, p in enumerate(c.tolist()):
+        assert km.M[where[tuple(p)], 13] == j
+    with pytest.raises(ValueError):
+        oc.build_kmap(c, 3, 2, dilate=True)
+    with pytest.raises(ValueError):
+        oc.build_kmap(c, 3, 1, transposed=True, dilate=True)
+
+
+def test_dilated_forward_is_dense_conv3d_and_zero_elsewhere():
+    """A sparse cloud in a zero-filled grid: conv3d(padding=1) of the dense grid equals the
+    dilated sparse convolution on the dilated set and is exactly zero everywhere else (so the set
+    is complete); gradients through the adjoint identities."""
+    rng = np.random.default_rng(77)
+    G = 9
+    c = gen.uniform_cloud(40, G - 2, 41) + np.array([0, 1, 1, 1])     # one cell of margin: the dilated set stays inside
+    X = rng.standard_normal((40, 3))
+    W = rng.standard_normal((27, 3, 5))
+    km = oc.build_kmap(c, 3, 1, dilate=True)
+    Y = oc.forward(X, W, km.M)
+    ref = torch.nn.functional.conv3d(_dense_from_sparse(c, X, 1, G), _torch_weight(W, 3), padding=1)[0].numpy()
+    seen = np.zeros((G, G, G), dtype=bool)
+    for (b, x, y, z), row in zip(km.out_coords, Y):
+        np.testing.assert_allclose(row, ref[:, x, y, z], rtol=1e-12, atol=1e-12)
+        seen[x, y, z] = True
+    assert np.abs(ref[:, ~seen]).max() == 0.0
+    G_out = rng.standard_normal(Y.shape)
+    lhs = float((Y * G_out).sum())
+    np.testing.assert_allclose(lhs, float((X * oc.dgrad(G_out, W, km.M, km.n_in)).sum()), rtol=1e-12)
+    np.testing.assert_allclose(lhs, float((W * oc.wgrad(X, G_out, km.M)).sum()), rtol=1e-12)

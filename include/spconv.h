@@ -25,7 +25,9 @@
  *   - offset index k = ((dx+r)*K + (dy+r))*K + (dz+r), r = (K-1)/2, i.e. x
  *     slowest, z fastest; K is 1 or 3, or 2 with offsets {0, 1}^3 (r = 0: the
  *     paper defines odd K only; with stride 2 this is the non-overlapping
- *     2x2x2 layer); bit k of a neighbour bitmask is 1u<<k;
+ *     2x2x2 layer); bit k of a neighbour bitmask is 1u<<k.  K = 5 (125
+ *     offsets) is refused with SPCONV_EINVAL: bitmasks, sort keys and tile
+ *     masks are 32 bits wide throughout;
  *   - output q reads the input at s*q + delta with W[delta] (no kernel flip);
  *   - stride 1: P_out = P_in in input order; stride s > 1: P_out = unique
  *     floor(p / s), sorted ascending lexicographically in (b, x, y, z);
@@ -157,6 +159,16 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
  * Other map kinds are built synchronously, exactly as by spconv_build_kmap. */
 SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, int stride, int transposed,
                                        void* stream, spconv_kmap** out);
+
+/* Stride-1 convolution whose output set is not the input set (Equation 1, Section 2.1, with
+ * P_out != P_in): P_out = every point that has at least one input in its K^3 neighbourhood,
+ * { q : q + delta in P_in for some delta }, sorted ascending lexicographically in (b, x, y, z); the
+ * map is M[n][k] = j with p_j = q_n + delta_k as always.  K is 1 or 3.  A layer on this kmap grows
+ * the occupied set by one voxel in every direction (the "dilating" convolution of dense-output
+ * heads); forward, dgrad and wgrad run on it like on any other kmap.  Synchronises `stream` once
+ * (size of P_out, error flags).  Errors: EINVAL, ERANGE (also when an output would lie outside the
+ * packable coordinate range), EDUP, ENOMEM, EHIP.  spconv_kmap_transpose refuses such a kmap. */
+SPCONV_API int spconv_build_kmap_dilated(const int32_t* coords, int64_t N, int K, void* stream, spconv_kmap** out);
 
 /* The kmap of the transposed convolution that pairs with km: the same (input, output) pairs with
  * the two roles exchanged, i.e. exactly what spconv_build_kmap returns for the same rows with

@@ -70,6 +70,7 @@ def load_library():
     protos = {
         "spconv_build_kmap": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
         "spconv_build_kmap_async": (i32, [vp, i64, i32, i32, i32, vp, C.POINTER(vp)]),
+        "spconv_build_kmap_dilated": (i32, [vp, i64, i32, vp, C.POINTER(vp)]),
         "spconv_kmap_status": (i32, [vp, vp]),
         "spconv_kmap_transpose": (i32, [vp, vp, C.POINTER(vp)]),
         "spconv_kmap_pointwise": (i32, [vp, i32, vp, C.POINTER(vp)]),
@@ -250,13 +251,20 @@ class KMap:
 
 
 def build_kmap(coords, K: int = 3, stride: int = 1, transposed: bool = False, stream=None,
-               asynchronous: bool = False) -> KMap:
-    """spconv_build_kmap (or spconv_build_kmap_async): coords is an int32 device tensor [N, 4] = (b, x, y, z)."""
+               asynchronous: bool = False, dilate: bool = False) -> KMap:
+    """spconv_build_kmap (or spconv_build_kmap_async, or spconv_build_kmap_dilated with dilate=True):
+    coords is an int32 device tensor [N, 4] = (b, x, y, z)."""
     _dev_tensor(coords, torch.int32)
     if coords.ndim != 2 or coords.shape[1] != 4:
         raise ValueError("coords must be [N, 4]")
     h = C.c_void_p()
     lib = load_library()
+    if dilate:
+        if stride != 1 or transposed or asynchronous:
+            raise ValueError("dilated kmaps are stride 1, not transposed, built synchronously")
+        _check(lib.spconv_build_kmap_dilated(_ptr(coords), coords.shape[0], K, _stream(stream), C.byref(h)),
+               "spconv_build_kmap_dilated")
+        return KMap(h, K)
     fn, name = (lib.spconv_build_kmap_async, "spconv_build_kmap_async") if asynchronous else \
                (lib.spconv_build_kmap, "spconv_build_kmap")
     _check(fn(_ptr(coords), coords.shape[0], K, stride, int(transposed), _stream(stream), C.byref(h)), name)

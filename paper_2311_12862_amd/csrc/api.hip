@@ -346,6 +346,16 @@ SPCONV_API int spconv_build_kmap_async(const int32_t* coords, int64_t N, int K, 
   return kmap_build(coords, N, K, stride, transposed, true, (hipStream_t)stream, out);
 }
 
+SPCONV_API int spconv_build_kmap_dilated(const int32_t* coords, int64_t N, int K, void* stream, spconv_kmap** out) {
+  StreamScope scope((hipStream_t)stream);
+  if (!out) return SPCONV_EINVAL;
+  *out = nullptr;
+  // the candidate set holds up to K^3 points per input row
+  if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 / 27 || (N > 0 && !coords)) return SPCONV_EINVAL;
+  if (K != 1 && K != 3) return SPCONV_EINVAL;
+  return kmap_build(coords, N, K, 1, 0, false, (hipStream_t)stream, out, true);
+}
+
 SPCONV_API int spconv_kmap_pointwise(spconv_kmap* km, int on_outputs, void* stream, spconv_kmap** out) {
   StreamScope scope((hipStream_t)stream);
   if (!out) return SPCONV_EINVAL;
@@ -394,7 +404,7 @@ SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* 
   StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_in > 0)) return SPCONV_EINVAL;
   if (km->n_in == 0) return SPCONV_OK;
-  const DevBuf& b = (km->transposed && km->stride == 1) ? km->out_coords : km->in_coords;
+  const DevBuf& b = (km->transposed && km->stride == 1 && !km->dilated) ? km->out_coords : km->in_coords;
   SPC_HIP(hipMemcpyAsync(dst, b.p, (size_t)km->n_in * 16, hipMemcpyDeviceToDevice, (hipStream_t)stream));
   return SPCONV_OK;
 }

@@ -114,6 +114,7 @@ struct SideMap {      // one output-stationary table: rows x V
 
 struct spconv_kmap {
   int K = 3, V = 27, stride = 1, transposed = 0;
+  int dilated = 0;  // stride 1 with P_out = every point that has an input in its neighbourhood (not P_in)
   int64_t n_in = 0, n_out = 0, n_pairs = -1;
   hipStream_t build_stream = nullptr;
   hipStream_t last_stream = nullptr;  // stream of the most recent call that used this kmap
@@ -145,14 +146,14 @@ struct spconv_kmap {
   bool pending = false;
   int build_status = SPCONV_OK;  // verdict of the build once resolved: every later spconv_kmap_status returns it
   ~spconv_kmap();
-  bool submanifold() const { return stride == 1 && !transposed; }
+  bool submanifold() const { return stride == 1 && !transposed && !dilated; }
 };
 
 namespace spc {
 
 // ---- kmap.hip
 int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
-               spconv_kmap** out);
+               spconv_kmap** out, bool dilate = false);
 int kmap_status(spconv_kmap* km, hipStream_t st);  // resolves a pending asynchronous build (synchronises)
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);

@@ -223,6 +223,65 @@ __global__ void __launch_bounds__(256) k_coarse_unique(const int4* __restrict__ 
   }
 }
 
+// Candidate outputs of a dilated stride-1 map: q = p - delta for every input p and offset delta
+// (Equation 1 with P_out = every point that reads at least one input), de-duplicated and appended
+// like the coarse points above.  One thread per (input row, offset).
+template <int K>
+__global__ void __launch_bounds__(256) k_dilate_unique(const int4* __restrict__ coords, long long n,
+                                                       unsigned long long* tab, int log_cap,
+                                                       unsigned long long* __restrict__ ukeys, Ctl* ctl) {
+  constexpr int V = K * K * K, R = (K - 1) / 2;
+  __shared__ unsigned long long s_or[4], s_and[4];
+  const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  const long long j = t / V;
+  const int k = (int)(t - j * V);
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  bool fresh = false;
+  unsigned long long key = 0, k_or = 0, k_and = ~0ull;
+  if (j < n) {
+    const int4 c = coords[j];
+    const int qx = c.y - (k / (K * K) - R), qy = c.z - ((k / K) % K - R), qz = c.w - (k % K - R);
+    if (coord_ok(c.x, c.y, c.z, c.w)) {  // (an invalid input row is flagged by the insert kernel)
+      if (!coord_ok(c.x, qx, qy, qz)) {
+        atomicOr(&ctl->flags, FLAG_RANGE);  // an output beside the packable range
+      } else {
+        key = pack_key(c.x, qx, qy, qz);
+        const int r = table_insert(tab, log_cap, key, 0, nullptr);
+        fresh = (r == 0);
+        if (r == 2) atomicOr(&ctl->flags, FLAG_FULL);
+        k_or = key;
+        k_and = key;
+      }
+    }
+  }
+  __shared__ unsigned wave_cnt[4];
+  __shared__ unsigned long long block_base;
+  const unsigned long long bal = __ballot(fresh);
+  if (lane == 0) wave_cnt[wave] = (unsigned)__popcll(bal);
+  for (int o = 32; o > 0; o >>= 1) {
+    k_or |= __shfl_xor(k_or, o);
+    k_and &= __shfl_xor(k_and, o);
+  }
+  if (lane == 0) {
+    s_or[wave] = k_or;
+    s_and[wave] = k_and;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned total = wave_cnt[0] + wave_cnt[1] + wave_cnt[2] + wave_cnt[3];
+    block_base = total ? atomicAdd(&ctl->count, (unsigned long long)total) : 0ull;
+    const int slot = (blockIdx.x % kPairSlots) * 16;
+    atomicOr(&ctl->key_or[slot], s_or[0] | s_or[1] | s_or[2] | s_or[3]);
+    atomicAnd(&ctl->key_and[slot], s_and[0] & s_and[1] & s_and[2] & s_and[3]);
+  }
+  __syncthreads();
+  if (fresh) {
+    unsigned before = 0;
+    for (int w = 0; w < wave; ++w) before += wave_cnt[w];
+    ukeys[block_base + before + __popcll(bal & ((1ull << lane) - 1ull))] = key;
+  }
+}
+
 __global__ void __launch_bounds__(256) k_decode_keys(const unsigned long long* __restrict__ keys, int n,
                                                      int4* __restrict__ coords) {
   const int i = blockIdx.x * blockDim.x + threadIdx.x;
@@ -762,17 +821,21 @@ int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
 int kmap_status(spconv_kmap* km, hipStream_t st) { return kmap_status_impl(km, st, false); }
 
 int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
-               spconv_kmap** out) {
+               spconv_kmap** out, bool dilate) {
   std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
   if (!km) return SPCONV_ENOMEM;
   km->K = K;
   km->V = K * K * K;
   km->stride = stride;
   km->transposed = transposed;
+  km->dilated = dilate ? 1 : 0;
   km->build_stream = st;
   km->last_stream = st;
   const int V = km->V;
-  const bool needs_coarse = stride > 1;
+  // builds whose output (or, transposed, input) set is derived from the caller's rows: the coarse
+  // points of a strided map, or the dilated set of a stride-1 map
+  const bool needs_coarse = stride > 1 || dilate;
+  const int64_t cand = dilate ? N * V : N;  // most points that derivation can yield
 
   if (N == 0) {
     km->n_in = km->n_out = 0;
@@ -786,7 +849,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   }
 
   const int4* rows = reinterpret_cast<const int4*>(coords);
-  if (K == 3 && stride == 1 && !transposed) {
+  if (K == 3 && stride == 1 && !transposed && !dilate) {
     SPC_TRY(build_submanifold3(km.get(), rows, N, async, st));
     *out = km.release();
     return SPCONV_OK;
@@ -800,7 +863,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   // Stride-2 3x3x3 maps are built from the input side and need no table of the fine points.  (Only
   // stride 2: there every input row meets the output floor(p/2), so every row writes at least one
   // entry and duplicate rows cannot escape the entry count; at larger strides some rows write none.)
-  const bool from_inputs = (K == 3 && stride == 2 && !transposed);
+  const bool from_inputs = (K == 3 && stride == 2 && !transposed && !dilate);
   // fine table: key(p_j) -> j.  Also the duplicate / range check of the caller's rows.
   const int lc_fine = log2_capacity(N);
   // the caller's rows are kept: they are P_in (and P_out for stride 1), or the fine output set
@@ -818,14 +881,25 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   Ctl h{};
   int64_t U = 0;
   DevBuf coarse_rows;
+  const int lc_coarse = dilate ? log2_capacity(cand) : lc_fine;
   if (needs_coarse) {
-    SPC_TRY(tab_coarse.alloc((size_t)16 << lc_fine));
-    SPC_TRY(fill_u32(tab_coarse.p, (int64_t)4 << lc_fine, 0xFFFFFFFFu, st));
-    SPC_TRY(ukeys_a.alloc((size_t)N * 8));
-    SPC_TRY(ukeys_b.alloc((size_t)N * 8));
-    hipLaunchKernelGGL(k_coarse_unique, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N, stride,
-                       tab_coarse.as<unsigned long long>(), lc_fine, ukeys_a.as<unsigned long long>(), ctl,
-                       from_inputs ? own_rows.as<int4>() : nullptr);
+    SPC_TRY(tab_coarse.alloc((size_t)16 << lc_coarse));
+    SPC_TRY(fill_u32(tab_coarse.p, (int64_t)4 << lc_coarse, 0xFFFFFFFFu, st));
+    SPC_TRY(ukeys_a.alloc((size_t)cand * 8));
+    SPC_TRY(ukeys_b.alloc((size_t)cand * 8));
+    if (dilate) {
+      const unsigned blocks = blocks_for(cand, 256);
+      if (K == 3)
+        hipLaunchKernelGGL(k_dilate_unique<3>, dim3(blocks), dim3(256), 0, st, rows, (long long)N,
+                           tab_coarse.as<unsigned long long>(), lc_coarse, ukeys_a.as<unsigned long long>(), ctl);
+      else
+        hipLaunchKernelGGL(k_dilate_unique<1>, dim3(blocks), dim3(256), 0, st, rows, (long long)N,
+                           tab_coarse.as<unsigned long long>(), lc_coarse, ukeys_a.as<unsigned long long>(), ctl);
+    } else {
+      hipLaunchKernelGGL(k_coarse_unique, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N, stride,
+                         tab_coarse.as<unsigned long long>(), lc_coarse, ukeys_a.as<unsigned long long>(), ctl,
+                         from_inputs ? own_rows.as<int4>() : nullptr);
+    }
     SPC_LAUNCH_CHECK();
   }
   if (needs_coarse) {
@@ -862,14 +936,14 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     if (runs.total <= 32) {
       // ukeys_b's N * 8 bytes hold both dense key buffers
       uint32_t* dense_a = ukeys_b.as<uint32_t>();
-      uint32_t* dense_b = dense_a + N;
+      uint32_t* dense_b = dense_a + cand;
       hipLaunchKernelGGL(k_compress_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st,
                          ukeys_a.as<unsigned long long>(), (int)U, runs, dense_a);
       SPC_LAUNCH_CHECK();
       SPC_TRY(radix_sort_u32(dense_a, dense_b, nullptr, nullptr, U, runs.total, hist.as<uint32_t>(), st, &in_b));
       hipLaunchKernelGGL(k_expand_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, in_b ? dense_b : dense_a, (int)U,
                          runs, coarse_rows.as<int4>(),
-                         want_rank ? tab_coarse.as<unsigned long long>() : (unsigned long long*)nullptr, lc_fine);
+                         want_rank ? tab_coarse.as<unsigned long long>() : (unsigned long long*)nullptr, lc_coarse);
       SPC_LAUNCH_CHECK();
     } else {
       SPC_TRY(radix_sort_u64(ukeys_a.as<uint64_t>(), ukeys_b.as<uint64_t>(), U, varying, hist.as<uint32_t>(), st,
@@ -880,7 +954,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
       SPC_LAUNCH_CHECK();
       if (want_rank) {
         hipLaunchKernelGGL(k_assign_rank, dim3(blocks_for(U, 256)), dim3(256), 0, st, sorted, (int)U,
-                           tab_coarse.as<unsigned long long>(), lc_fine);
+                           tab_coarse.as<unsigned long long>(), lc_coarse);
         SPC_LAUNCH_CHECK();
       }
     }
@@ -892,7 +966,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     km->n_out = U;
     SPC_TRY(alloc_side(km->out_side, U, V, st, true));
     hipLaunchKernelGGL(k_scatter_down3, dim3(blocks_for(ceil_div(N, 8), 4)), dim3(256), 0, st, rows, (int)N, stride,
-                       tab_coarse.as<unsigned long long>(), lc_fine, km->out_side.map.as<int>(), ctl);
+                       tab_coarse.as<unsigned long long>(), lc_coarse, km->out_side.map.as<int>(), ctl);
     SPC_LAUNCH_CHECK();
     hipLaunchKernelGGL((k_mask_from_map<27>), dim3(blocks_for(ceil_div(U, 2), 4)), dim3(256), 0, st,
                        km->out_side.map.as<int>(), (int)U, km->out_side.mask.as<unsigned>(), ctl);
@@ -905,6 +979,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     int* mp = km->out_side.map.as<int>();
     unsigned* mk = km->out_side.mask.as<unsigned>();
     const unsigned long long* tf = tab_fine.as<unsigned long long>();
+    // (a dilated map probes like any other stride-1 map, from its derived output points)
     status = K == 3   ? launch_probe<3>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st)
              : K == 2 ? launch_probe<2>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st)
                       : launch_probe<1>(false, qrows, km->n_out, stride, tf, lc_fine, mp, mk, ctl, st);
@@ -917,9 +992,10 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     SPC_TRY(alloc_side(km->out_side, km->n_out, V, st));
     int* mp = km->out_side.map.as<int>();
     unsigned* mk = km->out_side.mask.as<unsigned>();
-    status = K == 3   ? launch_probe<3>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st)
-             : K == 2 ? launch_probe<2>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st)
-                      : launch_probe<1>(true, rows, N, stride, tab, lc_fine, mp, mk, ctl, st);
+    const int lc = needs_coarse ? lc_coarse : lc_fine;
+    status = K == 3   ? launch_probe<3>(true, rows, N, stride, tab, lc, mp, mk, ctl, st)
+             : K == 2 ? launch_probe<2>(true, rows, N, stride, tab, lc, mp, mk, ctl, st)
+                      : launch_probe<1>(true, rows, N, stride, tab, lc, mp, mk, ctl, st);
     SPC_TRY(status);
   }
   km->out_side.ready = true;
@@ -1017,7 +1093,7 @@ int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap
   // a transposed one).
   const DevBuf* from;
   if (!src->transposed)
-    from = (on_outputs && src->stride > 1) ? &src->out_coords : &src->in_coords;
+    from = (on_outputs && (src->stride > 1 || src->dilated)) ? &src->out_coords : &src->in_coords;
   else
     from = (!on_outputs && src->stride > 1) ? &src->in_coords : &src->out_coords;
   if (rows == 0 || !from->p) {
@@ -1031,6 +1107,7 @@ int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap
 }
 
 int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out) {
+  if (src->dilated) return SPCONV_EINVAL;  // (no build call returns the transposed partner of a dilated map)
   if (src->pending) SPC_TRY(kmap_status(src, st));  // a failed build has no transpose
   SPC_TRY(kmap_build_in_side(src, st));
   // The transposed convolution's output-stationary table is the source's input-side table and the

@@ -376,3 +376,58 @@ def test_transposed_partner_outlives_its_source(sp):
     np.testing.assert_array_equal(again.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)
     up.destroy()
     np.testing.assert_array_equal(again.export().cpu().numpy(), oc.build_kmap(c, 3, 2).M)
+
+
+@pytest.mark.parametrize("seed,n", [(51, 40), (52, 3000)])
+def test_dilated_stride1_output_set(sp, seed, n):
+    """spconv_build_kmap_dilated: P_out = every point with an input in its neighbourhood (Eq. 1 with
+    P_out != P_in).  Output set, map and masks bit-exact against the oracle; features within tolerance."""
+    import torch
+    from _util import TOL, make_layer, norm_err
+    c = gen.lidar_scene(seed, target_n=n) if n > 100 else gen.uniform_cloud(n, 6, seed, lo=-3)
+    ref = oc.build_kmap(c, 3, 1, dilate=True)
+    km = sp.build_kmap(coords_dev(c), 3, 1, dilate=True)
+    assert (km.n_in, km.n_out) == (ref.n_in, ref.n_out) and km.n_out > km.n_in
+    np.testing.assert_array_equal(km.out_coords().cpu().numpy(), ref.out_coords)
+    np.testing.assert_array_equal(km.in_coords().cpu().numpy(), c)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    np.testing.assert_array_equal(km.export_mask().cpu().numpy().view(np.uint32), oc.bitmask(ref.M))
+    assert km.n_pairs() == int((ref.M >= 0).sum()) == 27 * ref.n_in      # every input is read by 27 outputs
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, 27, "f16", seed)
+    for n_split, kernel in ((0, 0), (1, 1), (2, 2)):
+        cfg = sp.Config()
+        cfg.n_split, cfg.kernel = n_split, kernel
+        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"]
+        assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"]
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    pw = km.pointwise(on_outputs=True)                                   # 1x1x1 layer over the dilated rows
+    np.testing.assert_array_equal(pw.out_coords().cpu().numpy(), ref.out_coords)
+    with pytest.raises(sp.SpconvError) as e:
+        km.transpose()
+    assert e.value.status == -1
+
+
+def test_dilated_errors_and_k1(sp):
+    import torch
+    c = gen.uniform_cloud(200, 9, 53)
+    ref = oc.build_kmap(c, 1, 1, dilate=True)                            # K = 1: the inputs, sorted
+    km = sp.build_kmap(coords_dev(c), 1, 1, dilate=True)
+    np.testing.assert_array_equal(km.out_coords().cpu().numpy(), ref.out_coords)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    edge = c.copy()
+    edge[3] = (0, -32768, 5, 5)                                          # its neighbour at x - 1 cannot be packed
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(edge), 3, 1, dilate=True)
+    assert e.value.status == -2
+    dup = c.copy()
+    dup[7] = dup[9]
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(dup), 3, 1, dilate=True)
+    assert e.value.status == -3
+    lib = sp.load_library()
+    import ctypes
+    out = ctypes.c_void_p()
+    assert lib.spconv_build_kmap_dilated(None, 0, 5, None, ctypes.byref(out)) == -1
+    assert lib.spconv_build_kmap_dilated(None, 0, 2, None, ctypes.byref(out)) == -1
+    empty = sp.build_kmap(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 3, 1, dilate=True)
+    assert empty.n_out == 0

@@ -138,27 +138,13 @@ __global__ void k_ctl_init(Ctl* ctl) {
   ctl->key_and[threadIdx.x * 16] = ~0ull;
 }
 
-// Insert key(p_j) -> j for every input row; flags range and duplicate errors.  The kernel is a
-// chain of two memory round trips per thread on a grid that leaves most of the chip idle, so it also
-// presets the map and masks (map4 may be null): those stores ride along for free, and only the
-// probe, which runs next, needs them.
+// Insert key(p_j) -> j for every input row; flags range and duplicate errors.
 __global__ void __launch_bounds__(256) k_insert_rows(const int4* __restrict__ coords, int n,
                                                      unsigned long long* tab, int log_cap, Ctl* ctl,
-                                                     int4* __restrict__ keep, int4* __restrict__ map4,
-                                                     long long map_vec4, unsigned* __restrict__ mask,
-                                                     long long mask_n) {
+                                                     int4* __restrict__ keep) {
   const int j = blockIdx.x * blockDim.x + threadIdx.x;
-  // The row is requested before the preset stores go out: behind 100 bytes of stores per thread
-  // the load took 10 us to come back (23 600 clk mean L1 -> L2 read latency in this kernel, by
-  // the counters), and the insert, which needs it, is the kernel's critical path.
-  int4 c = make_int4(0, 0, 0, 0);
-  if (j < n) c = coords[j];
-  if (map4) {
-    const long long stride = (long long)gridDim.x * blockDim.x;
-    for (long long i = j; i < map_vec4; i += stride) map4[i] = make_int4(-1, -1, -1, -1);
-    for (long long i = j; i < mask_n; i += stride) mask[i] = 0u;
-  }
   if (j >= n) return;
+  const int4 c = coords[j];
   keep[j] = c;  // the kmap's own copy of the caller's rows
   if (!coord_ok(c.x, c.y, c.z, c.w)) {
     atomicOr(&ctl->flags, FLAG_RANGE);
@@ -417,16 +403,12 @@ __global__ void __launch_bounds__(256) k_fill_u32(unsigned* __restrict__ dst, lo
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) dst[i] = v;
 }
 
-// One launch that prepares a submanifold build: empties the hash table, presets the whole map
-// to "absent" and the masks to zero, and clears the control block.
-__global__ void __launch_bounds__(256)
-    k_build_init(ulonglong2* __restrict__ tab, long long slots, int4* __restrict__ map4, long long map_vec4,
-                 unsigned* __restrict__ mask, long long mask_n, Ctl* ctl) {
+// One launch that prepares a submanifold build: fills the table with ones (every key empty,
+// every cell -1) and clears the control block.
+__global__ void __launch_bounds__(256) k_build_init(ulonglong2* __restrict__ tab, long long words, Ctl* ctl) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   const long long t = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  for (long long i = t; i < slots; i += stride) tab[i] = make_ulonglong2(kEmpty, kEmpty);
-  for (long long i = t; i < map_vec4; i += stride) map4[i] = make_int4(-1, -1, -1, -1);
-  for (long long i = t; i < mask_n; i += stride) mask[i] = 0u;
+  for (long long i = t; i < words; i += stride) tab[i] = make_ulonglong2(kEmpty, kEmpty);
   if (blockIdx.x == 0) {
     if (threadIdx.x == 0) {
       ctl->flags = 0;
@@ -440,59 +422,93 @@ __global__ void __launch_bounds__(256)
   }
 }
 
-// Submanifold probe that uses the symmetry M[n][k] = j  <=>  M[j][V-1-k] = n: only the offsets
-// below the centre are looked up (13 of 27); a hit writes both entries and both mask bits.  The
-// map was preset to -1 and the masks to 0, so misses write nothing.  Lanes: 14 per row
-// (k = 0..13, the last one being the centre), 4 rows per wave.
-__global__ void __launch_bounds__(256)
-    k_probe_sym3(const int4* __restrict__ rows, int n_rows, const unsigned long long* __restrict__ tab, int log_cap,
-                 int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl, HostResult* host) {
-  __shared__ unsigned wave_pairs[4];
-  constexpr int V = 27, HALF = 13, LPR = 14, RPW = 4;
-  const int lane = threadIdx.x & 63;
-  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
-  const int sub = lane / LPR, k = lane - sub * LPR;
-  const long long row = wave * RPW + sub;
-  const bool active = (sub < RPW) && (row < n_rows);
-  int found = -1;
-  if (active) {
-    if (k == HALF) {
-      found = (int)row;
-      map[row * V + HALF] = found;
-    } else {
-      const int4 c = rows[row];
-      const int tx = c.y + k / 9 - 1, ty = c.z + (k / 3) % 3 - 1, tz = c.w + k % 3 - 1;
-      if (coord_ok(c.x, tx, ty, tz)) found = table_find(tab, log_cap, pack_key(c.x, tx, ty, tz), nullptr);
-      if (found >= 0) {
-        map[row * V + k] = found;
-        map[(long long)found * V + (V - 1 - k)] = (int)row;
-        atomicOr(&mask[found], 1u << (V - 1 - k));
-      }
-    }
+// ---- submanifold 3x3x3 build over a table of z-runs ----
+// One table entry holds four cells that are neighbours along z: the key is (b, x, y, z >> 2) and
+// rows[z & 3] the input row there.  A voxel's three neighbours in a column (x + dx, y + dy,
+// z - 1 .. z + 1) lie in one entry, or in two when the range crosses a multiple of four, so the
+// whole 27-neighbourhood takes 13.5 entry reads on average (as many as the 13 single-voxel lookups
+// that the symmetry M[n][k] = j <=> M[j][26 - k] = n leaves), and every read returns up to three
+// neighbours.  Each row then writes its own 27 map entries and its own mask: no entry of another
+// row is touched, so the map needs no preset and the masks no atomics.
+struct RunSlot {
+  unsigned long long key;
+  int rows[4];
+  unsigned long long pad;
+};
+static_assert(sizeof(RunSlot) == 32, "two entries per 64-byte line");
+
+// (32-bit mixing: a 64-bit multiply costs several times as many instructions, and the probe hashes
+// twice per lane)
+__device__ __forceinline__ unsigned hash_slot(unsigned long long key, int log_cap) {
+  unsigned h = (unsigned)key * 0x9E3779B1u ^ (unsigned)(key >> 32) * 0x85EBCA77u;
+  h ^= h >> 15;
+  return (h * 0xC2B2AE3Du) >> (32 - log_cap);
+}
+
+// The table arrives filled with ones: every key empty, every cell -1.  Duplicate rows store into
+// one cell; the probe notices, because one of them no longer finds itself there.
+__global__ void __launch_bounds__(256) k_insert_runs(const int4* __restrict__ coords, int n, RunSlot* tab, int log_cap,
+                                                     Ctl* ctl, int4* __restrict__ keep) {
+  const int j = blockIdx.x * blockDim.x + threadIdx.x;
+  if (j >= n) return;
+  const int4 c = coords[j];
+  keep[j] = c;  // the kmap's own copy of the caller's rows
+  if (!coord_ok(c.x, c.y, c.z, c.w)) {
+    atomicOr(&ctl->flags, FLAG_RANGE);
+    return;
   }
-  const unsigned long long bal = __ballot(found >= 0);
-  if (active && k == 0) atomicOr(&mask[row], (unsigned)((bal >> (sub * LPR)) & ((1ull << LPR) - 1ull)));
-  // pairs: every hit below the centre stands for two, the centre for one
-  const unsigned long long centre = (1ull << HALF) | (1ull << (HALF + LPR)) | (1ull << (HALF + 2 * LPR)) |
-                                    (1ull << (HALF + 3 * LPR));
-  if (lane == 0) wave_pairs[threadIdx.x >> 6] = 2u * (unsigned)__popcll(bal & ~centre) + (unsigned)__popcll(bal & centre);
-  __syncthreads();
-  // The workgroup that arrives last sums the pair counters and writes the result into pinned
-  // host memory.  A pair slot is one 64-bit counter: pairs in its low 40 bits, arrivals above, so
-  // that one atomic both adds the workgroup's pairs and tells it whether it was the slot's last
-  // (a second level counts the finished slots: no address sees more than gridDim/64 or 64
-  // atomics).  Only the first wave waits for that atomic; the others leave after the barrier and
-  // free their slots on the CU (two returning atomics in a row, awaited by the whole workgroup,
-  // kept every wave of this kernel resident for 7 us).  Every value the last workgroup reads was
-  // produced by an atomic whose return its producer waited for before counting itself in, and is
-  // read with an atomic, so no cache write-back is needed.
-  if (threadIdx.x >= 64) return;
+  const unsigned long long key = pack_key(c.x, c.y, c.z, c.w >> 2);
+  const unsigned slot_mask = (1u << log_cap) - 1u;
+  unsigned s = hash_slot(key, log_cap);
+  for (unsigned it = 0; it <= slot_mask; ++it) {
+    const unsigned long long old = atomicCAS(&tab[s].key, kEmpty, key);
+    if (old == kEmpty || old == key) {
+      tab[s].rows[c.w & 3] = j;
+      return;
+    }
+    s = (s + 1) & slot_mask;
+  }
+  atomicOr(&ctl->flags, FLAG_FULL);
+}
+
+// Finishes a lookup whose first entry (slot s) is already loaded: a = key and cells 0, 1.  FULL
+// also fetches cells 2, 3.
+template <bool FULL>
+__device__ __forceinline__ void run_resolve(const RunSlot* tab, int log_cap, unsigned long long key, unsigned s,
+                                            uint4 a, int cells[4]) {
+  const unsigned slot_mask = (1u << log_cap) - 1u;
+  for (unsigned it = 0; it <= slot_mask; ++it) {
+    const unsigned long long k = (unsigned long long)a.x | ((unsigned long long)a.y << 32);
+    if (k == key) {
+      cells[0] = (int)a.z;
+      cells[1] = (int)a.w;
+      if (FULL) {
+        const uint2 b = *reinterpret_cast<const uint2*>(&tab[s].rows[2]);
+        cells[2] = (int)b.x;
+        cells[3] = (int)b.y;
+      }
+      return;
+    }
+    if (k == kEmpty) return;
+    s = (s + 1) & slot_mask;
+    a = *reinterpret_cast<const uint4*>(tab + s);
+  }
+}
+
+// The workgroup that arrives last sums the pair counters and writes the result into pinned host
+// memory.  A pair slot is one 64-bit counter: pairs in its low 40 bits, arrivals above, so that one
+// atomic both adds the workgroup's pairs and tells it whether it was the slot's last (a second
+// level counts the finished slots: no address sees more than gridDim/64 or 64 atomics).  Called by
+// the first wave only, after the others have left: two returning atomics in a row, awaited by the
+// whole workgroup, kept every wave of the probe resident for 7 us.  Every value the last workgroup
+// reads was produced by an atomic whose return its producer waited for before counting itself in,
+// and is read with an atomic, so no cache write-back is needed.
+__device__ __forceinline__ void publish_pairs(unsigned wg_pairs, Ctl* ctl, HostResult* host) {
   constexpr unsigned long long kArrive = 1ull << 40;
   int last = 0;
   if (threadIdx.x == 0) {
-    const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
     const unsigned slot = blockIdx.x % kPairSlots;
-    const unsigned long long before = atomicAdd(&ctl->pairs[slot * 16], (unsigned long long)n + kArrive);
+    const unsigned long long before = atomicAdd(&ctl->pairs[slot * 16], (unsigned long long)wg_pairs + kArrive);
     const unsigned slot_wgs = (gridDim.x - slot + kPairSlots - 1) / kPairSlots;
     const unsigned used_slots = gridDim.x < (unsigned)kPairSlots ? gridDim.x : (unsigned)kPairSlots;
     if ((unsigned)(before >> 40) + 1 == slot_wgs) last = atomicAdd(&ctl->tick_top, 1u) + 1 == used_slots;
@@ -504,6 +520,84 @@ __global__ void __launch_bounds__(256)
     if (threadIdx.x == 0)
       host->word = kHostReady | ((unsigned long long)(ctl->flags & 0xFFu) << 48) | (v & 0xFFFFFFFFFFFFull);
   }
+}
+
+__device__ __forceinline__ unsigned spread3(unsigned g) {  // bit c of 9 -> bit 3c
+  g = (g | (g << 16)) & 0x030000FFu;
+  g = (g | (g << 8)) & 0x0300F00Fu;
+  g = (g | (g << 4)) & 0x030C30C3u;
+  return (g | (g << 2)) & 0x09249249u;
+}
+
+// Nine lanes per row, one per column (dx, dy); seven rows per wave.  Rows of the padding
+// (n_rows <= row < rows_pad) get an empty neighbourhood.
+__global__ void __launch_bounds__(256)
+    k_probe_runs3(const int4* __restrict__ rows, int n_rows, long long rows_pad, const RunSlot* __restrict__ tab,
+                  int log_cap, int* __restrict__ map, unsigned* __restrict__ mask, Ctl* ctl, HostResult* host) {
+  __shared__ unsigned wave_pairs[4];
+  constexpr int V = 27, LPR = 9, RPW = 7;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int sub = lane / LPR, col = lane - sub * LPR;
+  const long long row = wave * RPW + sub;
+  const bool active = (sub < RPW) && (row < rows_pad);
+  int nb[3] = {-1, -1, -1};
+  if (active && row < n_rows) {
+    const int4 c = rows[row];
+    const int tx = c.y + col / 3 - 1, ty = c.z + col % 3 - 1;
+    // The cells z - 1, z, z + 1 are three in a row of the window [run q_lo | run q_lo + 1], starting
+    // at (z - 1) & 3: of the upper run only cells 0 and 1 can be needed, which come with its key.
+    // (z itself is in range, so the runs' indices fit the key's field; cells beside the range are
+    // dropped below.  A row beside the range fails the build; its neighbourhood stays empty.)
+    const int q_lo = (c.w - 1) >> 2, i0 = (c.w - 1) & 3;
+    if (coord_ok(c.x, c.y, c.z, c.w) && coord_ok(c.x, tx, ty, c.w)) {
+      const unsigned long long key_lo = pack_key(c.x, tx, ty, q_lo), key_hi = key_lo + 1;
+      const unsigned s_lo = hash_slot(key_lo, log_cap), s_hi = hash_slot(key_hi, log_cap);
+      const uint4 a_lo = *reinterpret_cast<const uint4*>(tab + s_lo);
+      const uint2 b_lo = *reinterpret_cast<const uint2*>(&tab[s_lo].rows[2]);
+      // (the kernel is bound by the number of read requests a CU keeps in flight: the upper run is
+      // only read where the window reaches into it)
+      uint4 a_hi = make_uint4(~0u, ~0u, 0u, 0u);
+      if (i0 >= 2) a_hi = *reinterpret_cast<const uint4*>(tab + s_hi);  // all in flight
+      int w[8] = {-1, -1, -1, -1, -1, -1, -1, -1};
+      {
+        const unsigned long long k = (unsigned long long)a_lo.x | ((unsigned long long)a_lo.y << 32);
+        if (k == key_lo) {
+          w[0] = (int)a_lo.z;
+          w[1] = (int)a_lo.w;
+          w[2] = (int)b_lo.x;
+          w[3] = (int)b_lo.y;
+        } else if (k != kEmpty) {
+          run_resolve<true>(tab, log_cap, key_lo, s_lo, a_lo, w);
+        }
+      }
+      if (i0 >= 2) run_resolve<false>(tab, log_cap, key_hi, s_hi, a_hi, w + 4);
+      const bool b1 = i0 & 1, b2 = i0 & 2;
+#pragma unroll
+      for (int d = 0; d < 3; ++d) {
+        const int v = b2 ? (b1 ? w[3 + d] : w[2 + d]) : (b1 ? w[1 + d] : w[d]);
+        nb[d] = coord_ok(c.x, tx, ty, c.w + d - 1) ? v : -1;
+      }
+      // a row that does not find itself at its own place shares it with another row
+      if (col == 4 && nb[1] != (int)row) atomicOr(&ctl->flags, FLAG_DUP);
+    }
+  }
+  if (active) {
+    int* dst = map + row * V + 3 * col;
+    dst[0] = nb[0];
+    dst[1] = nb[1];
+    dst[2] = nb[2];
+  }
+  const unsigned long long b0 = __ballot(nb[0] >= 0), b1 = __ballot(nb[1] >= 0), b2 = __ballot(nb[2] >= 0);
+  if (active && col == 0) {
+    const int sh = sub * LPR;
+    mask[row] = spread3((unsigned)(b0 >> sh) & 0x1FFu) | (spread3((unsigned)(b1 >> sh) & 0x1FFu) << 1) |
+                (spread3((unsigned)(b2 >> sh) & 0x1FFu) << 2);
+  }
+  if (lane == 0) wave_pairs[threadIdx.x >> 6] = (unsigned)(__popcll(b0) + __popcll(b1) + __popcll(b2));
+  __syncthreads();
+  if (threadIdx.x >= 64) return;
+  publish_pairs(wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3], ctl, host);
 }
 
 // T[j][k] = n for every present pair M[n][k] = j.
@@ -728,35 +822,35 @@ int flags_status(const Ctl& h) {
 int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream);
 namespace {
 
-// Submanifold 3x3x3 build: init, insert, symmetric probe (whose last workgroup publishes the result
-// to pinned host memory).
+// Submanifold 3x3x3 build: init, insert, probe (whose last workgroup publishes the result to
+// pinned host memory).
 int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async, hipStream_t st) {
   const int V = 27;
   DevBuf ctl_buf, tab, own_rows;
   SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
   Ctl* ctl = ctl_buf.as<Ctl>();
-  const int lc = log2_capacity(N);
-  SPC_TRY(tab.alloc((size_t)16 << lc));
+  const int lc = log2_capacity(N);  // entries >= 2 N >= twice the z-runs
+  SPC_TRY(tab.alloc(sizeof(RunSlot) << lc));
   SPC_TRY(own_rows.alloc((size_t)N * 16));
   SideMap& side = km->out_side;
   side.rows = N;
   side.rows_pad = round_up(N, kRowPad);
   SPC_TRY(side.map.alloc((size_t)side.rows_pad * V * sizeof(int)));
   SPC_TRY(side.mask.alloc((size_t)side.rows_pad * sizeof(unsigned)));
-  const long long slots = 1ll << lc, map_vec4 = side.rows_pad * V / 4;
-  const unsigned init_blocks = (unsigned)std::min<int64_t>(ceil_div(slots, 256), 4096);
-  hipLaunchKernelGGL(k_build_init, dim3(init_blocks), dim3(256), 0, st, tab.as<ulonglong2>(), slots,
-                     (int4*)nullptr, 0ll, (unsigned*)nullptr, 0ll, ctl);
+  const long long words = 2ll << lc;  // 16-byte words of the table, all set to ones
+  const unsigned init_blocks = (unsigned)std::min<int64_t>(ceil_div(words, 256), 4096);
+  hipLaunchKernelGGL(k_build_init, dim3(init_blocks), dim3(256), 0, st, tab.as<ulonglong2>(), words,
+                     ctl);
   SPC_LAUNCH_CHECK();
-  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                     tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>(), side.map.as<int4>(), map_vec4,
-                     side.mask.as<unsigned>(), (long long)side.rows_pad);
+  hipLaunchKernelGGL(k_insert_runs, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N, tab.as<RunSlot>(), lc,
+                     ctl, own_rows.as<int4>());
   SPC_LAUNCH_CHECK();
   HostCtl* hc = host_ctl_acquire();
   if (!hc) return SPCONV_ENOMEM;
   hc->res.word = 0;  // (pinned memory: visible to the kernel launched below)
-  hipLaunchKernelGGL(k_probe_sym3, dim3(blocks_for(ceil_div(N, 4), 4)), dim3(256), 0, st, rows, (int)N,
-                     tab.as<unsigned long long>(), lc, side.map.as<int>(), side.mask.as<unsigned>(), ctl, hc->dev);
+  hipLaunchKernelGGL(k_probe_runs3, dim3(blocks_for(ceil_div(side.rows_pad, 7), 4)), dim3(256), 0, st, rows, (int)N,
+                     (long long)side.rows_pad, tab.as<RunSlot>(), lc, side.map.as<int>(), side.mask.as<unsigned>(),
+                     ctl, hc->dev);
   const bool ok = hipGetLastError() == hipSuccess;
   if (!ok) {
     (void)hipGetLastError();
@@ -873,8 +967,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     SPC_TRY(tab_fine.alloc((size_t)16 << lc_fine));
     SPC_TRY(fill_u32(tab_fine.p, (int64_t)4 << lc_fine, 0xFFFFFFFFu, st));
     hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
-                       tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>(), (int4*)nullptr, 0ll,
-                       (unsigned*)nullptr, 0ll);
+                       tab_fine.as<unsigned long long>(), lc_fine, ctl, own_rows.as<int4>());
     SPC_LAUNCH_CHECK();
   }
 

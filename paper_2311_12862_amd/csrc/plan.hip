@@ -100,17 +100,276 @@ __global__ void __launch_bounds__(256)
   val[r] = r;
 }
 
-// perm_out[r] = sorted row index (or -1 in the padding); reordered[r][c] = map[perm[r]][lo + c]
+// ---- bitmask argsort in few launches (maps of up to kSortMaxWgs * kSortWg rows) ----
+// Stable least-significant-digit radix sort of (key, row): one launch per digit, and one in front
+// that clears three counters.  A workgroup owns kSortWg consecutive items, each of its four waves
+// a quarter.  It counts its items per digit value, publishes the counts as a row of the matrix
+// hist[workgroup][value], and waits until every workgroup of the launch has done so (all of them
+// are resident: at most kSortMaxWgs workgroups on 256 CUs; the wait is bounded all the same, and a
+// wait that runs out fails the sort).  It then finds its own offsets by summing the rows in front
+// of it (a coalesced read of at most 256 KB, in place of a scan launch) and ranks its items with
+// ballots as the general sort does.  The first digit's keys come straight from the masks, the last
+// digit writes only the row order.
+constexpr int kSortWg = 2048, kSortWaves = 4, kSortThreads = 64 * kSortWaves;
+constexpr int kSortWave = kSortWg / kSortWaves, kSortSteps = kSortWave / 64;
+constexpr int kSortMaxWgs = 64;
+constexpr int kSortMaxBits = 10, kSortMaxBins = 1 << kSortMaxBits;
+constexpr unsigned kSortSpinLimit = 1u << 20;  // polls of the arrival counter (about a second)
+// head of the counter buffer: arrive[16 * pass], error at [48]
+constexpr int kSortSyncWords = 64;
+constexpr int kSortRound = 32;  // matrix rows a thread reads at a time
+
+struct MaskKeys {
+  const unsigned* mask;
+  const int4* coords;  // null: no slabs
+  const int* partial;  // kBoundsBlocks partial bounds
+  int lo, width;
+};
+
+// the first wave folds the partial bounds and picks the longest axis: slab[0..2] = axis, lowest
+// coordinate, extent
+__device__ __forceinline__ void fold_bounds(const int* __restrict__ partial, int n_partial, int* slab) {
+  if (threadIdx.x < 64) {
+    int mn[3], mx[3];
+    for (int a = 0; a < 3; ++a) {
+      int l = 0x7FFFFFFF, h = (int)0x80000000;
+      for (int b = threadIdx.x; b < n_partial; b += 64) {
+        l = min(l, partial[b * 6 + a]);
+        h = max(h, partial[b * 6 + 3 + a]);
+      }
+      for (int o = 32; o > 0; o >>= 1) {
+        l = min(l, __shfl_xor(l, o));
+        h = max(h, __shfl_xor(h, o));
+      }
+      mn[a] = l, mx[a] = h;
+    }
+    if (threadIdx.x == 0) {
+      int axis = 0;
+      for (int a = 1; a < 3; ++a)
+        if ((long long)mx[a] - mn[a] > (long long)mx[axis] - mn[axis]) axis = a;
+      slab[0] = axis;
+      slab[1] = mn[axis];
+      slab[2] = (int)min((long long)mx[axis] - mn[axis] + 1, (long long)0x7FFFFFFF);
+    }
+  }
+}
+
+// bits [lo, lo + width) of the row's mask, below the row's slab if there are slabs
+__device__ __forceinline__ unsigned mask_key(const MaskKeys& mk, const int* slab, int r) {
+  unsigned k = (mk.mask[r] >> mk.lo) & ((1u << mk.width) - 1u);
+  if (mk.coords) {
+    const int4 c = mk.coords[r];
+    const int v = slab[0] == 0 ? c.y : slab[0] == 1 ? c.z : c.w;
+    k |= (unsigned)(((long long)v - slab[1]) * kSlabs / slab[2]) << mk.width;  // slab 0 .. kSlabs-1
+  }
+  return k;
+}
+
+__global__ void __launch_bounds__(64) k_msort_clear(unsigned* __restrict__ sync) { sync[threadIdx.x] = 0; }
+
+template <bool FIRST, bool LAST>
+__global__ void __launch_bounds__(kSortThreads)
+    k_msort_pass(MaskKeys mk, const unsigned* __restrict__ kin, const int* __restrict__ vin,
+                 unsigned* __restrict__ kout, int* __restrict__ vout, int rows, int shift, int bits,
+                 unsigned* hist, unsigned* arrive, unsigned* error) {
+  __shared__ unsigned off[kSortWaves][kSortMaxBins];  // wave counts, then the waves' running places within the workgroup
+  __shared__ unsigned first[kSortMaxBins];   // the workgroup's first place per digit value
+  __shared__ unsigned part[2][kSortThreads][4];       // partial sums of the matrix rows: [before | total][thread][digit of quad]
+  __shared__ unsigned wave_sum[kSortWaves];
+  __shared__ int slab[3];
+  const int wib = threadIdx.x >> 6, lane = threadIdx.x & 63;
+  const int bins = 1 << bits;
+  const int begin = blockIdx.x * kSortWg + wib * kSortWave;
+  for (int d = threadIdx.x; d < kSortWaves * kSortMaxBins; d += kSortThreads) (&off[0][0])[d] = 0;
+  if (FIRST && mk.coords) fold_bounds(mk.partial, kBoundsBlocks, slab);
+  if (FIRST) __syncthreads();
+  // all of the wave's items are fetched up front (the ranking steps depend on each other)
+  unsigned kreg[kSortSteps];
+  int vreg[kSortSteps];
+#pragma unroll
+  for (int s = 0; s < kSortSteps; ++s) {
+    const int i = begin + s * 64 + lane;
+    kreg[s] = 0;
+    vreg[s] = i;
+    if (i < rows) {
+      kreg[s] = FIRST ? mask_key(mk, slab, i) : kin[i];
+      if (!FIRST) vreg[s] = vin[i];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < kSortSteps; ++s)
+    if (begin + s * 64 + lane < rows) atomicAdd(&off[wib][(kreg[s] >> shift) & (unsigned)(bins - 1)], 1u);
+  __syncthreads();
+  // publish this workgroup's counts (whole quads: the readers take four at a time); the wave
+  // counts become the waves' first places within the workgroup's share of each digit value
+  for (int d = threadIdx.x; d < (bins > 4 ? bins : 4); d += kSortThreads) {
+    unsigned run = 0;
+    for (int w = 0; w < kSortWaves; ++w) {
+      const unsigned c = off[w][d];
+      off[w][d] = run;
+      run += c;
+    }
+    hist[(size_t)blockIdx.x * kSortMaxBins + d] = run;
+  }
+  // The way a grid-wide barrier is built: workgroup barrier, then one thread releases at device
+  // scope (which covers what the workgroup's threads wrote before the barrier) and counts the
+  // workgroup in; after the wait it acquires at device scope in front of a second workgroup barrier.
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    __hip_atomic_fetch_add(arrive, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  // While the other workgroups arrive: every item's place within the workgroup's share of its
+  // digit value (ballots find the lanes with equal digits; the rank is the number of such lanes
+  // below; the wave's running places live in LDS).
+  const unsigned long long lt = (1ull << lane) - 1ull;
+  unsigned lpos[kSortSteps];
+#pragma unroll
+  for (int s = 0; s < kSortSteps; ++s) {
+    const bool valid = begin + s * 64 + lane < rows;
+    const unsigned d = (kreg[s] >> shift) & (unsigned)(bins - 1);
+    unsigned long long peers = __ballot(valid);
+    for (int b = 0; b < bits; ++b) {
+      const bool bit = (d >> b) & 1u;
+      const unsigned long long bal = __ballot(bit);
+      peers &= bit ? bal : ~bal;
+    }
+    const unsigned rank = (unsigned)__popcll(peers & lt);
+    unsigned pos = 0;
+    if (valid) pos = off[wib][d];
+    __builtin_amdgcn_wave_barrier();  // every lane has read its place before a leader advances it
+    if (valid && rank == 0) off[wib][d] = pos + (unsigned)__popcll(peers);
+    __builtin_amdgcn_wave_barrier();
+    lpos[s] = pos + rank;
+  }
+  if (threadIdx.x == 0) {
+    unsigned polls = 0;
+    while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
+      if (++polls > kSortSpinLimit) {
+        atomicOr(error, 1u);
+        break;
+      }
+      __builtin_amdgcn_s_sleep(2);
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");  // the other workgroups' counts are read below
+  }
+  __syncthreads();
+  // First places of this workgroup.  The matrix rows are summed by all threads: thread (g, q)
+  // takes the four digit values of quad q in the rows w = g, g + ng, ...; before = items in the
+  // workgroups in front, total = in all workgroups.
+  const int nq = bins >= 4 ? bins / 4 : 1, ng = kSortThreads / nq;
+  {
+    const int q = threadIdx.x % nq, g = threadIdx.x / nq;
+    unsigned before[4] = {0, 0, 0, 0}, total[4] = {0, 0, 0, 0};
+    const unsigned* col = hist + 4 * q;
+    // (rounds of kSortRound loads, all in flight together: the rows come from memory, and a load
+    // that waits for the one before it costs a round trip each)
+    for (int w0 = g; w0 < (int)gridDim.x; w0 += kSortRound * ng) {
+      uint4 h[kSortRound];
+#pragma unroll
+      for (int i = 0; i < kSortRound; ++i) {
+        const int w = w0 + i * ng;
+        h[i] = make_uint4(0u, 0u, 0u, 0u);
+        if (w < (int)gridDim.x) h[i] = *reinterpret_cast<const uint4*>(col + (size_t)w * kSortMaxBins);
+      }
+#pragma unroll
+      for (int i = 0; i < kSortRound; ++i) {
+        const unsigned hv[4] = {h[i].x, h[i].y, h[i].z, h[i].w};
+        const bool front = w0 + i * ng < (int)blockIdx.x;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          total[j] += hv[j];
+          before[j] += front ? hv[j] : 0u;
+        }
+      }
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      part[0][threadIdx.x][j] = before[j];
+      part[1][threadIdx.x][j] = total[j];
+    }
+  }
+  __syncthreads();
+  unsigned before[4] = {0, 0, 0, 0}, total[4] = {0, 0, 0, 0};
+  const int d0 = 4 * threadIdx.x;  // thread t < nq owns digit values 4t .. 4t+3
+  if (threadIdx.x < nq) {
+    for (int g = 0; g < ng; ++g)
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        before[j] += part[0][g * nq + threadIdx.x][j];
+        total[j] += part[1][g * nq + threadIdx.x][j];
+      }
+  }
+  const unsigned mine = total[0] + total[1] + total[2] + total[3];
+  unsigned incl = mine;  // inclusive scan of the threads' sums
+#pragma unroll
+  for (int o = 1; o < 64; o <<= 1) {
+    const unsigned up = __shfl_up(incl, o);
+    if (lane >= o) incl += up;
+  }
+  if (lane == 63) wave_sum[wib] = incl;
+  __syncthreads();
+  unsigned base = incl - mine;
+  for (int w = 0; w < wib; ++w) base += wave_sum[w];
+  if (threadIdx.x < nq) {
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      first[d0 + j] = base + before[j];  // first place of digit value d0 + j for this workgroup
+      base += total[j];
+    }
+  }
+  __syncthreads();
+#pragma unroll
+  for (int s = 0; s < kSortSteps; ++s) {
+    const bool valid = begin + s * 64 + lane < rows;
+    const unsigned key = kreg[s];
+    const unsigned pos = first[(key >> shift) & (unsigned)(bins - 1)] + lpos[s];
+    if (valid && pos < (unsigned)rows) {  // (always below rows when the counters are consistent)
+      vout[pos] = vreg[s];
+      if (!LAST) kout[pos] = key;
+    }
+  }
+}
+
+// Offline reordering (Section 3.2) of one part of the map, and the OR of each tile's keys.  A
+// workgroup takes 256 consecutive places of the order (a whole number of tiles): perm_out[r] =
+// row at place r (-1 in the padding), reordered[r][c] = map[perm[r]][lo + c], tilemask[t] = OR of
+// the keys of tile t's rows.  If the sort reported a failed wait (*error != 0) the rows stay in map
+// order: any order gives the same results, an order that is no permutation would not.
 __global__ void __launch_bounds__(256)
-    k_reorder(const int* __restrict__ map, int V, const int* __restrict__ sorted_rows, int rows, long long rows_pad,
-              int lo, int width, int* __restrict__ reordered, int* __restrict__ perm_out) {
-  const long long e = (long long)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= rows_pad * width) return;
-  const long long r = e / width;
-  const int c = (int)(e - r * width);
-  const int src = (r < rows) ? sorted_rows[r] : -1;
-  reordered[e] = (src >= 0) ? map[(long long)src * V + lo + c] : -1;
-  if (c == 0) perm_out[r] = src;
+    k_reorder_tiles(const int* __restrict__ map, const unsigned* __restrict__ mask, int V,
+                    const int* __restrict__ sorted_rows, const unsigned* __restrict__ error, int rows, int lo,
+                    int width, int tile_m, long long n_tiles, int* __restrict__ reordered,
+                    int* __restrict__ perm_out, unsigned* __restrict__ tilemask) {
+  __shared__ int src_of[256];
+  __shared__ unsigned wave_or[4];
+  const long long r = (long long)blockIdx.x * 256 + threadIdx.x;
+  const bool failed = error && *error != 0;
+  const int src = r < rows ? (failed ? (int)r : sorted_rows[r]) : -1;
+  src_of[threadIdx.x] = src;
+  if (blockIdx.y == 0) perm_out[r] = src;
+  unsigned m = src >= 0 ? (mask[src] >> lo) & (width >= 32 ? 0xFFFFFFFFu : ((1u << width) - 1u)) : 0u;
+  const int span = tile_m < 64 ? tile_m : 64;
+  for (int o = span >> 1; o > 0; o >>= 1) m |= __shfl_xor(m, o);
+  if ((threadIdx.x & 63) == 0) wave_or[threadIdx.x >> 6] = m;
+  __syncthreads();
+  if (blockIdx.y == 0 && threadIdx.x % tile_m == 0) {
+    const long long t = r / tile_m;
+    unsigned all = m;
+    for (int w = 1; w < tile_m / 64; ++w) all |= wave_or[(threadIdx.x >> 6) + w];
+    if (t < n_tiles) tilemask[t] = all;
+  }
+  // one thread per entry of the block's 256 x width entries (consecutive threads, consecutive
+  // addresses); the workgroups of one blockIdx.x share them.  e / width for e < 6912 by a multiply:
+  // (e + 0.5) / width stays 0.5 / 27 away from every integer, far beyond the rounding of the product.
+  int* dst = reordered + (long long)blockIdx.x * 256 * width;
+  const float inv_width = 1.0f / (float)width;
+  for (int e = threadIdx.x + 256 * blockIdx.y; e < 256 * width; e += 256 * gridDim.y) {
+    const int rr = (int)(((float)e + 0.5f) * inv_width);
+    const int sr = src_of[rr];
+    dst[e] = sr >= 0 ? map[(long long)sr * V + lo + (e - rr * width)] : -1;
+  }
 }
 
 // tilemask[t] = OR over the tile's rows of their split keys.  One wave per tile.
@@ -439,29 +698,74 @@ int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_
       }
       DevBuf key_a, key_b, val_a, val_b, hist;
       const size_t n = (size_t)p->rows;
+      const int n_wg = (int)ceil_div(p->rows, kSortWg);
+      const bool few_launches = n_wg <= kSortMaxWgs;
       SPC_TRY(key_a.alloc(n * 4));
       SPC_TRY(key_b.alloc(n * 4));
       SPC_TRY(val_a.alloc(n * 4));
       SPC_TRY(val_b.alloc(n * 4));
-      SPC_TRY(hist.alloc(sort_hist_elems(p->rows) * sizeof(uint32_t)));
+      const size_t hist_elems = (size_t)n_wg * kSortMaxBins;
+      SPC_TRY(hist.alloc((few_launches ? kSortSyncWords + 3 * hist_elems : sort_hist_elems(p->rows)) * sizeof(uint32_t)));
       for (int i = 0; i < p->parts; ++i) {
-        hipLaunchKernelGGL(k_split_keys, dim3(blocks_for(p->rows, 256)), dim3(256), 0, st,
-                           side.mask.as<unsigned>(), (int)p->rows, p->lo[i], p->width[i],
-                           slabs ? crd.as<int4>() : (const int4*)nullptr, bounds.as<int>(), kBoundsBlocks,
-                           key_a.as<unsigned>(), val_a.as<int>());
-        SPC_LAUNCH_CHECK();
-        int in_b = 0;
-        SPC_TRY(radix_sort_u32(key_a.as<uint32_t>(), key_b.as<uint32_t>(), val_a.as<int32_t>(), val_b.as<int32_t>(),
-                               p->rows, p->width[i] + (slabs ? kSlabBits : 0), hist.as<uint32_t>(), st, &in_b));
-        const int* sorted_rows = in_b ? val_b.as<int>() : val_a.as<int>();
+        const int key_bits = p->width[i] + (slabs ? kSlabBits : 0);
+        const int* sorted_rows = nullptr;
+        if (few_launches) {
+          const MaskKeys mk{side.mask.as<unsigned>(), slabs ? crd.as<int4>() : (const int4*)nullptr, bounds.as<int>(),
+                            p->lo[i], p->width[i]};
+          const int passes = (key_bits + kSortMaxBits - 1) / kSortMaxBits;  // <= 3: key_bits <= 30
+          const int bits = (key_bits + passes - 1) / passes;
+          unsigned* sync = hist.as<unsigned>();
+          unsigned* h[3] = {sync + kSortSyncWords, sync + kSortSyncWords + hist_elems,
+                            sync + kSortSyncWords + 2 * hist_elems};
+          unsigned *ka = key_a.as<unsigned>(), *kb = key_b.as<unsigned>();
+          int *va = val_a.as<int>(), *vb = val_b.as<int>();
+          const dim3 grid((unsigned)n_wg), block(kSortThreads);
+          const int rows_i = (int)p->rows;
+          const int b_last = key_bits - (passes - 1) * bits;  // width of the last digit
+          unsigned* err = sync + 48;
+          hipLaunchKernelGGL(k_msort_clear, dim3(1), dim3(kSortSyncWords), 0, st, sync);
+          SPC_LAUNCH_CHECK();
+          if (passes == 1) {
+            hipLaunchKernelGGL((k_msort_pass<true, true>), grid, block, 0, st, mk, (const unsigned*)nullptr,
+                               (const int*)nullptr, (unsigned*)nullptr, vb, rows_i, 0, bits, h[0], sync, err);
+            sorted_rows = vb;
+          } else if (passes == 2) {
+            hipLaunchKernelGGL((k_msort_pass<true, false>), grid, block, 0, st, mk, (const unsigned*)nullptr,
+                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err);
+            SPC_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_msort_pass<false, true>), grid, block, 0, st, mk, (const unsigned*)kb,
+                               (const int*)vb, (unsigned*)nullptr, va, rows_i, bits, b_last, h[1], sync + 16, err);
+            sorted_rows = va;
+          } else {
+            hipLaunchKernelGGL((k_msort_pass<true, false>), grid, block, 0, st, mk, (const unsigned*)nullptr,
+                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err);
+            SPC_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_msort_pass<false, false>), grid, block, 0, st, mk, (const unsigned*)kb,
+                               (const int*)vb, ka, va, rows_i, bits, bits, h[1], sync + 16, err);
+            SPC_LAUNCH_CHECK();
+            hipLaunchKernelGGL((k_msort_pass<false, true>), grid, block, 0, st, mk, (const unsigned*)ka,
+                               (const int*)va, (unsigned*)nullptr, vb, rows_i, 2 * bits, b_last, h[2], sync + 32, err);
+            sorted_rows = vb;
+          }
+          SPC_LAUNCH_CHECK();
+        } else {
+          hipLaunchKernelGGL(k_split_keys, dim3(blocks_for(p->rows, 256)), dim3(256), 0, st,
+                             side.mask.as<unsigned>(), (int)p->rows, p->lo[i], p->width[i],
+                             slabs ? crd.as<int4>() : (const int4*)nullptr, bounds.as<int>(), kBoundsBlocks,
+                             key_a.as<unsigned>(), val_a.as<int>());
+          SPC_LAUNCH_CHECK();
+          int in_b = 0;
+          SPC_TRY(radix_sort_u32(key_a.as<uint32_t>(), key_b.as<uint32_t>(), val_a.as<int32_t>(), val_b.as<int32_t>(),
+                                 p->rows, key_bits, hist.as<uint32_t>(), st, &in_b));
+          sorted_rows = in_b ? val_b.as<int>() : val_a.as<int>();
+        }
         int* perm_i = p->perm.as<int>() + (size_t)i * p->rows_pad;
-        hipLaunchKernelGGL(k_reorder, dim3(blocks_for(p->rows_pad * p->width[i], 256)), dim3(256), 0, st,
-                           side.map.as<int>(), V, sorted_rows, (int)p->rows, (long long)p->rows_pad, p->lo[i],
-                           p->width[i], p->maps.as<int>() + p->map_off[i], perm_i);
-        SPC_LAUNCH_CHECK();
-        hipLaunchKernelGGL(k_tile_mask, dim3(tile_blocks), dim3(256), 0, st, side.mask.as<unsigned>(),
-                           (const int*)perm_i, (long long)p->rows, tile_m, p->lo[i], p->width[i],
-                           (long long)p->n_tiles, p->tilemask.as<unsigned>() + (size_t)i * tiles_alloc);
+        hipLaunchKernelGGL(k_reorder_tiles, dim3((unsigned)(p->rows_pad / 256), 8), dim3(256), 0, st, side.map.as<int>(),
+                           side.mask.as<unsigned>(), V, sorted_rows,
+                           few_launches ? (const unsigned*)(hist.as<unsigned>() + 48) : (const unsigned*)nullptr,
+                           (int)p->rows, p->lo[i], p->width[i], tile_m,
+                           (long long)p->n_tiles, p->maps.as<int>() + p->map_off[i], perm_i,
+                           p->tilemask.as<unsigned>() + (size_t)i * tiles_alloc);
         SPC_LAUNCH_CHECK();
       }
       // the sort temporaries return to the pool while the stream may still use them;

@@ -206,6 +206,46 @@ def test_sort_invariants(sp, cloud, n_split):
         assert (np.diff(perm)[same] > 0).all()
 
 
+def _check_order(perm, key, rows):
+    assert sorted(perm.tolist()) == list(range(rows))
+    k = key[perm].astype(np.int64)
+    assert (np.diff(k) >= 0).all()
+    assert (np.diff(perm)[np.diff(k) == 0] > 0).all()
+
+
+@pytest.mark.parametrize("n_split", [1, 2, 3])
+def test_sort_invariants_on_the_input_side_of_a_strided_map(sp, n_split):
+    """dgrad of a strided map walks the input-side map T[j][k] = n  <=>  M[n][k] = j; its rows are
+    sorted by their own bitmasks (which offsets reach input j), part by part."""
+    c = gen.lidar_scene(78, target_n=2900)
+    ref = oc.build_kmap(c, 3, 2)
+    km = sp.build_kmap(coords_dev(c), 3, 2)
+    T = np.full((ref.n_in, 27), -1, np.int64)
+    n, k = np.nonzero(ref.M >= 0)
+    T[ref.M[n, k], k] = n
+    mask = oc.bitmask(T).astype(np.uint64)
+    cfg = _cfg(sp, n_split)
+    for i, (lo, hi) in enumerate(oc.split_ranges(27, n_split)):
+        perm = km.export_perm(sp.OP_DGRAD, cfg, i).cpu().numpy()
+        _check_order(perm, (mask >> np.uint64(lo)) & np.uint64((1 << (hi - lo)) - 1), ref.n_in)
+
+
+@pytest.mark.parametrize("target_n", [2048, 2049, 131072, 140000])
+def test_sort_invariants_across_the_sizes_that_change_the_sort(sp, target_n):
+    """One workgroup of the few-launch sort, one row more, its largest map (64 workgroups), and a
+    map beyond it (the general radix sort).  The masks come from the library's own map, which
+    test_gpu_kmap holds against the oracle bit by bit; here only the order is at stake."""
+    c = gen.lidar_scene(79, target_n=target_n + 200)[:target_n]
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    M = km.export().cpu().numpy()
+    mask = oc.bitmask(M).astype(np.uint64)
+    for n_split in (1, 2):
+        cfg = _cfg(sp, n_split)
+        for i, (lo, hi) in enumerate(oc.split_ranges(27, n_split)):
+            perm = km.export_perm(sp.OP_FWD, cfg, i).cpu().numpy()
+            _check_order(perm, (mask >> np.uint64(lo)) & np.uint64((1 << (hi - lo)) - 1), len(c))
+
+
 @pytest.mark.parametrize("kernel", [1, 2])
 @pytest.mark.parametrize("n_split", [1, 2, 3])
 def test_spatial_slabs_in_front_of_the_sort_keys(sp, cloud, kernel, n_split):

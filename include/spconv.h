@@ -25,9 +25,16 @@
  *   - offset index k = ((dx+r)*K + (dy+r))*K + (dz+r), r = (K-1)/2, i.e. x
  *     slowest, z fastest; K is 1 or 3, or 2 with offsets {0, 1}^3 (r = 0: the
  *     paper defines odd K only; with stride 2 this is the non-overlapping
- *     2x2x2 layer); bit k of a neighbour bitmask is 1u<<k.  K = 5 (125
- *     offsets) is refused with SPCONV_EINVAL: bitmasks, sort keys and tile
- *     masks are 32 bits wide throughout;
+ *     2x2x2 layer); bit k of a neighbour bitmask is 1u<<k.  K = 5 (the 125
+ *     offsets of Section 2.1's neighbourhood) exists for submanifold maps
+ *     (stride 1, not transposed, synchronous build): the library holds such
+ *     a map as five planes of 25 offsets (dx = g - 2; offset k is offset
+ *     k % 25 of plane k / 25), runs forward and dgrad plane by plane and sums
+ *     the planes like the parts of a split, and sorts each plane by its own
+ *     25-bit mask.  spconv_kmap_export_perm then counts parts over the
+ *     planes (split = plane * n_split + part); the tuners, the paired
+ *     transposed kmap, fetch-on-demand and spconv_fwd_noalloc refuse a K = 5
+ *     kmap with SPCONV_EINVAL;
  *   - output q reads the input at s*q + delta with W[delta] (no kernel flip);
  *   - stride 1: P_out = P_in in input order; stride s > 1: P_out = unique
  *     floor(p / s), sorted ascending lexicographically in (b, x, y, z);
@@ -140,7 +147,7 @@ typedef struct spconv_config {
 /* Kernel-map construction ("mapping operations", Sections 3.1, 4.2, 6.2).
  *   coords      device, int32 [N][4] = (b, x, y, z), unique rows.
  *   N           number of rows, >= 0 (N = 0 gives an empty kmap).
- *   K           kernel size: 1, 3, or 2 (K = 2 only together with stride 2).
+ *   K           kernel size: 1, 3, 2 (K = 2 only together with stride 2), or 5 (stride 1, transposed = 0 only).
  *   stride      >= 1 (stride 1 with transposed = 0 is the submanifold case).
  *   transposed  0: coords are P_in.  1: coords are the fine output set.
  *   out         receives a new kmap; release with spconv_kmap_destroy.
@@ -221,7 +228,8 @@ SPCONV_API int spconv_kmap_in_coords(const spconv_kmap* km, int32_t* dst, void* 
  * M[n][k] = j where p_j = s*q_n + delta_k (the pairs that Equation 1 sums over), -1 = absent. */
 SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* stream);
 
-/* Copies the neighbour bitmasks (uint32 [n_out], Section 2.2.3) to dst (device). */
+/* Copies the neighbour bitmasks (uint32 [n_out], Section 2.2.3) to dst (device).  K = 5: uint32
+ * [n_out][4], bit k of a row's 125-bit mask in bit k % 32 of word k / 32; dst 16-byte aligned. */
 SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, void* stream);
 
 /* Builds (and caches in the kmap) everything op needs under cfg before the

@@ -215,7 +215,9 @@ class KMap:
         return dst
 
     def export_mask(self, stream=None):
-        dst = torch.empty((self.n_out,), dtype=torch.int32, device="cuda")  # bit patterns of uint32
+        # bit patterns of uint32; K = 5: four words per row (bit k of the mask is bit k % 32 of word k // 32)
+        shape = (self.n_out, 4) if self.K == 5 else (self.n_out,)
+        dst = torch.empty(shape, dtype=torch.int32, device="cuda")
         _check(load_library().spconv_kmap_export_mask(self.handle, _ptr(dst), _stream(stream)), "spconv_kmap_export_mask")
         return dst
 

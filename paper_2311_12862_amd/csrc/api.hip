@@ -235,6 +235,61 @@ int static_scratch(void** out) {
 
 // prepared_only: the call may not allocate.  Plans are looked up, never built (SPCONV_ENOPLAN when
 // missing), and split partial sums go to the fixed scratch array (SPCONV_ELIMIT beyond its size).
+// K = 5: forward / dgrad as the sum over the five 25-offset planes.  Every plane runs like a kmap of
+// its own (its plan, the kernel and tiles chosen for 25 offsets) and writes fp32 partial sums; one
+// reduction adds the parts of all planes and rounds once (Section 4.1's split reduction, over planes
+// as well as over mask splits).  Plane g holds the offsets 25 g .. 25 g + 24, so its weights are
+// that slice; dgrad on the submanifold map mirrors the offset, 124 - k, which is offset 24 - j of
+// plane 4 - g.
+int run_planes(spconv_op op, const void* src, const void* weights, spconv_kmap* km, int C_in, int C_out,
+               spconv_dtype dtype, const spconv_config* cfg, const spconv_config& c_in, void* dst, hipStream_t st) {
+  const int64_t rows = km->n_out;
+  const int dgrad = op == SPCONV_OP_DGRAD;
+  const int c_red = dgrad ? C_out : C_in, c_dst = dgrad ? C_in : C_out;
+  const size_t e = dtype == SPCONV_F32 ? 4 : 2;
+  const int n_planes = (int)km->groups.size();
+  struct Launch {
+    IgemmPlan* plan;
+    bool wave;
+    int tile_n;
+  };
+  std::vector<Launch> ls((size_t)n_planes);
+  int parts_total = 0;
+  for (int g = 0; g < n_planes; ++g) {
+    spconv_kmap* sub = km->groups[(size_t)g].get();
+    sub->last_stream = st;
+    spconv_config c = c_in;
+    KernelChoice kc;
+    SPC_TRY(choose_kernel(sub->V, rows, c_red, c_dst, dtype, cfg && cfg->tile_m != 0, c, &kc));
+    c.tile_m = kc.wave ? c.tile_m : kc.tile_m;
+    SPC_TRY(plan_get(sub, sub->out_side, c.n_split, plan_tile(c, kc.wave), st, &ls[(size_t)g].plan));
+    ls[(size_t)g].wave = kc.wave;
+    ls[(size_t)g].tile_n = kc.tile_n;
+    parts_total += ls[(size_t)g].plan->parts;
+  }
+  SPC_TRY(km->scratch.reserve((size_t)parts_total * rows * c_dst * sizeof(float)));
+  int part0 = 0;
+  for (int g = 0; g < n_planes; ++g) {
+    spconv_kmap* sub = km->groups[(size_t)g].get();
+    const int wg = dgrad ? n_planes - 1 - g : g;
+    IgemmArgs a{};
+    a.feats = src;
+    a.weights = static_cast<const char*>(weights) + (size_t)wg * sub->V * C_in * C_out * e;
+    a.C_in = C_in;
+    a.C_out = C_out;
+    a.dgrad = dgrad;
+    a.mirror = dgrad;
+    a.dtype = dtype;
+    a.tile_n = ls[(size_t)g].tile_n;
+    a.out = nullptr;
+    a.partial = km->scratch.as<float>() + (size_t)part0 * rows * c_dst;
+    const IgemmPlan& plan = *ls[(size_t)g].plan;
+    SPC_TRY(ls[(size_t)g].wave ? igemm_wave_run(sub, sub->out_side, plan, a, st) : igemm_run(sub, sub->out_side, plan, a, st));
+    part0 += plan.parts;
+  }
+  return split_reduce(km->scratch.as<float>(), parts_total, rows, c_dst, dtype, dst, st);
+}
+
 int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap* km, int C_in, int C_out,
                  spconv_dtype dtype, const spconv_config* cfg, void* dst, hipStream_t st,
                  bool prepared_only = false) {
@@ -246,6 +301,10 @@ int run_igemm_op(spconv_op op, const void* src, const void* weights, spconv_kmap
   if (!src || !weights || !dst) return SPCONV_EINVAL;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
+  if (!km->groups.empty()) {
+    if (prepared_only || c.kernel == 3) return SPCONV_EINVAL;
+    return run_planes(op, src, weights, km, C_in, C_out, dtype, cfg, c, dst, st);
+  }
   if (c.kernel == 3) {  // fetch-on-demand dataflow over the weight-stationary pair lists
     if (prepared_only) return SPCONV_EINVAL;
     const int dgrad = op == SPCONV_OP_DGRAD;
@@ -326,8 +385,9 @@ SPCONV_API int spconv_build_kmap(const int32_t* coords, int64_t N, int K, int st
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
   if (N < 0 || N > (int64_t)0x7FFFFF00 / 32 || (N > 0 && !coords)) return SPCONV_EINVAL;
-  if (K != 1 && K != 2 && K != 3) return SPCONV_EINVAL;
+  if (K != 1 && K != 2 && K != 3 && K != 5) return SPCONV_EINVAL;
   if (K == 2 && stride != 2) return SPCONV_EINVAL;  // the even kernel is the non-overlapping 2x2x2 / stride-2 layer
+  if (K == 5 && (stride != 1 || transposed)) return SPCONV_EINVAL;  // K = 5: submanifold maps only
   if (stride < 1 || stride > 64) return SPCONV_EINVAL;
   if (transposed != 0 && transposed != 1) return SPCONV_EINVAL;
   return kmap_build(coords, N, K, stride, transposed, false, (hipStream_t)stream, out);
@@ -369,7 +429,7 @@ SPCONV_API int spconv_kmap_transpose(spconv_kmap* km, void* stream, spconv_kmap*
   StreamScope scope((hipStream_t)stream);
   if (!out) return SPCONV_EINVAL;
   *out = nullptr;
-  if (!km) return SPCONV_EINVAL;
+  if (!km || !km->groups.empty()) return SPCONV_EINVAL;
   km->last_stream = (hipStream_t)stream;
   return kmap_transpose(km, (hipStream_t)stream, out);
 }
@@ -413,6 +473,16 @@ SPCONV_API int spconv_kmap_export(const spconv_kmap* km, int32_t* dst, void* str
   StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_out > 0)) return SPCONV_EINVAL;
   if (km->n_out == 0) return SPCONV_OK;
+  if (!km->groups.empty()) {  // K = 5: column 25 g + j of the whole map is column j of plane g
+    const size_t n_planes = km->groups.size();
+    for (size_t g = 0; g < n_planes; ++g) {
+      const spconv_kmap& sub = *km->groups[g];
+      SPC_HIP(hipMemcpy2DAsync(dst + g * sub.V, (size_t)km->V * sizeof(int32_t), sub.out_side.map.p,
+                               (size_t)sub.V * sizeof(int32_t), (size_t)sub.V * sizeof(int32_t), (size_t)km->n_out,
+                               hipMemcpyDeviceToDevice, (hipStream_t)stream));
+    }
+    return SPCONV_OK;
+  }
   SPC_HIP(hipMemcpyAsync(dst, km->out_side.map.p, (size_t)km->n_out * km->V * sizeof(int32_t),
                          hipMemcpyDeviceToDevice, (hipStream_t)stream));
   return SPCONV_OK;
@@ -422,6 +492,7 @@ SPCONV_API int spconv_kmap_export_mask(const spconv_kmap* km, uint32_t* dst, voi
   StreamScope scope((hipStream_t)stream);
   if (!km || (!dst && km->n_out > 0)) return SPCONV_EINVAL;
   if (km->n_out == 0) return SPCONV_OK;
+  if (!km->groups.empty()) return kmap_export_mask_words(km, dst, (hipStream_t)stream);
   SPC_HIP(hipMemcpyAsync(dst, km->out_side.mask.p, (size_t)km->n_out * sizeof(uint32_t), hipMemcpyDeviceToDevice,
                          (hipStream_t)stream));
   return SPCONV_OK;
@@ -432,6 +503,10 @@ SPCONV_API int spconv_kmap_prepare(spconv_kmap* km, spconv_op op, const spconv_c
   if (!km || op < SPCONV_OP_FWD || op > SPCONV_OP_WGRAD) return SPCONV_EINVAL;
   hipStream_t st = (hipStream_t)stream;
   km->last_stream = st;
+  if (!km->groups.empty()) {
+    for (auto& sub : km->groups) SPC_TRY(spconv_kmap_prepare(sub.get(), op, cfg, stream));
+    return SPCONV_OK;
+  }
   spconv_config c;
   SPC_TRY(resolve_config(cfg, SPCONV_F16, &c));
   if (op == SPCONV_OP_WGRAD) {
@@ -461,6 +536,10 @@ SPCONV_API int spconv_kmap_drop_plans(spconv_kmap* km) {
     km->in_side.ready = false;
   }
   km->wplans.clear();
+  for (auto& sub : km->groups) {
+    sub->out_side.plans.clear();
+    sub->wplans.clear();
+  }
   return SPCONV_OK;
 }
 
@@ -471,6 +550,10 @@ SPCONV_API int spconv_kmap_export_perm(spconv_kmap* km, spconv_op op, const spco
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, SPCONV_F16, &c));
+  if (!km->groups.empty()) {  // parts of plane 0, then of plane 1, ...
+    if (c.n_split == 0 || split < 0 || split >= c.n_split * (int)km->groups.size()) return SPCONV_EINVAL;
+    return spconv_kmap_export_perm(km->groups[split / c.n_split].get(), op, cfg, split % c.n_split, dst, stream);
+  }
   if (c.n_split == 0 || split < 0 || split >= c.n_split) return SPCONV_EINVAL;
   OpSide os;
   SPC_TRY(side_for(km, op, st, &os));
@@ -489,6 +572,16 @@ SPCONV_API int spconv_kmap_mac_units(spconv_kmap* km, spconv_op op, const spconv
   hipStream_t st = (hipStream_t)stream;
   spconv_config c;
   SPC_TRY(resolve_config(cfg, SPCONV_F16, &c));
+  if (!km->groups.empty()) {
+    *executed = *effective = 0;
+    for (auto& sub : km->groups) {
+      int64_t ex = 0, ef = 0;
+      SPC_TRY(spconv_kmap_mac_units(sub.get(), op, cfg, &ex, &ef, stream));
+      *executed += ex;
+      *effective += ef;
+    }
+    return SPCONV_OK;
+  }
   if (km->n_pairs < 0) SPC_TRY(kmap_count_pairs(km, st, nullptr));
   *effective = km->n_pairs;
   if (c.kernel == 3) {  // fetch-on-demand walks the pair lists: nothing but valid pairs is multiplied
@@ -535,6 +628,13 @@ SPCONV_API int spconv_wgrad(const void* feats, const void* dout, spconv_kmap* km
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
   km->last_stream = st;
+  if (!km->groups.empty()) {  // each plane fills its own 25 slices of dW
+    for (size_t g = 0; g < km->groups.size(); ++g) {
+      spconv_kmap* sub = km->groups[g].get();
+      SPC_TRY(spconv_wgrad(feats, dout, sub, C_in, C_out, dtype, cfg, dweights + g * (size_t)sub->V * C_in * C_out, stream));
+    }
+    return SPCONV_OK;
+  }
   if (km->n_pairs < 0 && !km->pending) SPC_TRY(kmap_count_pairs(km, st, nullptr));
   const int64_t target = c.wgrad_pairs > 0 ? c.wgrad_pairs : auto_wgrad_pairs(km, C_in, C_out);
   WgradPlan* wp = nullptr;
@@ -547,6 +647,7 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
   StreamScope scope((hipStream_t)stream);
   if (!km || !best || !dtype_ok(dtype) || op < SPCONV_OP_FWD || op > SPCONV_OP_WGRAD || layers_sharing_kmap < 1)
     return SPCONV_EINVAL;
+  if (!km->groups.empty()) return SPCONV_EINVAL;  // (K = 5 kmaps run the automatic or the caller's configuration)
   SPC_TRY(check_channels(C_in, C_out, dtype));
   hipStream_t st = (hipStream_t)stream;
   const size_t e = dtype == SPCONV_F32 ? 4 : 2;
@@ -731,6 +832,7 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
                                  spconv_config* wgrad, float* group_us, void* stream) {
   StreamScope scope((hipStream_t)stream);
   if (!km || !layers || n_layers < 1 || !fwd || !dtype_ok(dtype)) return SPCONV_EINVAL;
+  if (!km->groups.empty()) return SPCONV_EINVAL;
   if (training && (!dgrad || !wgrad)) return SPCONV_EINVAL;
   int max_ci = 0, max_co = 0;
   std::vector<std::pair<int, int>> shapes;  // distinct shapes
@@ -892,14 +994,14 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
 
 SPCONV_API int spconv_describe_launch(int K, int64_t rows, int64_t rows_src, int C_red, int C_cols, spconv_dtype dtype,
                                       const spconv_config* cfg, int dgrad, spconv_launch_info* out) {
-  if (!out || !dtype_ok(dtype) || (K != 1 && K != 2 && K != 3) || rows < 0 || rows_src < 0 || (dgrad != 0 && dgrad != 1))
+  if (!out || !dtype_ok(dtype) || (K != 1 && K != 2 && K != 3 && K != 5) || rows < 0 || rows_src < 0 || (dgrad != 0 && dgrad != 1))
     return SPCONV_EINVAL;
   std::memset(out, 0, sizeof(*out));
   SPC_TRY(check_channels(C_red, C_cols, dtype));
   spconv_config c;
   SPC_TRY(resolve_config(cfg, dtype, &c));
   if (c.kernel == 3) return SPCONV_EINVAL;  // (fetch-on-demand launches are sized by the pair lists, not by these shapes)
-  const int V = K * K * K;
+  const int V = K == 5 ? 25 : K * K * K;  // K = 5 launches once per 25-offset plane: the launch of one plane
   if (c.n_split > V) return SPCONV_EINVAL;
   if (rows == 0) return SPCONV_OK;  // nothing is launched
   KernelChoice kc;

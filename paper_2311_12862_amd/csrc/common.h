@@ -139,6 +139,11 @@ struct spconv_kmap {
   spconv_kmap(const spconv_kmap&) = delete;
   spconv_kmap& operator=(const spconv_kmap&) = delete;
   std::map<int64_t, std::unique_ptr<spc::WgradPlan>> wplans;  // by target_pairs
+  // K = 5 (125 offsets): the kmap is held as its five x-planes, each a submanifold map of 25 offsets
+  // (dx = g - 2) over the same rows, so that masks, sort keys and tile masks stay 32-bit words and
+  // every kernel runs on a plane as it runs on a 27-offset map; the planes' results are summed like
+  // the parts of a split.  Offset k of the whole map is offset k % 25 of plane k / 25.
+  std::vector<std::unique_ptr<spconv_kmap>> groups;
   spc::DevBuf scratch;    // split partial sums / wgrad partial tiles
   // build whose status was not read yet: the pinned block the probe kernel publishes flags and
   // pair count to, with the event that marks the probe's completion
@@ -157,6 +162,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
 int kmap_status(spconv_kmap* km, hipStream_t st);  // resolves a pending asynchronous build (synchronises)
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st);
 int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k /*[V] or null*/);
+int kmap_export_mask_words(const spconv_kmap* km, uint32_t* dst, hipStream_t st);  // K = 5: [n_out][4]
 int kmap_transpose(spconv_kmap* src, hipStream_t st, spconv_kmap** out);
 int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap** out);
 
@@ -219,7 +225,7 @@ struct IgemmArgs {
   const void* feats;    // [rows_src][c_red]
   const void* weights;  // [V][C_in][C_out] (always the forward layout)
   void* out;            // [rows][c_out_eff] in dtype, or nullptr when partial sums are used
-  float* partial;       // [parts][rows][c_out_eff] fp32 when parts > 1
+  float* partial;       // [parts][rows][c_out_eff] fp32: the kernels write partial sums whenever this is set
   int C_in, C_out;      // of the layer (forward orientation)
   int dgrad;            // 0: reduce over C_in, produce C_out.  1: reduce over C_out, produce C_in
   int mirror;           // weight slice of map column k is V-1-k (dgrad on the submanifold map itself)

@@ -376,7 +376,7 @@ __global__ void __launch_bounds__(NW * 64) k_igemm(const IgemmParams p) {
         const int col = n0 + wave_n * WN + nb * 16 + (lane & 15);
         if (col >= c_out) continue;
         const float v = acc[mb][nb][r];
-        if (p.parts > 1)
+        if (p.partial)
           p.partial[((long long)part * p.rows + orow) * c_out + col] = v;
         else
           reinterpret_cast<T*>(p.out)[(long long)orow * c_out + col] = (T)v;
@@ -480,7 +480,7 @@ __global__ void __launch_bounds__(256) k_igemm_f32(const IgemmParams p) {
     for (int j = 0; j < 4; ++j) {
       const int col = n0 + tx * 4 + j;
       if (col >= c_out) continue;
-      if (p.parts > 1)
+      if (p.partial)
         p.partial[((long long)part * p.rows + orow) * c_out + col] = acc[i][j];
       else
         reinterpret_cast<float*>(p.out)[(long long)orow * c_out + col] = acc[i][j];

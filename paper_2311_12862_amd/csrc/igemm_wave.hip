@@ -352,7 +352,7 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   offsets_done:
 
     // ---- output rows
-    if (p.parts > 1) {
+    if (p.partial) {
       // fp32 partial sums: lane holds rows 4*(lane/16)+r, column lane%16 of each 16-column block
       int o4[4];
 #pragma unroll

@@ -338,6 +338,43 @@ __global__ void __launch_bounds__(256) k_probe(const int4* __restrict__ rows, in
   }
 }
 
+// K = 5, submanifold: the 125 offsets as five x-planes of 25 (dx = g - 2; offset j of a plane is
+// dy = j / 5 - 2, dz = j % 5 - 2), one map and one 25-bit mask array per plane.  blockIdx.y is the
+// plane; one lane per (row, offset of the plane), two rows per wave.
+struct Planes5 {
+  int* map[5];
+  unsigned* mask[5];
+};
+constexpr int kPlaneSlots = 12;  // pair-count slots per plane (5 x 12 <= kPairSlots)
+__global__ void __launch_bounds__(256)
+    k_probe_planes5(const int4* __restrict__ rows, int n_rows, const unsigned long long* __restrict__ tab, int log_cap,
+                    Planes5 pl, Ctl* ctl) {
+  __shared__ unsigned wave_pairs[4];
+  constexpr int VP = 25, RPW = 2;
+  const int g = blockIdx.y;
+  const int lane = threadIdx.x & 63;
+  const long long wave = ((long long)blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+  const int sub = lane / VP, k = lane - sub * VP;
+  const long long row = wave * RPW + sub;
+  const bool active = (sub < RPW) && (row < n_rows);
+  int found = -1;
+  if (active) {
+    const int4 c = rows[row];
+    const int tx = c.y + g - 2, ty = c.z + k / 5 - 2, tz = c.w + k % 5 - 2;
+    if (coord_ok(c.x, c.y, c.z, c.w) && coord_ok(c.x, tx, ty, tz))
+      found = table_find(tab, log_cap, pack_key(c.x, tx, ty, tz), nullptr);
+    pl.map[g][row * VP + k] = found;
+  }
+  const unsigned long long bal = __ballot(found >= 0);
+  if (active && k == 0) pl.mask[g][row] = (unsigned)((bal >> (sub * VP)) & ((1ull << VP) - 1ull));
+  if (lane == 0) wave_pairs[threadIdx.x >> 6] = (unsigned)__popcll(bal);
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned n = wave_pairs[0] + wave_pairs[1] + wave_pairs[2] + wave_pairs[3];
+    if (n) atomicAdd(&ctl->pairs[(g * kPlaneSlots + blockIdx.x % kPlaneSlots) * 16], (unsigned long long)n);
+  }
+}
+
 // Strided 3x3x3 map built from the input side.  Input p meets output q exactly when
 // p = s*q + delta with delta in {-1, 0, 1}^3 (Eq. 1 with stride s), so per axis q is floor(p/s)
 // (delta = p - s*q, if that is <= 1) or floor(p/s) + 1 (delta = p - s*q, if that is >= -1): at most
@@ -870,6 +907,56 @@ int build_submanifold3(spconv_kmap* km, const int4* rows, int64_t N, bool async,
   return SPCONV_OK;
 }
 
+// K = 5 submanifold build: one table of the rows, one probe launch over the five planes, one read of
+// the control block (flags and the planes' pair counts).
+int build_submanifold5(spconv_kmap* km, const int4* rows, int64_t N, hipStream_t st) {
+  constexpr int VP = 25;
+  DevBuf ctl_buf, tab, own_rows;
+  SPC_TRY(ctl_buf.alloc(sizeof(Ctl)));
+  Ctl* ctl = ctl_buf.as<Ctl>();
+  hipLaunchKernelGGL(k_ctl_init, dim3(1), dim3(kPairSlots), 0, st, ctl);
+  SPC_LAUNCH_CHECK();
+  const int lc = log2_capacity(N);
+  SPC_TRY(tab.alloc((size_t)16 << lc));
+  SPC_TRY(fill_u32(tab.p, (int64_t)4 << lc, 0xFFFFFFFFu, st));
+  SPC_TRY(own_rows.alloc((size_t)N * 16));
+  hipLaunchKernelGGL(k_insert_rows, dim3(blocks_for(N, 256)), dim3(256), 0, st, rows, (int)N,
+                     tab.as<unsigned long long>(), lc, ctl, own_rows.as<int4>());
+  SPC_LAUNCH_CHECK();
+  Planes5 pl{};
+  for (int g = 0; g < 5; ++g) {
+    std::unique_ptr<spconv_kmap> sub(new (std::nothrow) spconv_kmap(
+        std::make_shared<SideMap>(), std::make_shared<SideMap>(), km->in_coords_ref, km->out_coords_ref));
+    if (!sub) return SPCONV_ENOMEM;
+    sub->K = 5;
+    sub->V = VP;
+    sub->n_in = sub->n_out = N;
+    sub->build_stream = sub->last_stream = st;
+    SPC_TRY(alloc_side(sub->out_side, N, VP, st));
+    sub->out_side.ready = true;
+    pl.map[g] = sub->out_side.map.as<int>();
+    pl.mask[g] = sub->out_side.mask.as<unsigned>();
+    km->groups.push_back(std::move(sub));
+  }
+  hipLaunchKernelGGL(k_probe_planes5, dim3(blocks_for(ceil_div(N, 2), 4), 5), dim3(256), 0, st, rows, (int)N,
+                     tab.as<unsigned long long>(), lc, pl, ctl);
+  SPC_LAUNCH_CHECK();
+  Ctl h{};
+  SPC_TRY(read_ctl(ctl, &h, st));
+  std::swap(km->in_coords.p, own_rows.p);  // P_out == P_in: out_coords stays empty
+  std::swap(km->in_coords.bytes, own_rows.bytes);
+  km->n_in = km->n_out = N;
+  km->n_pairs = 0;
+  for (int g = 0; g < 5; ++g) {
+    int64_t n = 0;
+    for (int i = 0; i < kPlaneSlots; ++i) n += (int64_t)h.pairs[(g * kPlaneSlots + i) * 16];
+    km->groups[g]->n_pairs = n;
+    km->n_pairs += n;
+  }
+  km->build_status = flags_status(h);
+  return km->build_status;
+}
+
 }  // namespace
 
 struct HostCtlHandle {
@@ -943,6 +1030,11 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   }
 
   const int4* rows = reinterpret_cast<const int4*>(coords);
+  if (K == 5) {  // (submanifold only: the entry points refuse other K = 5 maps)
+    SPC_TRY(build_submanifold5(km.get(), rows, N, st));  // (range and duplicate errors: no kmap, as for every synchronous build)
+    *out = km.release();
+    return SPCONV_OK;
+  }
   if (K == 3 && stride == 1 && !transposed && !dilate) {
     SPC_TRY(build_submanifold3(km.get(), rows, N, async, st));
     *out = km.release();
@@ -1253,6 +1345,38 @@ int kmap_count_pairs(spconv_kmap* km, hipStream_t st, int64_t* per_k) {
     if (per_k) per_k[k] = (int64_t)h[k];
   }
   km->n_pairs = total;
+  return SPCONV_OK;
+}
+
+namespace {
+// The 125-bit mask of a K = 5 row from its planes' 25-bit masks: bit k of the row's mask is bit
+// k % 32 of word k / 32, and k = 25 g + j.
+__global__ void __launch_bounds__(256) k_join_masks5(Planes5 pl, long long rows, uint4* __restrict__ dst) {
+  const long long r = (long long)blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= rows) return;
+  unsigned long long lo = 0, hi = 0;  // bits 0..63, 64..127
+#pragma unroll
+  for (int g = 0; g < 5; ++g) {
+    const unsigned long long m = pl.mask[g][r];
+    const int at = 25 * g;
+    if (at < 64) {
+      lo |= m << at;
+      if (at + 25 > 64) hi |= m >> (64 - at);
+    } else {
+      hi |= m << (at - 64);
+    }
+  }
+  dst[r] = make_uint4((unsigned)lo, (unsigned)(lo >> 32), (unsigned)hi, (unsigned)(hi >> 32));
+}
+}  // namespace
+
+int kmap_export_mask_words(const spconv_kmap* km, uint32_t* dst, hipStream_t st) {
+  if (km->groups.size() != 5) return SPCONV_EINVAL;
+  Planes5 pl{};
+  for (int g = 0; g < 5; ++g) pl.mask[g] = km->groups[(size_t)g]->out_side.mask.as<unsigned>();
+  hipLaunchKernelGGL(k_join_masks5, dim3(blocks_for(km->n_out, 256)), dim3(256), 0, st, pl, (long long)km->n_out,
+                     reinterpret_cast<uint4*>(dst));
+  SPC_LAUNCH_CHECK();
   return SPCONV_OK;
 }
 

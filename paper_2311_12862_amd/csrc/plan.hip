@@ -858,6 +858,8 @@ int wplan_get(spconv_kmap* km, int64_t target_pairs, hipStream_t st, WgradPlan**
                      p->max_items, p->seg.as<int>(), p->items.as<WgradItem>(), p->item_seg.as<int>())
   if (V == 27) {
     if (self_scan) SPC_FILL(27, true); else SPC_FILL(27, false);
+  } else if (V == 25) {  // a plane of a K = 5 map
+    if (self_scan) SPC_FILL(25, true); else SPC_FILL(25, false);
   } else if (V == 8) {
     if (self_scan) SPC_FILL(8, true); else SPC_FILL(8, false);
   } else {

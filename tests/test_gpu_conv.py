@@ -469,3 +469,42 @@ def test_two_kmaps_on_two_streams(sp):
         assert norm_err(y, oc.forward(x32, w32, r.M)) <= TOL["f16"]
         assert norm_err(dx, oc.dgrad(g32, w32, r.M, r.n_in)) <= TOL["f16"]
         assert norm_err(dw, oc.wgrad(x32, g32, r.M)) <= 1e-4
+
+
+@pytest.fixture(scope="module")
+def cloud5():
+    """A cloud for the 5 x 5 x 5 neighbourhood: several 256-row tiles, a ragged tail, two batches."""
+    c = gen.uniform_cloud(2500, 18, seed=555)
+    c[:900, 0] = 1
+    return c, oc.build_kmap(c, 5, 1)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "f32"])
+@pytest.mark.parametrize("n_split,kernel", [(0, 0), (1, 1), (2, 2), (3, 0)])
+def test_k5_forward_dgrad_wgrad(sp, cloud5, dtype, n_split, kernel):
+    """K = 5 submanifold layer (Equation 1 over the 125 offsets of Section 2.1): the sum over five
+    25-offset planes, each run like a map of its own, against the oracle on the whole map."""
+    if dtype == "f32" and kernel == 1:
+        pytest.skip("kernel 1 is a 16-bit kernel")
+    c, ref = cloud5
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 32, 64, 125, dtype, 123)
+    km = sp.build_kmap(coords_dev(c), 5, 1)
+    cfg = _cfg(sp, n_split, kernel=kernel)
+    assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL[dtype]
+    assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL[dtype]
+    assert norm_err(sp.wgrad(x, g, km), oc.wgrad(x32, g32, ref.M)) <= 1e-4
+    ex, eff = km.mac_units(sp.OP_FWD, cfg)
+    assert eff == int((ref.M >= 0).sum()) and ex >= eff
+    km.destroy()
+
+
+def test_k5_sort_order_per_plane(sp, cloud5):
+    """Sorted K = 5 plans: every plane's rows in stable ascending order of that plane's 25-bit mask."""
+    c, ref = cloud5
+    km = sp.build_kmap(coords_dev(c), 5, 1)
+    cfg = _cfg(sp, 1)
+    big = oc.bitmask(ref.M)
+    for g in range(5):
+        key = np.array([(int(m) >> (25 * g)) & ((1 << 25) - 1) for m in big], np.int64)
+        _check_order(km.export_perm(sp.OP_FWD, cfg, g).cpu().numpy(), key, ref.n_out)
+    km.destroy()

@@ -119,7 +119,7 @@ def test_errors(sp):
         with pytest.raises(sp.SpconvError) as e:
             sp.build_kmap(coords_dev(r), 3, 1)
         assert e.value.status == -2
-    for K, stride in ((2, 1), (5, 1), (3, 0), (3, 65)):
+    for K, stride in ((2, 1), (5, 2), (7, 1), (3, 0), (3, 65)):
         with pytest.raises(sp.SpconvError) as e:
             sp.build_kmap(coords_dev(c), K, stride)
         assert e.value.status == -1
@@ -431,3 +431,57 @@ def test_dilated_errors_and_k1(sp):
     assert lib.spconv_build_kmap_dilated(None, 0, 2, None, ctypes.byref(out)) == -1
     empty = sp.build_kmap(torch.empty((0, 4), dtype=torch.int32, device="cuda"), 3, 1, dilate=True)
     assert empty.n_out == 0
+
+
+def _mask_words(big, words):
+    """Python-int bitmasks -> uint32 [n][words], bit k in bit k % 32 of word k // 32."""
+    out = np.zeros((len(big), words), np.uint32)
+    for r, m in enumerate(big):
+        m = int(m)
+        for w in range(words):
+            out[r, w] = (m >> (32 * w)) & 0xFFFFFFFF
+    return out
+
+
+@pytest.mark.parametrize("n,grid,lo", [(2000, 20, 0), (3000, 16, -8), (300, 7, 32760)])
+def test_k5_submanifold_map_and_masks(sp, n, grid, lo):
+    """K = 5 (125 offsets, Section 2.1's neighbourhood for any odd K): the library holds the map as five
+    25-offset planes; what it exports is the whole map, bit for bit the oracle's, with 125-bit masks."""
+    c = gen.uniform_cloud(n, grid, seed=500 + n, lo=lo)
+    c[: n // 4, 0] = 3
+    ref = oc.build_kmap(c, 5, 1)
+    km = sp.build_kmap(coords_dev(c), 5, 1)
+    assert (km.n_in, km.n_out, km.V) == (ref.n_in, ref.n_out, 125)
+    np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
+    np.testing.assert_array_equal(km.in_coords().cpu().numpy(), ref.in_coords)
+    np.testing.assert_array_equal(km.out_coords().cpu().numpy(), ref.out_coords)
+    words = km.export_mask().cpu().numpy().view(np.uint32)
+    np.testing.assert_array_equal(words, _mask_words(oc.bitmask(ref.M), 4))
+    assert km.n_pairs() == int((ref.M >= 0).sum())
+    km.destroy()
+
+
+def test_k5_refusals(sp):
+    """K = 5 exists as a submanifold map only; duplicates and rows beside the range fail as for K = 3."""
+    c = gen.uniform_cloud(500, 16, seed=77)
+    for stride, transposed in ((2, False), (1, True)):
+        with pytest.raises(sp.SpconvError) as e:
+            sp.build_kmap(coords_dev(c), 5, stride, transposed)
+        assert e.value.status == -1
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(c), 5, 1, asynchronous=True)
+    assert e.value.status == -1
+    dup = np.concatenate([c, c[:1]])
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(dup), 5, 1)
+    assert e.value.status == -3
+    far = c.copy()
+    far[3, 2] = 40000
+    with pytest.raises(sp.SpconvError) as e:
+        sp.build_kmap(coords_dev(far), 5, 1)
+    assert e.value.status == -2
+    km = sp.build_kmap(coords_dev(c), 5, 1)
+    with pytest.raises(sp.SpconvError) as e:
+        km.transpose()
+    assert e.value.status == -1
+    km.destroy()

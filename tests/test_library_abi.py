@@ -44,7 +44,7 @@ def test_argument_errors_need_no_gpu():
     assert lib.spconv_kmap_sizes(None, None, None, None) == -1
     assert lib.spconv_fwd(None, None, None, 64, 64, 1, None, None, None) == -1
     assert lib.spconv_fwd_noalloc(None, None, None, 64, 64, 1, None, None, None) == -1
-    for K, stride, transposed in ((4, 1, 0), (5, 1, 0), (3, 0, 0), (3, 65, 0), (3, 1, 2), (2, 1, 0), (2, 3, 0)):
+    for K, stride, transposed in ((4, 1, 0), (5, 2, 0), (5, 1, 1), (7, 1, 0), (3, 0, 0), (3, 65, 0), (3, 1, 2), (2, 1, 0), (2, 3, 0)):
         assert lib.spconv_build_kmap(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1, (K, stride)
         assert lib.spconv_build_kmap_async(None, 0, K, stride, transposed, None, ctypes.byref(out)) == -1
     assert lib.spconv_build_kmap(None, 0, 3, 1, 0, None, None) == -1

@@ -97,8 +97,9 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *               rows are visited in ascending order of that range's bitmask
  *               bits (stable), and for s > 1 the fp32 partial sums of the
  *               ranges are added by a reduction kernel.
- *   kernel      which fwd / dgrad kernel runs (F16 / BF16 only; F32 always runs
- *               its one kernel and refuses kernel = 3):
+ *   kernel      which fwd / dgrad kernel runs (F32 has one implicit-GEMM kernel,
+ *               which runs for 0, 1 and 2, and one fetch-on-demand kernel with
+ *               tiles of 64 pairs x 64 channels for 3):
  *               1: weights of a split resident in LDS, one wave per 16-row
  *                  block (needs reduced channels <= 128 and the split's
  *                  weight slices for tile_n channels to fit in LDS, else
@@ -117,7 +118,7 @@ typedef struct spconv_kmap spconv_kmap; /* opaque */
  *                  rows) is small, else 2.
  *   tile_m      output rows per workgroup of kernel 2: 64, 128 or 256 (0 = 64 or
  *               128, from the row count and the channel counts);
- *               pairs per workgroup of kernel 3: 64 or 128 (0 = 64).
+ *               pairs per workgroup of kernel 3: 64 or 128 (0 = 64; F32: 64 only).
  *   tile_n      output channels per workgroup: 16, 32, 64 (kernel 1) or 32, 64,
  *               128 (kernels 2 and 3); 0 = chosen from the channel counts (and,
  *               for kernel 2, from how many workgroups the rows give).

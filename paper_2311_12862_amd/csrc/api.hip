@@ -118,11 +118,11 @@ int resolve_config(const spconv_config* cfg, spconv_dtype dtype, spconv_config* 
   if (c.tile_m != 64 && c.tile_m != 128 && c.tile_m != 256) return SPCONV_EINVAL;
   if (c.tile_n != 0 && c.tile_n != 16 && c.tile_n != 32 && c.tile_n != 64 && c.tile_n != 128) return SPCONV_EINVAL;
   if (c.wgrad_pairs < 0 || c.kernel < 0 || c.kernel > 3 || (c.flags & ~SPCONV_FLAG_SLABS)) return SPCONV_EINVAL;
-  if (c.kernel == 3) {  // fetch-on-demand: unsorted pair lists, tiles of 64 or 128 pairs, 16-bit types
+  if (c.kernel == 3) {  // fetch-on-demand: unsorted pair lists, tiles of 64 or 128 pairs (fp32: 64)
     if (cfg->tile_m == 0) c.tile_m = 64;
-    if (dtype == SPCONV_F32 || c.n_split != 0 || c.tile_m == 256 || c.tile_n == 16) return SPCONV_EINVAL;
-  }
-  if (dtype == SPCONV_F32) {  // the fp32 kernel has one tile shape
+    if (c.n_split != 0 || c.tile_m == 256 || c.tile_n == 16) return SPCONV_EINVAL;
+    if (dtype == SPCONV_F32 && c.tile_m != 64) return SPCONV_EINVAL;
+  } else if (dtype == SPCONV_F32) {  // the fp32 implicit-GEMM kernel has one tile shape
     c.tile_m = 64;
     c.kernel = 2;
   }
@@ -685,6 +685,7 @@ SPCONV_API int spconv_tune(spconv_kmap* km, int C_in, int C_out, spconv_dtype dt
     const int c_red = op == SPCONV_OP_DGRAD ? C_out : C_in, c_dst = op == SPCONV_OP_DGRAD ? C_in : C_out;
     if (fod_supported(km, op == SPCONV_OP_DGRAD, C_in, C_out, dtype))
       for (int tm : {64, 128}) {  // the fetch-on-demand dataflow (its mapping: the pair lists)
+        if (dtype == SPCONV_F32 && tm != 64) continue;
         spconv_config c{};
         c.kernel = 3;
         c.tile_m = tm;
@@ -891,7 +892,7 @@ SPCONV_API int spconv_tune_group(spconv_kmap* km, const spconv_layer_shape* laye
         const int c_red = op == SPCONV_OP_DGRAD ? co : ci, c_dst = op == SPCONV_OP_DGRAD ? ci : co;
         std::vector<spconv_config> cands;
         for (int tm : {64, 128, 256}) {
-          if (fod ? tm == 256 : (dtype == SPCONV_F32 && tm != 64)) continue;
+          if (fod ? (tm == 256 || (dtype == SPCONV_F32 && tm != 64)) : (dtype == SPCONV_F32 && tm != 64)) continue;
           spconv_config c{};
           c.n_split = fod ? 0 : s;
           c.tile_m = tm;

@@ -249,6 +249,97 @@ __global__ void __launch_bounds__(256) k_fod(const FodParams p) {
   }
 }
 
+// fp32 fetch-on-demand (the precision of the paper's own dataflow comparison, Section 6.1): plain
+// FMA arithmetic, an item of up to 64 pairs x 64 output channels per workgroup, 4 x 4 products per
+// thread, the reduction in chunks of 16 channels through LDS; products added to the accumulator's
+// rows with the same atomics as the 16-bit kernel.
+constexpr int FF_BM = 64, FF_BN = 64, FF_KC = 16;
+__global__ void __launch_bounds__(256) k_fod_f32(const FodParams p) {
+  __shared__ float As[FF_BM][FF_KC + 1];
+  __shared__ float Bs[FF_KC][FF_BN + 4];
+  __shared__ int srcS[FF_BM], dstS[FF_BM];
+  const int item_id = blockIdx.x;
+  if (item_id >= p.item_seg[p.V]) return;  // the grid is sized by a bound on the item count
+  const int tid = threadIdx.x, tx = tid % 16, ty = tid / 16;
+  const int n0 = blockIdx.y * FF_BN;
+  const WgradItem item = p.items[item_id];
+  int cnt = item.pair_end - item.pair_begin;
+  if (cnt > FF_BM) cnt = FF_BM;  // items are cut to at most 64 pairs by the plan
+  const __amdgpu_buffer_rsrc_t x_rsrc = make_rsrc(p.feats, p.feats_bytes);
+  const __amdgpu_buffer_rsrc_t w_rsrc = make_rsrc(p.weights, (unsigned)((size_t)p.V * p.C_in * p.C_out * 4));
+  const __amdgpu_buffer_rsrc_t p_rsrc = make_rsrc(p.pairs, p.pairs_bytes);
+  const __amdgpu_buffer_rsrc_t o_rsrc = make_rsrc(p.acc, p.acc_bytes);
+  const int c_red = p.c_red;
+  const unsigned row_bytes = (unsigned)c_red * 4u;
+  const unsigned wk = (unsigned)item.k * (unsigned)(p.C_in * p.C_out) * 4u;
+  if (tid < FF_BM) {
+    const bool live = tid < cnt;
+    const int2 pr = buf_load8(p_rsrc, live ? (unsigned)(item.pair_begin + tid) * 8u : 0xFFFFFFFFu);
+    srcS[tid] = live ? (p.dgrad ? pr.x : pr.y) : -1;
+    dstS[tid] = live ? (p.dgrad ? pr.y : pr.x) : -1;
+  }
+  __syncthreads();
+  float acc[4][4] = {};
+  const int n_chunks = (c_red + FF_KC - 1) / FF_KC;
+  for (int chunk = 0; chunk < n_chunks; ++chunk) {
+    {  // A: 64 rows x 16 floats, one 16-byte load per thread (a dead row or channel reads zeros)
+      const int r = tid / 4, seg = tid % 4;
+      const int idx = srcS[r];
+      const unsigned col = (unsigned)(chunk * FF_KC + seg * 4);
+      const uint4 v = buf_load16(x_rsrc, col < (unsigned)c_red ? (unsigned)idx * row_bytes + col * 4u : 0xFFFFFFFFu);
+      As[r][seg * 4 + 0] = __uint_as_float(v.x);
+      As[r][seg * 4 + 1] = __uint_as_float(v.y);
+      As[r][seg * 4 + 2] = __uint_as_float(v.z);
+      As[r][seg * 4 + 3] = __uint_as_float(v.w);
+    }
+    if (!p.dgrad) {  // B[kk][n] = W[k][ci = chunk*KC + kk][co = n0 + n]
+      const int kk = tid / 16, n4 = (tid % 16) * 4;
+      const int ci = chunk * FF_KC + kk, co = n0 + n4;
+      const uint4 v = buf_load16(w_rsrc, (ci < p.C_in && co < p.C_out) ? wk + (unsigned)(ci * p.C_out + co) * 4u : 0xFFFFFFFFu);
+      Bs[kk][n4 + 0] = __uint_as_float(v.x);
+      Bs[kk][n4 + 1] = __uint_as_float(v.y);
+      Bs[kk][n4 + 2] = __uint_as_float(v.z);
+      Bs[kk][n4 + 3] = __uint_as_float(v.w);
+    } else {  // B[kk][n] = W[k][ci = n0 + n][co = chunk*KC + kk]
+      const int n = tid / 4, kk4 = (tid % 4) * 4;
+      const int ci = n0 + n, co = chunk * FF_KC + kk4;
+      const uint4 v = buf_load16(w_rsrc, (ci < p.C_in && co < p.C_out) ? wk + (unsigned)(ci * p.C_out + co) * 4u : 0xFFFFFFFFu);
+      Bs[kk4 + 0][n] = __uint_as_float(v.x);
+      Bs[kk4 + 1][n] = __uint_as_float(v.y);
+      Bs[kk4 + 2][n] = __uint_as_float(v.z);
+      Bs[kk4 + 3][n] = __uint_as_float(v.w);
+    }
+    __syncthreads();
+#pragma unroll
+    for (int kk = 0; kk < FF_KC; ++kk) {
+      float a[4], b[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) a[i] = As[ty * 4 + i][kk];
+#pragma unroll
+      for (int j = 0; j < 4; ++j) b[j] = Bs[kk][tx * 4 + j];
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) acc[i][j] = fmaf(a[i], b[j], acc[i][j]);
+    }
+    __syncthreads();
+  }
+  const int c_out = p.c_out;
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int drow = dstS[ty * 4 + i];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int col = n0 + tx * 4 + j;
+      // (lanes of dead rows and of columns past the tensor issue nothing: an atomic needs an aligned
+      // address whether or not it is in range)
+      if (drow >= 0 && col < c_out)
+        __builtin_amdgcn_raw_ptr_buffer_atomic_fadd_f32(acc[i][j], o_rsrc,
+                                                        ((unsigned)drow * (unsigned)c_out + (unsigned)col) * 4u, 0, 0);
+    }
+  }
+}
+
 __global__ void __launch_bounds__(256) k_zero_f4(float4* __restrict__ dst, long long n4) {
   const long long stride = (long long)gridDim.x * blockDim.x;
   for (long long i = (long long)blockIdx.x * blockDim.x + threadIdx.x; i < n4; i += stride)
@@ -291,16 +382,18 @@ int launch_fod_bm(const FodParams& p, int bm, int bn, int kc, dim3 grid, hipStre
 }  // namespace
 
 bool fod_supported(const spconv_kmap* km, int dgrad, int C_in, int C_out, spconv_dtype dtype) {
-  if (dtype != SPCONV_F16 && dtype != SPCONV_BF16) return false;
+  if (dtype != SPCONV_F16 && dtype != SPCONV_BF16 && dtype != SPCONV_F32) return false;
   const int64_t rows_src = dgrad ? km->n_out : km->n_in, rows_dst = dgrad ? km->n_in : km->n_out;
   const int c_red = dgrad ? C_out : C_in, c_dst = dgrad ? C_in : C_out;
+  const uint64_t e = dtype == SPCONV_F32 ? 4 : 2;
   // buffer descriptors address 32 bits
-  return (uint64_t)rows_src * c_red * 2 < 0xFFFFC000ull && (uint64_t)rows_dst * c_dst * 4 < 0xFFFFC000ull &&
+  return (uint64_t)rows_src * c_red * e < 0xFFFFC000ull && (uint64_t)km->V * C_in * C_out * e < 0xFFFFC000ull && (uint64_t)rows_dst * c_dst * 4 < 0xFFFFC000ull &&
          (uint64_t)km->n_out * km->V * 8 < 0xFFFFC000ull;
 }
 
 int fod_run(spconv_kmap* km, const WgradPlan& wp, const IgemmArgs& a, int tile_m, void* dst, hipStream_t st) {
   if (tile_m != 64 && tile_m != 128) return SPCONV_EINVAL;
+  if (a.dtype == SPCONV_F32 && tile_m != FF_BM) return SPCONV_EINVAL;  // the fp32 kernel has one tile shape
   if (wp.target_pairs != tile_m) return SPCONV_EINVAL;  // one work item is one tile of pairs
   if (wp.max_items >= (1 << 20)) return SPCONV_EINVAL;  // the plan's item table is capped there
   if (!fod_supported(km, a.dgrad, a.C_in, a.C_out, a.dtype)) return SPCONV_EINVAL;
@@ -324,13 +417,19 @@ int fod_run(spconv_kmap* km, const WgradPlan& wp, const IgemmArgs& a, int tile_m
     p.pairs = wp.pairs.as<int2>();
     p.items = wp.items.as<WgradItem>();
     p.item_seg = wp.item_seg.as<int>();
-    p.feats_bytes = (unsigned)((uint64_t)rows_src * p.c_red * 2);
+    p.feats_bytes = (unsigned)((uint64_t)rows_src * p.c_red * (a.dtype == SPCONV_F32 ? 4 : 2));
     p.pairs_bytes = (unsigned)((uint64_t)wp.pairs_cap * 8);
     p.acc_bytes = (unsigned)acc_bytes;
     p.V = km->V;
     p.C_in = a.C_in;
     p.C_out = a.C_out;
     p.dgrad = a.dgrad;
+    if (a.dtype == SPCONV_F32) {
+      dim3 grid((unsigned)wp.max_items, (unsigned)ceil_div(p.c_out, FF_BN));
+      hipLaunchKernelGGL(k_fod_f32, grid, dim3(256), 0, st, p);
+      SPC_LAUNCH_CHECK();
+      return split_reduce(km->scratch.as<float>(), 1, rows_dst, p.c_out, a.dtype, dst, st);
+    }
     int bn = a.tile_n;
     if (bn == 0) bn = p.c_out <= 32 ? 32 : (p.c_out <= 64 ? 64 : 128);
     if (bn != 32 && bn != 64 && bn != 128) return SPCONV_EINVAL;

@@ -365,12 +365,13 @@ def test_group_tuner(sp, stride, bind):
 
 
 def test_group_tuner_fp32(sp):
-    """fp32 layers have one kernel and no fetch-on-demand path: the group tuner only varies the splits."""
+    """fp32 layers have one implicit-GEMM kernel and one fetch-on-demand kernel: the group tuner varies the splits
+    and the dataflow; whatever it picks is correct."""
     c = gen.lidar_scene(78, target_n=3000)
     km = sp.build_kmap(coords_dev(c), 3, 1)
     ref = oc.build_kmap(c, 3, 1)
     f, d, w, us = sp.tune_group(km, [(16, 24), (24, 16)], torch.float32, training=True)
-    assert us > 0 and all(x.kernel != 3 for x in f + d)
+    assert us > 0
     (x32, x), (w32, wt), (g32, g) = make_layer(ref.n_in, ref.n_out, 16, 24, 27, "f32", 950)
     assert norm_err(sp.fwd(x, wt, km, f[0]), oc.forward(x32, w32, ref.M)) <= TOL["f32"]
     assert norm_err(sp.dgrad(g, wt, km, d[0]), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f32"]

@@ -127,9 +127,32 @@ def test_rejected_configurations(sp, cloud):
             sp.fwd(x, w, km, bad)
         assert e.value.status == -1
     (x32, xf), (w32, wf), _ = make_layer(ref.n_in, ref.n_out, 16, 16, 27, "f32", 7)
-    with pytest.raises(sp.SpconvError) as e:   # 16-bit types only: the call must refuse, not fall back
-        sp.fwd(xf, wf, km, _cfg(sp))
+    with pytest.raises(sp.SpconvError) as e:   # the fp32 kernel has tiles of 64 pairs only: refuse, do not fall back
+        sp.fwd(xf, wf, km, _cfg(sp, 128))
     assert e.value.status == -1
+
+
+@pytest.mark.parametrize("c_in,c_out", [(16, 16), (64, 64), (36, 100), (128, 64)])
+def test_fp32_forward_and_dgrad(sp, cloud, c_in, c_out):
+    """fp32 is the precision of the paper's own dataflow comparison (Section 6.1): plain FMA tiles, the
+    same pair lists and atomic scatter; held to the fp32 tolerance."""
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, "f32", 9)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    for tile_m in (0, 64):
+        cfg = _cfg(sp, tile_m)
+        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f32"]
+        assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f32"]
+
+
+def test_fp32_strided_and_transposed(sp):
+    c = gen.lidar_scene(83, target_n=2500)
+    for transposed in (False, True):
+        ref = oc.build_kmap(c, 3, 2, transposed)
+        (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 24, 40, 27, "f32", 10)
+        km = sp.build_kmap(coords_dev(c), 3, 2, transposed)
+        assert norm_err(sp.fwd(x, w, km, _cfg(sp)), oc.forward(x32, w32, ref.M, ref.n_out)) <= TOL["f32"]
+        assert norm_err(sp.dgrad(g, w, km, _cfg(sp)), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f32"]
 
 
 def test_tuners_consider_it(sp):

@@ -2,12 +2,16 @@
 // generation for strided maps, neighbour probe, neighbour bitmask, and the
 // input-side (transposed) table that dgrad of strided maps walks.
 //
-// The paper treats these "mapping operations" as a cost centre (Sections 4.2,
+// The paper counts these mapping operations as a cost centre (Sections 4.2,
 // 6.1, 6.3) but gives no algorithm for them; the design below is this
-// library's own: one 16-byte slot per key (64-bit packed coordinate + row
-// index) in an open-addressing table at load factor <= 0.5, one probe lane per
-// (output row, offset) so that map writes are contiguous per wave, and the
-// bitmask assembled from a wave ballot.
+// library's own.  Submanifold 3x3x3 maps, the common case, hash runs of four
+// cells along z (one 32-byte entry per run) and read 13.5 entries per voxel,
+// each row writing its own map row and mask.  The other maps use one 16-byte
+// slot per key (64-bit packed coordinate + row index) in an open-addressing
+// table at load factor <= 0.5 and one probe lane per (output row, offset), so
+// that map writes are contiguous per wave and the bitmask comes from a wave
+// ballot; stride-2 3x3x3 maps are filled from the input side; K = 5 maps are
+// held as five planes of 25 offsets.
 #include "common.h"
 
 #include <chrono>

@@ -5,9 +5,10 @@
 // one exclusive scan over the [digit][wave] matrix, and a scatter in which a
 // wave ranks its 64 items per step with ballots (lanes with equal digits find
 // each other from one ballot per digit bit; the rank is the number of peers in
-// lower lanes) against wave-private running offsets held in LDS.  Used for the
-// bitmask argsort of Sections 2.2.3 / 4.1 and for putting the output
-// coordinates of strided maps into their canonical order.
+// lower lanes) against wave-private running offsets held in LDS.  Used for
+// putting the output coordinates of strided maps into their canonical order,
+// and for the bitmask argsort of Sections 2.2.3 / 4.1 on maps too large for
+// the one-launch-per-digit sort in plan.hip.
 #include "common.h"
 
 #include <atomic>

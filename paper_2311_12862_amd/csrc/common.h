@@ -172,6 +172,9 @@ int kmap_pointwise(spconv_kmap* src, int on_outputs, hipStream_t st, spconv_kmap
 // result ended up (0: buffer a, 1: buffer b).  hist must hold
 // sort_hist_elems(n) uint32.
 size_t sort_hist_elems(int64_t n);
+// plan.hip: one launch per digit, at most 131072 keys (SPCONV_EINVAL beyond); see there for error_word
+int msort_keys_u32(uint32_t* key_a, uint32_t* key_b, int64_t n, int key_bits, unsigned* error_word, unsigned error_bit,
+                   hipStream_t st, int* in_b);
 // Exclusive scan in place; `sums` is scratch of scan_sums_elems(elems) counters.
 size_t scan_sums_elems(int64_t elems);
 int scan_u32_inplace(uint32_t* data, int64_t elems, uint32_t* sums, hipStream_t st);

@@ -27,7 +27,8 @@ namespace {
 
 constexpr unsigned long long kEmpty = ~0ull;
 
-enum : unsigned long long { FLAG_RANGE = 1, FLAG_DUP = 2, FLAG_FULL = 4 };
+enum : unsigned long long { FLAG_RANGE = 1, FLAG_DUP = 2, FLAG_FULL = 4, FLAG_SORT = 8 };  // SORT: a sort's bounded wait ran out
+constexpr int kRetryGeneralSort = 1;  // (internal) build again with the general sort
 
 // Control block read back by the host at the build's synchronisation point.  The pair counter
 // is spread over 64 cache lines (one atomic per probe workgroup) so that the adds do not queue
@@ -1005,8 +1006,19 @@ int kmap_status_impl(spconv_kmap* km, hipStream_t st, bool wait_stream) {
 
 int kmap_status(spconv_kmap* km, hipStream_t st) { return kmap_status_impl(km, st, false); }
 
+namespace {
+int kmap_build_impl(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
+                    spconv_kmap** out, bool dilate, bool few_launch_sort);
+}
 int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
                spconv_kmap** out, bool dilate) {
+  const int status = kmap_build_impl(coords, N, K, stride, transposed, async, st, out, dilate, true);
+  if (status != kRetryGeneralSort) return status;
+  return kmap_build_impl(coords, N, K, stride, transposed, async, st, out, dilate, false);
+}
+namespace {
+int kmap_build_impl(const int32_t* coords, int64_t N, int K, int stride, int transposed, bool async, hipStream_t st,
+                    spconv_kmap** out, bool dilate, bool few_launch_sort) {
   std::unique_ptr<spconv_kmap> km(new (std::nothrow) spconv_kmap);
   if (!km) return SPCONV_ENOMEM;
   km->K = K;
@@ -1129,7 +1141,16 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
       hipLaunchKernelGGL(k_compress_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st,
                          ukeys_a.as<unsigned long long>(), (int)U, runs, dense_a);
       SPC_LAUNCH_CHECK();
-      SPC_TRY(radix_sort_u32(dense_a, dense_b, nullptr, nullptr, U, runs.total, hist.as<uint32_t>(), st, &in_b));
+      // Builds that read the control block once more at their end (stride-2 3x3x3) sort with one
+      // launch per digit; should one of its bounded waits run out, that read shows it and the
+      // build is done again with the general sort.
+      int sorted = SPCONV_EINVAL;
+      if (few_launch_sort && from_inputs)
+        sorted = msort_keys_u32(dense_a, dense_b, U, runs.total, reinterpret_cast<unsigned*>(&ctl->flags),
+                                (unsigned)FLAG_SORT, st, &in_b);
+      if (sorted == SPCONV_EINVAL)
+        sorted = radix_sort_u32(dense_a, dense_b, nullptr, nullptr, U, runs.total, hist.as<uint32_t>(), st, &in_b);
+      SPC_TRY(sorted);
       hipLaunchKernelGGL(k_expand_keys, dim3(blocks_for(U, 256)), dim3(256), 0, st, in_b ? dense_b : dense_a, (int)U,
                          runs, coarse_rows.as<int4>(),
                          want_rank ? tab_coarse.as<unsigned long long>() : (unsigned long long*)nullptr, lc_coarse);
@@ -1195,6 +1216,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
     for (int i = 0; i < kPairSlots; ++i) pairs += (int64_t)h.pairs[i * 16];
     for (int i = 0; i < kPairSlots; ++i) entries += (int64_t)h.entries[i * 16];
     if (from_inputs && entries != pairs) h.flags |= FLAG_DUP;  // two rows wrote one entry
+    if (h.flags & FLAG_SORT) return kRetryGeneralSort;
     SPC_TRY(flags_status(h));
     km->n_pairs = pairs;
   }
@@ -1223,6 +1245,7 @@ int kmap_build(const int32_t* coords, int64_t N, int K, int stride, int transpos
   *out = km.release();
   return SPCONV_OK;
 }
+}  // namespace
 
 int kmap_build_in_side(spconv_kmap* km, hipStream_t st) {
   if (km->in_side.ready) return SPCONV_OK;

@@ -167,11 +167,12 @@ __device__ __forceinline__ unsigned mask_key(const MaskKeys& mk, const int* slab
 
 __global__ void __launch_bounds__(64) k_msort_clear(unsigned* __restrict__ sync) { sync[threadIdx.x] = 0; }
 
-template <bool FIRST, bool LAST>
+// KEYS: a plain sort of 32-bit keys (no rows travel with them; every digit writes the keys).
+template <bool FIRST, bool LAST, bool KEYS = false>
 __global__ void __launch_bounds__(kSortThreads)
     k_msort_pass(MaskKeys mk, const unsigned* __restrict__ kin, const int* __restrict__ vin,
                  unsigned* __restrict__ kout, int* __restrict__ vout, int rows, int shift, int bits,
-                 unsigned* hist, unsigned* arrive, unsigned* error) {
+                 unsigned* hist, unsigned* arrive, unsigned* error, unsigned error_bit) {
   __shared__ unsigned off[kSortWaves][kSortMaxBins];  // wave counts, then the waves' running places within the workgroup
   __shared__ unsigned first[kSortMaxBins];   // the workgroup's first place per digit value
   __shared__ unsigned part[2][kSortThreads][4];       // partial sums of the matrix rows: [before | total][thread][digit of quad]
@@ -193,7 +194,7 @@ __global__ void __launch_bounds__(kSortThreads)
     vreg[s] = i;
     if (i < rows) {
       kreg[s] = FIRST ? mask_key(mk, slab, i) : kin[i];
-      if (!FIRST) vreg[s] = vin[i];
+      if (!FIRST && !KEYS) vreg[s] = vin[i];
     }
   }
   __syncthreads();
@@ -247,7 +248,7 @@ __global__ void __launch_bounds__(kSortThreads)
     unsigned polls = 0;
     while (__hip_atomic_load(arrive, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) < gridDim.x) {
       if (++polls > kSortSpinLimit) {
-        atomicOr(error, 1u);
+        atomicOr(error, error_bit);
         break;
       }
       __builtin_amdgcn_s_sleep(2);
@@ -326,8 +327,8 @@ __global__ void __launch_bounds__(kSortThreads)
     const unsigned key = kreg[s];
     const unsigned pos = first[(key >> shift) & (unsigned)(bins - 1)] + lpos[s];
     if (valid && pos < (unsigned)rows) {  // (always below rows when the counters are consistent)
-      vout[pos] = vreg[s];
-      if (!LAST) kout[pos] = key;
+      if (!KEYS) vout[pos] = vreg[s];
+      if (!LAST || KEYS) kout[pos] = key;
     }
   }
 }
@@ -622,6 +623,40 @@ __global__ void __launch_bounds__(256)
 
 }  // namespace
 
+// Sorts n 32-bit keys of key_bits significant bits with the one-launch-per-digit sort above (at
+// most kSortMaxWgs * kSortWg keys: SPCONV_EINVAL beyond, and the caller takes the general sort).
+// A wait that runs out sets error_bit in *error_word (device memory that the caller reads back
+// later): the keys are then not sorted and the caller must sort them again.
+int msort_keys_u32(uint32_t* key_a, uint32_t* key_b, int64_t n, int key_bits, unsigned* error_word, unsigned error_bit,
+                   hipStream_t st, int* in_b) {
+  *in_b = 0;
+  if (n <= 1 || key_bits <= 0) return SPCONV_OK;
+  const int n_wg = (int)ceil_div(n, kSortWg);
+  if (n_wg > kSortMaxWgs || key_bits > 32) return SPCONV_EINVAL;
+  DevBuf hist;
+  const size_t hist_elems = (size_t)n_wg * kSortMaxBins;
+  const int passes = (key_bits + kSortMaxBits - 1) / kSortMaxBits;
+  const int bits = (key_bits + passes - 1) / passes;
+  SPC_TRY(hist.alloc((kSortSyncWords + (size_t)passes * hist_elems) * sizeof(uint32_t)));
+  unsigned* sync = hist.as<unsigned>();
+  hipLaunchKernelGGL(k_msort_clear, dim3(1), dim3(kSortSyncWords), 0, st, sync);
+  SPC_LAUNCH_CHECK();
+  const MaskKeys none{};
+  int shift = 0;
+  for (int p = 0; p < passes; ++p) {  // (passes <= 4: arrival counters at sync[16 p], p < 4)
+    const int b = shift + bits <= key_bits ? bits : key_bits - shift;
+    const unsigned* kin = *in_b ? key_b : key_a;
+    unsigned* kout = *in_b ? key_a : key_b;
+    hipLaunchKernelGGL((k_msort_pass<false, false, true>), dim3((unsigned)n_wg), dim3(kSortThreads), 0, st, none, kin,
+                       (const int*)nullptr, kout, (int*)nullptr, (int)n, shift, b,
+                       sync + kSortSyncWords + (size_t)p * hist_elems, sync + 16 * p, error_word, error_bit);
+    SPC_LAUNCH_CHECK();
+    *in_b ^= 1;
+    shift += b;
+  }
+  return SPCONV_OK;
+}
+
 int plan_shape(int V, int64_t rows, int n_split, int tile_m, PlanShape* s) {
   // every part needs at least one offset (a K = 1 map has a single one): the kernels index the
   // last column of a part's map
@@ -727,24 +762,24 @@ int plan_get(spconv_kmap* km, SideMap& side, int n_split, int tile_m, hipStream_
           SPC_LAUNCH_CHECK();
           if (passes == 1) {
             hipLaunchKernelGGL((k_msort_pass<true, true>), grid, block, 0, st, mk, (const unsigned*)nullptr,
-                               (const int*)nullptr, (unsigned*)nullptr, vb, rows_i, 0, bits, h[0], sync, err);
+                               (const int*)nullptr, (unsigned*)nullptr, vb, rows_i, 0, bits, h[0], sync, err, 1u);
             sorted_rows = vb;
           } else if (passes == 2) {
             hipLaunchKernelGGL((k_msort_pass<true, false>), grid, block, 0, st, mk, (const unsigned*)nullptr,
-                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err);
+                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err, 1u);
             SPC_LAUNCH_CHECK();
             hipLaunchKernelGGL((k_msort_pass<false, true>), grid, block, 0, st, mk, (const unsigned*)kb,
-                               (const int*)vb, (unsigned*)nullptr, va, rows_i, bits, b_last, h[1], sync + 16, err);
+                               (const int*)vb, (unsigned*)nullptr, va, rows_i, bits, b_last, h[1], sync + 16, err, 1u);
             sorted_rows = va;
           } else {
             hipLaunchKernelGGL((k_msort_pass<true, false>), grid, block, 0, st, mk, (const unsigned*)nullptr,
-                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err);
+                               (const int*)nullptr, kb, vb, rows_i, 0, bits, h[0], sync, err, 1u);
             SPC_LAUNCH_CHECK();
             hipLaunchKernelGGL((k_msort_pass<false, false>), grid, block, 0, st, mk, (const unsigned*)kb,
-                               (const int*)vb, ka, va, rows_i, bits, bits, h[1], sync + 16, err);
+                               (const int*)vb, ka, va, rows_i, bits, bits, h[1], sync + 16, err, 1u);
             SPC_LAUNCH_CHECK();
             hipLaunchKernelGGL((k_msort_pass<false, true>), grid, block, 0, st, mk, (const unsigned*)ka,
-                               (const int*)va, (unsigned*)nullptr, vb, rows_i, 2 * bits, b_last, h[2], sync + 32, err);
+                               (const int*)va, (unsigned*)nullptr, vb, rows_i, 2 * bits, b_last, h[2], sync + 32, err, 1u);
             sorted_rows = vb;
           }
           SPC_LAUNCH_CHECK();

@@ -84,6 +84,36 @@ def test_forward_design_space(sp, cloud, n_split, kernel, tile_m, tile_n):
     np.testing.assert_array_equal(km.export().cpu().numpy(), ref.M)
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("c_in,c_out", [(128, 128), (64, 192), (256, 64), (128, 72)])
+def test_tiles_of_256_rows_by_128_columns(sp, cloud, dtype, c_in, c_out):
+    """The largest tile of the tiled kernel with 64-channel reduction chunks: all split counts (sorted
+    and unsorted maps), a column tile that is partly or wholly past the last channel, forward and
+    input gradient (whose reduction then runs over c_out)."""
+    c, ref = cloud
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, c_in, c_out, 27, dtype, 21)
+    km = sp.build_kmap(coords_dev(c), 3, 1)
+    want_f, want_d = oc.forward(x32, w32, ref.M), oc.dgrad(g32, w32, ref.M, ref.n_in)
+    for n_split in range(5):
+        cfg = _cfg(sp, n_split, 256, 128, kernel=2)
+        assert norm_err(sp.fwd(x, w, km, cfg), want_f) <= TOL[dtype], n_split
+        assert norm_err(sp.dgrad(g, w, km, cfg), want_d) <= TOL[dtype], n_split
+
+
+@pytest.mark.parametrize("stride,transposed", [(2, False), (2, True)])
+def test_tiles_of_256_rows_on_strided_and_transposed_maps(sp, stride, transposed):
+    """The same tile on maps whose two sides differ: the strided map and its transpose, which reads
+    the weights mirrored."""
+    c = gen.lidar_scene(79, target_n=2600)
+    ref = oc.build_kmap(c, 3, stride, transposed)
+    (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 128, 27, "f16", 22)
+    km = sp.build_kmap(coords_dev(c), 3, stride, transposed)
+    for n_split in (0, 1, 3):
+        cfg = _cfg(sp, n_split, 256, 128, kernel=2)
+        assert norm_err(sp.fwd(x, w, km, cfg), oc.forward(x32, w32, ref.M)) <= TOL["f16"], n_split
+        assert norm_err(sp.dgrad(g, w, km, cfg), oc.dgrad(g32, w32, ref.M, ref.n_in)) <= TOL["f16"], n_split
+
+
 @pytest.mark.parametrize("tile_n", [32, 64, 128])
 def test_forward_tile_n(sp, cloud, tile_n):
     c, ref = cloud

@@ -15,10 +15,6 @@
 //     consume it;
 //   * offsets whose bit is clear in the block's mask are skipped: the lock-step
 //     unit of Section 2.2.3 is the 16-row block;
-//   * a wave issues in order, so the offset loop reads nothing from LDS where
-//     it needs it: the slab entry of an offset is read one step before its
-//     gathers are issued and the weight fragments of a slot one step before
-//     its MFMAs (instances whose registers allow a second fragment set);
 //   * the block's map rows are staged in a per-wave LDS slab (the hoisted
 //     addressing of Section 3.2), and output rows leave through the same slab
 //     as whole 16-byte segments.
@@ -198,43 +194,16 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
   uint4 fr[DEPTH][KS];
   int cc[DEPTH];
   unsigned m = 0;
-  // A wave issues in order, so every LDS read that sits between two of its instructions costs it
-  // a round trip through the LDS queue of sixteen waves.  The offset loop therefore reads nothing
-  // where it needs it: the slab entry of an offset is read one step before that offset's gathers
-  // are issued (pop), and the weight fragments of a slot one step before its MFMAs (fetch_b).
-  // (Only where the second set of weight fragments fits into the 128 registers of a 16-wave
-  // workgroup; the larger instances read both where they use them.)
-  constexpr bool AHEAD = KS <= 2 && KS * NB <= 4;
-  // "No offset left" is the offset number `width`: the mask carries a bit there that is never
-  // cleared, so that taking the next offset is find-first-set without a test for an empty mask.
-  // Reading at that index is harmless: in the slab it is the first entry of the next row (of the
-  // staging area after the last row), in the weights the 4 KB behind the last slice, which the
-  // slabs occupy (the host checks that they are at least a slice long); neither value is used.
-  const int c_end = width;
-  const unsigned m_end = 1u << width;  // (width <= 27)
-  int c_n = c_end;       // the offset that the next issue() gathers
-  unsigned slab_n = 0;   // and this lane's slab entry for it (byte offset of the row; kAbsent: no neighbour)
-  auto pop = [&]() {
-    c_n = __builtin_ctz(m);
-    m = (m & (m - 1u)) | m_end;
-    slab_n = *reinterpret_cast<const unsigned*>(slab + lane_map + (unsigned)c_n * 4u);
-  };
   // Always issues KS loads: with no offset left they are out-of-range loads (zeros, no traffic).
+  // The slab holds byte offsets of the gathered rows (kAbsent for a missing neighbour).
   auto issue = [&](int s) {
-    if constexpr (!AHEAD) pop();
-    cc[s] = c_n;
-    const unsigned rowb = c_n == c_end ? kAbsent : slab_n;
+    const int c = m ? __ffs((int)m) - 1 : -1;
+    m &= m - 1;  // 0 stays 0
+    cc[s] = c;
+    unsigned rowb = kAbsent;
+    if (c >= 0) rowb = *reinterpret_cast<const unsigned*>(slab + lane_map + (unsigned)c * 4u);
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) fr[s][ks] = buf_load16(x_rsrc, rowb + lane_col[ks]);
-  };
-  uint4 bf[AHEAD ? 2 : 1][KS][NB];  // weight fragments of the slot being multiplied and of the one after it, alternating
-  auto fetch_b = [&](int buf, int c) {
-    const unsigned char* wk = smem + (unsigned)c * (unsigned)(BN * ROW_HALFS * 2);
-#pragma unroll
-    for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-      for (int nb = 0; nb < NB; ++nb)
-        bf[buf][ks][nb] = *reinterpret_cast<const uint4*>(wk + lane_b[ks] + nb * (16 * ROW_HALFS * 2));
   };
   // Publishes the prefetched block in the wave's slab, takes the ticket of the block after it and
   // starts that block's prefetch, then puts the first DEPTH offsets in flight.
@@ -252,21 +221,14 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       bm |= __shfl_xor(bm, 4);
       bm |= __shfl_xor(bm, 8);
     }
-    m = __builtin_amdgcn_readfirstlane(bm) | m_end;
+    m = __builtin_amdgcn_readfirstlane(bm);
     unsigned t = 0;
     if (lane == 0) t = atomicAdd(&next_ticket, 1u);
     t_next = (int)__builtin_amdgcn_readfirstlane(t);
     prefetch_block(block_of(t_next < nj ? t_next : nj - 1));
     __builtin_amdgcn_wave_barrier();
 #pragma unroll
-    for (int s = 0; s < DEPTH; ++s) {
-      if constexpr (AHEAD) pop();
-      issue(s);
-    }
-    if constexpr (AHEAD) {
-      pop();
-      fetch_b(0, cc[0]);
-    }
+    for (int s = 0; s < DEPTH; ++s) issue(s);
   };
 
   // the first block's map rows travel while the weights are being staged
@@ -355,59 +317,23 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
 #pragma unroll
     for (int nb = 0; nb < NB; ++nb) acc[nb] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    // slot s: its permutes go first (they wait for the slot's gathers), then the reads of the
-    // next slot's weights, then the MFMAs, which wait for the permutes only
-    auto consume = [&](int s, int nxt) {
-      if constexpr (!AHEAD) {
-        const unsigned char* wk = smem + (unsigned)cc[s] * (unsigned)(BN * ROW_HALFS * 2);
-#pragma unroll
-        for (int ks = 0; ks < KS; ++ks) {
-          uint4 a = fr[s][ks];
-          if constexpr (QUAD) {
-            a.x = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].x);
-            a.y = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].y);
-            a.z = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].z);
-            a.w = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].w);
-          }
-#pragma unroll
-          for (int nb = 0; nb < NB; ++nb) {
-            const uint4 b = *reinterpret_cast<const uint4*>(wk + lane_b[ks] + nb * (16 * ROW_HALFS * 2));
-            acc[nb] = MfmaW<T>::run(a, b, acc[nb]);
-          }
-        }
-        return;
-      }
-      uint4 af[KS];
+    auto consume = [&](int s) {
+      const unsigned char* wk = smem + (unsigned)cc[s] * (unsigned)(BN * ROW_HALFS * 2);
 #pragma unroll
       for (int ks = 0; ks < KS; ++ks) {
-        af[ks] = fr[s][ks];
+        uint4 af = fr[s][ks];
         if constexpr (QUAD) {  // gather layout -> MFMA A-fragment layout
-          af[ks].x = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].x);
-          af[ks].y = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].y);
-          af[ks].z = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].z);
-          af[ks].w = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].w);
+          af.x = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].x);
+          af.y = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].y);
+          af.z = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].z);
+          af.w = (unsigned)__builtin_amdgcn_ds_bpermute(frag_src, (int)fr[s][ks].w);
+        }
+#pragma unroll
+        for (int nb = 0; nb < NB; ++nb) {
+          const uint4 bf = *reinterpret_cast<const uint4*>(wk + lane_b[ks] + nb * (16 * ROW_HALFS * 2));
+          acc[nb] = MfmaW<T>::run(af, bf, acc[nb]);
         }
       }
-      if constexpr (QUAD) __builtin_amdgcn_sched_barrier(0);  // (permutes first: the wait below counts on it)
-      fetch_b((s + 1) & 1, cc[nxt]);
-      // (the instruction scheduler would otherwise sink these reads between the MFMAs and hoist the
-      // address arithmetic of the next gathers above them, and every wait in between would become a
-      // wait for the newest LDS operation)
-      __builtin_amdgcn_sched_barrier(0);
-      // One wait for the whole slot instead of one per MFMA (a hint only: the compiler still adds
-      // whatever wait it finds missing): this slot's gathers are the oldest KS of KS * DEPTH loads,
-      // and of the LDS operations only the KS * NB reads just issued (and, without the permutes,
-      // the slab read before them) may stay outstanding.
-      {
-        constexpr int vm = KS * (DEPTH - 1), lg = KS * NB + (QUAD ? 0 : 1);
-        static_assert(!AHEAD || (vm < 64 && lg < 16), "wait counts fit their fields");
-        __builtin_amdgcn_s_waitcnt((vm & 15) | ((vm >> 4) << 14) | (7 << 4) | (lg << 8));
-      }
-#pragma unroll
-      for (int ks = 0; ks < KS; ++ks)
-#pragma unroll
-        for (int nb = 0; nb < NB; ++nb) acc[nb] = MfmaW<T>::run(af[ks], bf[AHEAD ? (s & 1) : 0][ks][nb], acc[nb]);
-      __builtin_amdgcn_sched_barrier(0);
     };
 
     // The exits leave the loop directly (not through its latch), so that the wait-count
@@ -417,13 +343,9 @@ __global__ void __launch_bounds__(DEPTH > 4 ? 512 : 1024) k_igemm_wave(const Wav
       for (int rep = 0; rep < kLoopUnroll; ++rep) {
 #pragma unroll
         for (int s = 0; s < DEPTH; ++s) {
-          if (cc[s] == c_end) goto offsets_done;
-          consume(s, (s + 1) % DEPTH);
+          if (cc[s] < 0) goto offsets_done;
+          consume(s);
           issue(s);
-          if constexpr (AHEAD) {
-            __builtin_amdgcn_sched_barrier(0);
-            pop();
-          }
         }
       }
     }
@@ -517,9 +439,7 @@ int launch_wave_ks(int ks, int nb, const WaveParams& p, dim3 grid, int threads, 
 
 constexpr size_t kLdsBudget = 160 * 1024 - 64;  // (64 bytes for the static ticket counter)
 
-// (one entry more than the 16 rows hold: the offset loop's "no offset left" index reads the entry
-// behind the last row)
-size_t map_bytes_for(int max_width) { return (size_t)round_up((int64_t)16 * max_width * 4 + 4, 16); }
+size_t map_bytes_for(int max_width) { return (size_t)round_up((int64_t)16 * max_width * 4, 16); }
 
 size_t slab_bytes_for(int max_width, int bn, int parts) {
   return map_bytes_for(max_width) + (parts == 1 ? (size_t)16 * bn * 2 : 0);
@@ -544,7 +464,7 @@ int igemm_wave_pick_bn(int V, int n_split, int c_red, int c_out, int tile_n, int
     const size_t w = (size_t)max_width * bn * ks * 64;
     const size_t slab = slab_bytes_for(max_width, bn, parts);
     for (int waves : {16, 8}) {
-      if (w + std::max((size_t)waves * slab, (size_t)bn * ks * 64) <= kLdsBudget) {
+      if (w + (size_t)waves * slab <= kLdsBudget) {
         if (waves_out) *waves_out = waves;
         return bn;
       }
@@ -575,10 +495,7 @@ int igemm_wave_shape(int V, int n_split, int64_t rows, int64_t rows_src, int c_r
   if ((uint64_t)ps.rows_pad * s->max_width * 4 >= 0xFFFF0000ull) return SPCONV_EINVAL;
   s->slab_bytes = (int)slab_bytes_for(s->max_width, s->bn, ps.parts);
   s->map_bytes = (int)map_bytes_for(s->max_width);
-  // (the slabs stand in for the weight slice behind the last one, which the offset loop's "no
-  // offset left" index reads: at least a slice of LDS follows the weights)
-  const size_t slice = (size_t)s->bn * s->ks * 64;
-  s->lds_bytes = (size_t)s->max_width * slice + std::max((size_t)waves * s->slab_bytes, slice);
+  s->lds_bytes = (size_t)s->max_width * s->bn * s->ks * 64 + (size_t)waves * s->slab_bytes;
   if (s->lds_bytes > kLdsBudget) return SPCONV_EINVAL;
   const int n_tiles_n = (int)ceil_div(c_out, s->bn);
   // persistent workgroups: about one per CU over all (n-tile, part) slices, each wave gets >= 1 block

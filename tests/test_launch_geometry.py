@@ -48,13 +48,9 @@ def _check_kernel1(info, V, rows, c_red, c_cols, n_split):
     max_width = max(info.width[:info.parts])
     assert sum(info.width[:info.parts]) == V and info.lo[0] == 0
     # LDS: resident weights of the widest part + one slab per wave (map rows, then the output tile)
-    # (the offset loop's "no offset left" index reads the slab entry behind the last row and the
-    # weight slice behind the last one: both must be allocated)
-    slice_bytes = info.tile_n * info.k_steps * 64
-    assert info.slab_map_bytes >= 16 * max_width * 4 + 4
+    assert info.slab_map_bytes >= 16 * max_width * 4
     assert info.slab_bytes >= info.slab_map_bytes + (16 * info.tile_n * 2 if info.parts == 1 else 0)
-    assert info.lds_bytes == max_width * slice_bytes + max(info.waves * info.slab_bytes, slice_bytes)
-    assert (max_width + 1) * slice_bytes <= info.lds_bytes
+    assert info.lds_bytes == max_width * info.tile_n * info.k_steps * 64 + info.waves * info.slab_bytes
     assert info.lds_bytes + 64 <= LDS_PER_CU
     assert info.n_tiles == -(-rows // 16) and info.rows_pad % 256 == 0 and info.rows_pad >= rows
     gx = info.grid[0]

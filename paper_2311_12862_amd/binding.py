@@ -2,6 +2,11 @@
 
 torch is used for device memory and the current HIP stream; every step of the
 computation runs inside libspconv.so.
+
+Stream ordering: every call enqueues its work on `stream` (default: torch's
+current stream) and returns without waiting.  A tensor that a call returns or
+fills is therefore ordered on that stream only: read it on the same stream, or
+synchronise that stream first (`tensor.cpu()` runs on torch's current stream).
 """
 from __future__ import annotations
 

@@ -539,3 +539,44 @@ def test_k5_sort_order_per_plane(sp, cloud5):
         key = np.array([(int(m) >> (25 * g)) & ((1 << 25) - 1) for m in big], np.int64)
         _check_order(km.export_perm(sp.OP_FWD, cfg, g).cpu().numpy(), key, ref.n_out)
     km.destroy()
+
+
+def test_steps_alternating_between_three_streams(sp):
+    """The launch pattern that bench.py times: asynchronous kmap build, forward, dgrad and wgrad of one
+    batch on one stream, the next batch on the next stream, no synchronisation in between, every
+    stream with kmaps and outputs of its own.  Each stream gets a cloud, features and weights of its
+    own here, so that anything taken from a neighbouring stream shows; all results against the oracle."""
+    lanes = []
+    for i, ts in enumerate([torch.cuda.current_stream(), torch.cuda.Stream(), torch.cuda.Stream()]):
+        c = gen.lidar_scene(300 + i, target_n=2600 + 700 * i)
+        ref = oc.build_kmap(c, 3, 1)
+        (x32, x), (w32, w), (g32, g) = make_layer(ref.n_in, ref.n_out, 64, 64, 27, "f16", 40 + i)
+        lanes.append(dict(ts=ts, s=ts.cuda_stream, coords=coords_dev(c), ref=ref, x=x, w=w, g=g,
+                          want=(oc.forward(x32, w32, ref.M), oc.dgrad(g32, w32, ref.M, ref.n_in),
+                                oc.wgrad(x32, g32, ref.M)),
+                          y=torch.empty(ref.n_out, 64, dtype=torch.float16, device="cuda"),
+                          dx=torch.empty(ref.n_in, 64, dtype=torch.float16, device="cuda"),
+                          dw=torch.empty(27, 64, 64, dtype=torch.float32, device="cuda"), prev=[]))
+    torch.cuda.synchronize()  # (the inputs were made on the current stream)
+    cfg = _cfg(sp, 0, 0, 32, kernel=1)
+    for step in range(12):
+        ln = lanes[step % 3]
+        k = sp.build_kmap(ln["coords"], 3, 1, stream=ln["s"], asynchronous=True)
+        sp.fwd(ln["x"], ln["w"], k, cfg, out=ln["y"], stream=ln["s"])
+        sp.dgrad(ln["g"], ln["w"], k, cfg, out=ln["dx"], stream=ln["s"])
+        sp.wgrad(ln["x"], ln["g"], k, out=ln["dw"], stream=ln["s"])
+        if ln["prev"]:
+            old = ln["prev"].pop()
+            old.status(stream=ln["s"])  # (raises on a build error)
+            old.destroy()
+        ln["prev"].append(k)
+    torch.cuda.synchronize()
+    for ln in lanes:
+        k = ln["prev"].pop()
+        k.status(stream=ln["s"])
+        m = k.export(stream=ln["s"])
+        ln["ts"].synchronize()  # (the copy runs on the lane's stream, .cpu() on the current one)
+        np.testing.assert_array_equal(m.cpu().numpy(), ln["ref"].M)
+        k.destroy()
+        for got, want in zip((ln["y"], ln["dx"], ln["dw"]), ln["want"]):
+            assert norm_err(got, want) <= TOL["f16"]

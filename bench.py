@@ -292,13 +292,16 @@ def main():
         return ms
 
     cur = torch.cuda.current_stream()
-    ms_one_stream = timed_loop([make_lane(cur)])
+    lanes = [make_lane(cur)]
+    ms_one_stream = timed_loop(lanes)
     if args.streams > 1:
         lanes = [make_lane(cur)] + [make_lane(torch.cuda.Stream()) for _ in range(args.streams - 1)]
         ms_per_step = timed_loop(lanes)
-        del lanes
     else:
         ms_per_step = ms_one_stream
+    # what the timed steps left in their output buffers is compared with the oracle further down
+    timed_outputs = [(lane["y"], lane["dx"], lane["dw"]) for lane in lanes]
+    del lanes
 
     flops_one = 2.0 * pairs * C_IN * C_OUT          # valid MACs of one of fwd / dgrad / wgrad
     value = 3.0 * flops_one / (ms_per_step * 1e-3) / 1e12
@@ -451,10 +454,18 @@ def main():
         ref = oc.build_kmap(coords_h, 3, 1)
         t_map = time.perf_counter() - t
         t = time.perf_counter()
-        oc.forward(x32, w32, ref.M)
-        oc.dgrad(g32, w32, ref.M, ref.n_in)
-        oc.wgrad(x32, g32, ref.M)
+        want = (oc.forward(x32, w32, ref.M), oc.dgrad(g32, w32, ref.M, ref.n_in), oc.wgrad(x32, g32, ref.M))
         t_feat = time.perf_counter() - t
+        # the outputs of the timed loop itself (every stream's last step) against the oracle:
+        # largest deviation over the largest reference magnitude, as in the parity tests
+        errs = [0.0, 0.0, 0.0]
+        for outs in timed_outputs:
+            for i, (got, ref_i) in enumerate(zip(outs, want)):
+                gh = got.to(torch.float64).cpu().numpy()
+                errs[i] = max(errs[i], float(np.abs(gh - ref_i).max() / np.abs(ref_i).max()))
+        out["timed_outputs_vs_oracle"] = {"fwd": float("%.3g" % errs[0]), "dgrad": float("%.3g" % errs[1]),
+                                          "wgrad": float("%.3g" % errs[2]), "streams_checked": len(timed_outputs),
+                                          "tolerance": 2e-2, "ok": bool(max(errs) <= 2e-2)}
         out["cpu_baseline"] = {"value": round(3.0 * flops_one / (t_map + t_feat) / 1e12, 6), "unit": "TFLOP/s",
                                "cores": int(cores), "kind": "oracle",
                                "sample": "the full workload once: dict kmap build %.2f s (one Python thread) + "
